@@ -1,0 +1,190 @@
+"""CPU oracle for the Cartridge hot path -- TEST INFRASTRUCTURE, NOT THE PRODUCT.
+
+Plain numpy, fp64 everywhere, full score rows materialised, no tiling, no
+online softmax, no code shared with the HIP library.  Only tests, the smoke
+check and the benchmark's cpu_baseline leg may import this module; the product
+path never routes through it.
+
+What each function follows (arxiv 2506.06266):
+
+* attn_fwd / attn_bwd -- Eq. 1 (Sec. 2.3, causal softmax attention) evaluated
+  over the cache ordering of Sec. 3.2 ("Cartridge KV cache": the p trainable
+  pairs (z_k, z_v) first, then the sequence's own pairs).  Every query sees all
+  p prefix slots; the own part is causal, j <= i, as Eq. 1's sum over j = 1..i.
+  The backward pass is the analytic gradient of that definition; Sec. 3.2
+  trains Z by back-propagating into the key and value vectors with the model
+  frozen, so dZ sums every query of every sequence in the batch.
+* distill_kl -- Eq. 3 (Sec. 4.2), the KL divergence from the teacher's to the
+  student's next-token distribution, restricted to the teacher entries that
+  were recorded (App. A.2 "Training Objective": top output probabilities are
+  collected at data-generation time).
+* decode -- Sec. 2.3 (decode: one new query over the whole cache) with the
+  cache of Sec. 3.3 (a cartridge is served as a cached prefix of length p).
+
+Readings where the paper is silent (listed in the design notes as well):
+scale is 1/sqrt(head_dim) per head unless given; query head h reads KV head
+h // (Hq // Hkv); teacher entries with a negative index are ignored.
+
+Parity pins: every function here is pinned by tests/test_oracle_*.py against
+closed forms, textbook special cases written independently in the tests,
+brute-force loops on tiny inputs and central finite differences.
+"""
+from __future__ import annotations
+
+import math
+from typing import Optional, Tuple
+
+import numpy as np
+
+__all__ = ["attn_fwd", "attn_bwd", "distill_kl", "decode"]
+
+
+def _f64(x) -> np.ndarray:
+    return np.asarray(x, dtype=np.float64)
+
+
+def _visible(S: int, p: int) -> np.ndarray:
+    """[S, p+S] boolean: column j of the concatenated cache is visible to query row i.
+
+    Prefix columns (j < p) are always visible; own column p + t is visible iff t <= i
+    (Sec. 3.2 cache ordering, Eq. 1 causal sum)."""
+    vis = np.ones((S, p + S), dtype=bool)
+    own = np.tril(np.ones((S, S), dtype=bool))
+    vis[:, p:] = own
+    return vis
+
+
+def _probs(q_bh: np.ndarray, keys: np.ndarray, vis: np.ndarray, scale: float):
+    """Softmax weights of Eq. 1 for one (sequence, query head): returns (P [S, p+S], lse [S])."""
+    s = scale * (q_bh @ keys.T)
+    s = np.where(vis, s, -np.inf)
+    m = s.max(axis=1, keepdims=True)
+    e = np.exp(s - m)
+    l = e.sum(axis=1, keepdims=True)
+    return e / l, (m + np.log(l))[:, 0]
+
+
+def attn_fwd(q, k_own, v_own, z_k, z_v, scale: Optional[float] = None) -> Tuple[np.ndarray, np.ndarray]:
+    """Cartridge attention forward.
+
+    q [B,S,Hq,d]; k_own, v_own [B,S,Hkv,d]; z_k, z_v [Hkv,p,d] (p may be 0).
+    Returns o [B,S,Hq,d] and lse [B,Hq,S] (log of the softmax denominator of each row)."""
+    q, k_own, v_own, z_k, z_v = map(_f64, (q, k_own, v_own, z_k, z_v))
+    B, S, Hq, d = q.shape
+    Hkv, p = z_k.shape[0], z_k.shape[1]
+    G = Hq // Hkv
+    assert Hq == G * Hkv and k_own.shape == (B, S, Hkv, d) and z_v.shape == (Hkv, p, d)
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    vis = _visible(S, p)
+    o = np.zeros((B, S, Hq, d))
+    lse = np.zeros((B, Hq, S))
+    for b in range(B):
+        for h in range(Hq):
+            hk = h // G
+            keys = np.concatenate([z_k[hk], k_own[b, :, hk]], axis=0)
+            vals = np.concatenate([z_v[hk], v_own[b, :, hk]], axis=0)
+            P, lse[b, h] = _probs(q[b, :, h], keys, vis, scale)
+            o[b, :, h] = P @ vals
+    return o, lse
+
+
+def attn_bwd(q, k_own, v_own, z_k, z_v, d_o, scale: Optional[float] = None):
+    """Gradient of sum(o * d_o) with respect to every input of attn_fwd.
+
+    Returns (d_q [B,S,Hq,d], d_k_own, d_v_own [B,S,Hkv,d], d_z_k, d_z_v [Hkv,p,d]).
+    With P the softmax weights, D_i = dO_i . O_i, dP = dO V^T, dS = P * (dP - D):
+    dQ = scale dS K, dK = scale dS^T Q, dV = P^T dO.  Key/value gradients sum over the
+    query heads of a group; for the prefix rows they also sum over the whole batch."""
+    q, k_own, v_own, z_k, z_v, d_o = map(_f64, (q, k_own, v_own, z_k, z_v, d_o))
+    B, S, Hq, d = q.shape
+    Hkv, p = z_k.shape[0], z_k.shape[1]
+    G = Hq // Hkv
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    vis = _visible(S, p)
+    d_q = np.zeros_like(q)
+    d_k_own = np.zeros_like(k_own)
+    d_v_own = np.zeros_like(v_own)
+    d_z_k = np.zeros_like(z_k)
+    d_z_v = np.zeros_like(z_v)
+    for b in range(B):
+        for h in range(Hq):
+            hk = h // G
+            keys = np.concatenate([z_k[hk], k_own[b, :, hk]], axis=0)
+            vals = np.concatenate([z_v[hk], v_own[b, :, hk]], axis=0)
+            P, _ = _probs(q[b, :, h], keys, vis, scale)
+            o = P @ vals
+            g = d_o[b, :, h]
+            D = (g * o).sum(axis=1, keepdims=True)
+            dP = g @ vals.T
+            dS = P * (dP - D)
+            d_q[b, :, h] = scale * (dS @ keys)
+            d_keys = scale * (dS.T @ q[b, :, h])
+            d_vals = P.T @ g
+            d_z_k[hk] += d_keys[:p]
+            d_z_v[hk] += d_vals[:p]
+            d_k_own[b, :, hk] += d_keys[p:]
+            d_v_own[b, :, hk] += d_vals[p:]
+    return d_q, d_k_own, d_v_own, d_z_k, d_z_v
+
+
+def distill_kl(logits, teacher_idx, teacher_logp, scale: float = 1.0):
+    """Context-distillation loss over recorded teacher entries and its gradient.
+
+    logits [N,V]; teacher_idx [N,k] integer (entries < 0 are ignored); teacher_logp [N,k].
+    Per row: t_j = exp(logp_j), log s = logits - logsumexp(logits),
+    KL_n = sum_j t_j (logp_j - log s[idx_j]);  loss = scale * sum_n KL_n.
+    d loss / d logits[n,v] = scale * (M_n s_nv - t_nv), M_n = sum_j t_j, t_nv = t_j at v = idx_j.
+    Returns (loss, d_logits [N,V], row_kl [N])."""
+    z = _f64(logits)
+    idx = np.asarray(teacher_idx, dtype=np.int64)
+    lp = _f64(teacher_logp)
+    N, V = z.shape
+    m = z.max(axis=1, keepdims=True)
+    lse = m + np.log(np.exp(z - m).sum(axis=1, keepdims=True))
+    log_s = z - lse
+    s = np.exp(log_s)
+    row_kl = np.zeros(N)
+    d_logits = np.zeros((N, V))
+    for n in range(N):
+        M = 0.0
+        for j in range(idx.shape[1]):
+            v = idx[n, j]
+            if v < 0:
+                continue
+            t = math.exp(lp[n, j])
+            row_kl[n] += t * (lp[n, j] - log_s[n, v])
+            d_logits[n, v] -= t
+            M += t
+        d_logits[n] += M * s[n]
+    return scale * row_kl.sum(), scale * d_logits, row_kl
+
+
+def decode(q, z_k, z_v, k_own, v_own, cu_lens, scale: Optional[float] = None):
+    """One query token per request over [shared cartridge ; the request's own KV].
+
+    q [B,Hq,d]; z_k, z_v [Hkv,p,d]; k_own, v_own [T,Hkv,d] ragged, request b owns rows
+    cu_lens[b] .. cu_lens[b+1]-1 (the current token's own key/value is the last of them), all
+    visible.  Returns o [B,Hq,d] and lse [B,Hq]."""
+    q, z_k, z_v, k_own, v_own = map(_f64, (q, z_k, z_v, k_own, v_own))
+    cu = np.asarray(cu_lens, dtype=np.int64)
+    B, Hq, d = q.shape
+    Hkv = z_k.shape[0]
+    G = Hq // Hkv
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    o = np.zeros((B, Hq, d))
+    lse = np.zeros((B, Hq))
+    for b in range(B):
+        for h in range(Hq):
+            hk = h // G
+            keys = np.concatenate([z_k[hk], k_own[cu[b]:cu[b + 1], hk]], axis=0)
+            vals = np.concatenate([z_v[hk], v_own[cu[b]:cu[b + 1], hk]], axis=0)
+            s = scale * (keys @ q[b, h])
+            m = s.max()
+            e = np.exp(s - m)
+            l = e.sum()
+            o[b, h] = (e / l) @ vals
+            lse[b, h] = m + math.log(l)
+    return o, lse
