@@ -1,0 +1,156 @@
+/*
+ * cartridge.h -- C ABI of the MI355X (gfx950) hot path of Cartridge / Self-Study training
+ * (arxiv 2506.06266).  C11; no HIP or PyTorch types appear here.
+ *
+ * Conventions shared by every entry point
+ *   - Every data pointer is a DEVICE pointer, 16-byte aligned, to a dense row-major tensor in the
+ *     layout stated at the entry point.  Descriptors are HOST structs passed by pointer.
+ *   - The caller owns every buffer, including the workspace; the library never allocates, frees
+ *     or synchronises.  All work is enqueued on `stream` (a hipStream_t passed as void*, NULL is
+ *     the default stream); outputs are valid once the caller has synchronised that stream.
+ *   - Arguments are validated on the host before anything is launched.  On any error the
+ *     matching status is returned and nothing is enqueued; nothing is thrown across the ABI.
+ *   - Data-shaped outputs (O, dQ, dK_own, dV_own, d_logits) have the input dtype, rounded from
+ *     fp32 to nearest-even; reductions that feed an optimiser or a merge (dZ, loss, LSE, row_kl)
+ *     are fp32.  All accumulation is fp32.
+ *   - Query head h reads KV head h / (Hq / Hkv).  Q and K arrive with positional encoding already
+ *     applied; Z_k is used as stored.
+ */
+#ifndef CARTRIDGE_H
+#define CARTRIDGE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    CART_OK = 0,
+    CART_ERR_NULL = 1,        /* a required pointer is NULL */
+    CART_ERR_SHAPE = 2,       /* a size is negative / zero where it may not be, or sizes disagree */
+    CART_ERR_UNSUPPORTED = 3, /* dtype / head_dim / mode not implemented */
+    CART_ERR_WORKSPACE = 4,   /* workspace NULL or smaller than the *_workspace() query */
+    CART_ERR_LAUNCH = 5,      /* the HIP runtime refused a launch */
+    CART_ERR_ALIGN = 6        /* a pointer is not 16-byte aligned */
+} cart_status;
+
+typedef enum { CART_F32 = 0, CART_BF16 = 1 } cart_dtype;
+
+/* Which kernels serve an attention call.  AUTO picks the MFMA kernels when the shape allows
+ * (bf16, head_dim 128) and the fp32 vector kernels otherwise. */
+typedef enum { CART_IMPL_AUTO = 0, CART_IMPL_VECTOR = 1, CART_IMPL_MFMA = 2 } cart_impl;
+
+/* One layer's cartridge attention problem (Sec. 3.2: trainable pairs first, then own pairs). */
+typedef struct {
+    int32_t B;              /* sequences in the batch, >= 1 */
+    int32_t S;              /* tokens per sequence, >= 1 */
+    int32_t Hq;             /* query heads */
+    int32_t Hkv;            /* key/value heads, divides Hq */
+    int32_t D;              /* head_dim: 1..256 (vector kernels), 128 (MFMA kernels) */
+    int32_t P;              /* prefix (cartridge) slots p, >= 0; 0 is plain causal attention */
+    cart_dtype dtype;       /* dtype of Q, K, V, Z, O, dO and of dQ, dK_own, dV_own */
+    float softmax_scale;    /* multiplies q.k; 0 selects 1/sqrt(D) */
+    int32_t n_frozen;       /* backward: dZ rows [0, n_frozen) are written as 0 (App. A.1, frozen
+                               attention-sink slot); 0 <= n_frozen <= P */
+    int32_t dz_accumulate;  /* backward: 0 overwrites d_z_k / d_z_v, 1 adds into them */
+    cart_impl impl;
+} cart_attn_desc;
+
+/* Context-distillation loss over N positions (Eq. 3, Sec. 4.2). */
+typedef struct {
+    int32_t N;              /* positions (rows), >= 1 */
+    int32_t V;              /* vocabulary size, >= 1 */
+    int32_t K;              /* recorded teacher entries per position, 1..V and <= 1024 */
+    cart_dtype logits_dtype;
+    float scale;            /* loss = scale * sum_n KL_n (1/N gives the mean) */
+} cart_kl_desc;
+
+/* Serve-time decode step over a shared cartridge (Sec. 3.3). */
+typedef struct {
+    int32_t B;                  /* requests, >= 1 */
+    int32_t Hq, Hkv, D, P;      /* as in cart_attn_desc */
+    int32_t total_own_tokens;   /* T = cu_lens[B] */
+    int32_t max_own_len;        /* upper bound on any request's own length (sizes the split) */
+    cart_dtype dtype;
+    float softmax_scale;        /* 0 selects 1/sqrt(D) */
+    cart_impl impl;
+} cart_decode_desc;
+
+/* Bytes of workspace each entry point needs for the given descriptor (0 on an invalid one). */
+size_t cart_attn_fwd_workspace(const cart_attn_desc *desc);
+size_t cart_attn_bwd_workspace(const cart_attn_desc *desc);
+size_t cart_kl_workspace(const cart_kl_desc *desc);
+size_t cart_decode_workspace(const cart_decode_desc *desc);
+
+/*
+ * cart_attn_fwd -- Eq. 1 (Sec. 2.3) over the cartridge cache of Sec. 3.2.
+ * For sequence b, query head h (KV head hk = h / (Hq/Hkv)) and token i, the keys are
+ * [ z_k[hk][0..P) ; k_own[b][0..i][hk] ] (every prefix slot visible, own tokens j <= i) and
+ *   o[b,i,h]   = sum_j softmax_j(scale * q[b,i,h] . key_j) value_j
+ *   lse[b,h,i] = log sum_j exp(scale * q[b,i,h] . key_j).
+ *   q      [B,S,Hq,D]   in      k_own, v_own [B,S,Hkv,D] in      z_k, z_v [Hkv,P,D] in
+ *   o      [B,S,Hq,D]   out     lse          [B,Hq,S] fp32 out
+ * z_k / z_v may be NULL when P == 0.  No output may alias an input.
+ */
+cart_status cart_attn_fwd(const cart_attn_desc *desc, const void *q, const void *k_own,
+                          const void *v_own, const void *z_k, const void *z_v, void *o,
+                          float *lse, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * cart_attn_bwd -- gradient of cart_attn_fwd (Sec. 3.2: the loss is back-propagated into the
+ * key and value vectors of Z with the model frozen).  Given d_o = dLoss/dO and the forward's o
+ * and lse:  P_ij = exp(s_ij - lse_i), D_i = d_o_i . o_i, dP_ij = d_o_i . value_j,
+ * dS_ij = P_ij (dP_ij - D_i);  dQ_i = scale sum_j dS_ij key_j;  dKey_j = scale sum_i dS_ij q_i;
+ * dValue_j = sum_i P_ij d_o_i, where sum_i runs over the rows and the Hq/Hkv query heads that
+ * see key j, and for prefix slots additionally over all B sequences.
+ *   d_q [B,S,Hq,D] out;  d_k_own, d_v_own [B,S,Hkv,D] out (input dtype)
+ *   d_z_k, d_z_v [Hkv,P,D] fp32 out (overwritten, or added into when dz_accumulate = 1; rows
+ *   below n_frozen are written as 0 / left untouched when accumulating).
+ * d_z_k / d_z_v / z_k / z_v may be NULL when P == 0.  Results are bit-reproducible run to run.
+ */
+cart_status cart_attn_bwd(const cart_attn_desc *desc, const void *q, const void *k_own,
+                          const void *v_own, const void *z_k, const void *z_v, const void *o,
+                          const float *lse, const void *d_o, void *d_q, void *d_k_own,
+                          void *d_v_own, float *d_z_k, float *d_z_v, void *workspace,
+                          size_t workspace_bytes, void *stream);
+
+/*
+ * cart_distill_kl_fwd_bwd -- Eq. 3 (Sec. 4.2) restricted to the teacher's recorded top entries
+ * (App. A.2 "Training Objective"), fused with its gradient.  Per position n, with
+ * t_j = exp(teacher_logp[n,j]), M_n = sum_j t_j and log s = log_softmax(logits[n,:]):
+ *   KL_n = sum_j t_j (teacher_logp[n,j] - log s[teacher_idx[n,j]])
+ *   loss = scale * sum_n KL_n
+ *   d_logits[n,v] = scale * (M_n s[v] - t_v),  t_v = t_j where v = teacher_idx[n,j], else 0.
+ *   logits [N,V] in;  teacher_idx [N,K] int32 in (distinct within a row, each < V; an entry < 0
+ *   is ignored);  teacher_logp [N,K] fp32 in
+ *   loss   [1] fp32 out (device);  d_logits [N,V] out, dtype of logits, MAY alias logits;
+ *   row_kl [N] fp32 out, may be NULL.
+ */
+cart_status cart_distill_kl_fwd_bwd(const cart_kl_desc *desc, const void *logits,
+                                    const int32_t *teacher_idx, const float *teacher_logp,
+                                    float *loss, void *d_logits, float *row_kl, void *workspace,
+                                    size_t workspace_bytes, void *stream);
+
+/*
+ * cart_decode -- Sec. 2.3 decode step with the cache of Sec. 3.3: one query token per request
+ * over [ z_k[hk][0..P) ; k_own[cu_lens[b] .. cu_lens[b+1])[hk] ], all visible (the current
+ * token's own key/value is the last own row; every request has at least one own row).  One
+ * cartridge is shared by all B requests.
+ *   q [B,Hq,D] in;  z_k, z_v [Hkv,P,D] in (NULL allowed when P == 0)
+ *   k_own, v_own [T,Hkv,D] in, ragged;  cu_lens [B+1] int32 in (device), cu_lens[0] = 0
+ *   o [B,Hq,D] out;  lse [B,Hq] fp32 out, may be NULL.
+ */
+cart_status cart_decode(const cart_decode_desc *desc, const void *q, const void *z_k,
+                        const void *z_v, const void *k_own, const void *v_own,
+                        const int32_t *cu_lens, void *o, float *lse, void *workspace,
+                        size_t workspace_bytes, void *stream);
+
+const char *cart_status_str(cart_status status);
+int cart_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CARTRIDGE_H */
