@@ -26,6 +26,9 @@ cart_status check_attn(const cart_attn_desc* d) {
 inline bool use_mfma(const cart_attn_desc& d) {
     return d.impl != CART_IMPL_VECTOR && cart::attn_mfma_supported(d);
 }
+inline bool use_mfma_bwd(const cart_attn_desc& d) {
+    return d.impl != CART_IMPL_VECTOR && cart::attn_mfma_bwd_supported(d);
+}
 inline float attn_scale(float s, int D) { return s > 0.f ? s : 1.0f / sqrtf(static_cast<float>(D)); }
 
 cart_status check_kl(const cart_kl_desc* d) {
@@ -70,7 +73,7 @@ size_t cart_attn_fwd_workspace(const cart_attn_desc* d) {
 size_t cart_attn_bwd_workspace(const cart_attn_desc* d) {
     if (check_attn(d) != CART_OK) return 0;
     size_t delta = round256(static_cast<size_t>(d->B) * d->Hq * d->S * sizeof(float));
-    return delta + (use_mfma(*d) ? cart::attn_mfma_bwd_workspace(*d) : 0);
+    return delta + (use_mfma_bwd(*d) ? cart::attn_mfma_bwd_workspace(*d) : 0);
 }
 
 size_t cart_kl_workspace(const cart_kl_desc* d) {
@@ -119,7 +122,7 @@ cart_status cart_attn_bwd(const cart_attn_desc* d, const void* q, const void* k_
     if (!workspace || workspace_bytes < need) return CART_ERR_WORKSPACE;
     const float scale = attn_scale(d->softmax_scale, d->D);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    int e = use_mfma(*d)
+    int e = use_mfma_bwd(*d)
                 ? cart::launch_attn_bwd_mfma(*d, scale, q, k_own, v_own, z_k, z_v, o, lse, d_o, d_q,
                                              d_k_own, d_v_own, d_z_k, d_z_v, workspace, st)
                 : cart::launch_attn_bwd_vector(*d, scale, q, k_own, v_own, z_k, z_v, o, lse, d_o,

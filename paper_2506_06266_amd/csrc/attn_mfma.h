@@ -1,0 +1,110 @@
+// Building blocks of the bf16 MFMA attention kernels (gfx950, head_dim 128).
+//
+// Matrix-core instruction used throughout: v_mfma_f32_32x32x16_bf16, D(32x32) += A(32x16) B(16x32).
+//   A: lane l holds row l%32,    k = 8*(l/32) + [0,8)      (8 bf16, 4 VGPRs)
+//   B: lane l holds column l%32, k = 8*(l/32) + [0,8)
+//   D: lane l holds column l%32, rows 8*(r/4) + 4*(l/32) + r%4 for r in [0,16)
+// Every product here is arranged so that the index kept per lane (a query, or a key) is the D
+// column and the contracted index of the NEXT product is the D row; the fp32 tile then turns
+// into the next product's 16-bit operand inside the lane, with no LDS round trip.  The D-row
+// order is a permutation of the contracted index; the other operand is fetched from LDS in the
+// same permuted order (see k_slot_row below), which a sum does not mind.
+#pragma once
+
+#include "cart_common.h"
+
+namespace cart {
+namespace mfma {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
+constexpr int HD = 128;           // head_dim
+constexpr int ROW_B = HD * 2;     // bytes per key/value/query row, in global memory and in LDS
+constexpr float NEG_BIG = -1.0e30f;
+constexpr float RESCALE_GAP = 8.0f;   // running max is moved only when exceeded by 2^8
+
+__device__ __forceinline__ f32x16 mma(bf16x8 a, bf16x8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// LDS tiles are [rows][128] bf16, 256 bytes per row, unpadded; the 16-byte chunk c of row r is
+// stored at chunk position c ^ swz(r).  swz is a bijection of r % 16 (16 consecutive rows read
+// at one logical chunk hit 16 distinct positions: row-wise ds_read_b128 is conflict-free) whose
+// bits 2..3 are r % 4 (4 consecutive rows x 4 consecutive chunks cover all 16 positions: the
+// transposing read is conflict-free too).
+__device__ __forceinline__ int swz(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
+
+// row-wise operand fragment: the 8 bf16 at columns [col, col+8) of one row (col % 8 == 0)
+__device__ __forceinline__ bf16x8 lds_frag_n(const char* tile, int row, int col) {
+    return *reinterpret_cast<const bf16x8*>(tile + row * ROW_B + (((col >> 3) ^ swz(row)) << 4));
+}
+
+// Transposed operand fragment for one 16-deep k-step of a [k][n] row-major tile: the lane that
+// owns operand row/column n gets the 8 k-values whose k-slots match the D-row order above:
+// slots e = 0..3 -> k = k0 + 4g + e, slots 4..7 -> k = k0 + 8 + 4g + (e-4), g = lane/32.
+// ds_read_b64_tr_b16: within each block of 16 lanes, lane i receives, for e = 0..3, element i%4 of
+// the 8 bytes addressed by lane 4e + i/4; so lane s of a block addresses row k + s/4, columns
+// n0 + 4*(s%4) .. +3, and lane i ends up with column n0 + i of rows k .. k+3.
+__device__ __forceinline__ bf16x8 lds_frag_t(const char* tile, int k0, int n0, int lane) {
+    const int blk = lane >> 4, s = lane & 15, g = lane >> 5;
+    const int row = k0 + 4 * g + (s >> 2);
+    const int col = n0 + 16 * (blk & 1) + 4 * (s & 3);
+    const int half = ((col >> 2) & 1) * 8;
+    typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (lds_ptr)(tile + row * ROW_B + (((col >> 3) ^ swz(row)) << 4) + half));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (lds_ptr)(tile + (row + 8) * ROW_B + (((col >> 3) ^ swz(row + 8)) << 4) + half));
+    s16x8 r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, r);
+}
+
+// D row held in register r of lane-group g (the k index the next product contracts over)
+__device__ __forceinline__ int d_row(int r, int g) { return 8 * (r >> 2) + 4 * g + (r & 3); }
+
+// value held by the lane 32 away
+__device__ __forceinline__ float partner(float x) {
+    uint32_t u = __float_as_uint(x);
+    auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return __uint_as_float((threadIdx.x & 32) ? r[0] : r[1]);
+}
+__device__ __forceinline__ float partner_max(float x) {
+    uint32_t u = __float_as_uint(x);
+    auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+// 8 fp32 D registers [r0, r0+8) -> one 16-bit operand fragment (same lane, same column)
+__device__ __forceinline__ bf16x8 pack_frag(const f32x16& s, int r0) {
+    u32x4 w = {pack_bf16x2(s[r0 + 0], s[r0 + 1]), pack_bf16x2(s[r0 + 2], s[r0 + 3]),
+               pack_bf16x2(s[r0 + 4], s[r0 + 5]), pack_bf16x2(s[r0 + 6], s[r0 + 7])};
+    return __builtin_bit_cast(bf16x8, w);
+}
+
+// Streams a ROWS x 128 bf16 tile from global memory straight into LDS (no register staging)
+// with the 4 wavefronts of a 256-thread workgroup.  One global_load_lds_dwordx4 moves 64 chunks
+// of 16 bytes = 4 tile rows; lane i's chunk lands at (wave-uniform base) + 16 i, so the lane
+// fetches the logical chunk that belongs at that position under the swizzle.  row_ptr(r) returns
+// the global address of tile row r (callers clamp rows past the end onto a valid row; such
+// rows are masked out of the softmax, so their contents never reach a result).
+template <int ROWS, typename RowPtr>
+__device__ __forceinline__ void tile_load_async(char* tile, RowPtr row_ptr) {
+    const int lane = threadIdx.x & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    constexpr int PER_WAVE = ROWS / 16;      // instructions per wavefront
+#pragma unroll
+    for (int i = 0; i < PER_WAVE; ++i) {
+        const int r0 = (PER_WAVE * wv + i) * 4;
+        const int r = r0 + (lane >> 4);
+        const char* src = row_ptr(r) + (((lane & 15) ^ swz(r)) << 4);
+        __builtin_amdgcn_global_load_lds(
+            (const __attribute__((address_space(1))) void*)src,
+            (__attribute__((address_space(3))) void*)(tile + r0 * ROW_B), 16, 0, 0);
+    }
+}
+
+}  // namespace mfma
+}  // namespace cart

@@ -78,7 +78,8 @@ int launch_decode_vector(const cart_decode_desc& d, float scale, const void* q, 
                          void* o, float* lse, hipStream_t st);
 
 // MFMA (bf16, head_dim 128) kernels
-bool attn_mfma_supported(const cart_attn_desc& d);
+bool attn_mfma_supported(const cart_attn_desc& d);       // forward
+bool attn_mfma_bwd_supported(const cart_attn_desc& d);
 size_t attn_mfma_fwd_workspace(const cart_attn_desc& d);
 size_t attn_mfma_bwd_workspace(const cart_attn_desc& d);   // beyond the delta array
 int launch_attn_fwd_mfma(const cart_attn_desc& d, float scale, const void* q, const void* k,
