@@ -1,0 +1,484 @@
+// Cartridge attention backward on the matrix cores (bf16 in, fp32 accumulate, head_dim 128):
+// the gradient of Eq. 1 over the cache of Sec. 3.2 with respect to Q, the own K/V and the
+// trainable prefix Z (Sec. 3.2 trains Z by back-propagation with the model frozen).
+//
+// Three kernels, each with one 64-wide operand block held stationary in registers per wavefront
+// and the other side streamed through LDS in tiles of 64 rows (sub-tiles of 32), in the same
+// software pipeline as the forward kernel; the probabilities are recomputed from the saved
+// log-sum-exp, so there is no running max and no rescale:
+//   dq kernel   (queries stationary): S^T = K Q^T, dP^T = V dO^T, dQ^T += K^T dS^T
+//   dk kernel   (keys stationary):    S = Q K^T,  dP = dO V^T,   dK^T += Q^T dS
+//   dv kernel   (keys stationary):    S = Q K^T,                 dV^T += dO^T P
+// with P = exp(scale S - lse), dS = P (dP - delta), delta_i = dO_i . O_i.  Nothing uses atomics:
+// a key-stationary workgroup owns its keys' gradients for one sequence; prefix-slot gradients
+// are written per sequence as fp32 partials and summed over the batch by dz_reduce_kernel in a
+// fixed order, so results are bit-reproducible.
+#include "attn_mfma.h"
+
+namespace cart {
+using namespace mfma;
+
+constexpr int BWD_TILE = 64;                      // rows per LDS tile
+constexpr int BWD_TILE_B = BWD_TILE * ROW_B;
+constexpr int BWD_NBUF = 3;
+constexpr int BWD_WG_ROWS = 256;                  // stationary rows per workgroup (4 x 64)
+
+// ---- delta = rowsum(dO * O), lse2 = lse * log2(e); 16 lanes per row, 8 elements per lane ----
+__global__ __launch_bounds__(256) void attn_bwd_prep_kernel(const bf16_t* __restrict__ o,
+                                                            const bf16_t* __restrict__ d_o,
+                                                            const float* __restrict__ lse,
+                                                            float* __restrict__ delta,
+                                                            float* __restrict__ lse2, int B, int S,
+                                                            int Hq) {
+    const long row = static_cast<long>(blockIdx.x) * 16 + (threadIdx.x >> 4);
+    const long rows = static_cast<long>(B) * S * Hq;
+    if (row >= rows) return;
+    const int sub = threadIdx.x & 15;
+    const u32x4 a = *reinterpret_cast<const u32x4*>(o + row * HD + sub * 8);
+    const u32x4 g = *reinterpret_cast<const u32x4*>(d_o + row * HD + sub * 8);
+    float s = 0.f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        s = fmaf(__uint_as_float(a[e] << 16), __uint_as_float(g[e] << 16), s);
+        s = fmaf(__uint_as_float(a[e] & 0xffff0000u), __uint_as_float(g[e] & 0xffff0000u), s);
+    }
+#pragma unroll
+    for (int off = 8; off > 0; off >>= 1) s += __shfl_xor(s, off, 16);
+    if (sub == 0) {
+        const int h = row % Hq, i = (row / Hq) % S, b = row / (static_cast<long>(Hq) * S);
+        const size_t st = (static_cast<size_t>(b) * Hq + h) * S + i;
+        delta[st] = s;
+        lse2[st] = lse[st] * CART_LOG2E;
+    }
+}
+
+// store a transposed accumulator block set: lane owns output row `row_ptr` (nullptr: skip),
+// register r of block db holds column 32 db + 8 (r/4) + 4 g + r%4
+__device__ __forceinline__ void store_rows_bf16(const f32x16 (&acc)[4], bf16_t* row_ptr, int lg, float mul) {
+    if (!row_ptr) return;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+            u32x2 w = {pack_bf16x2(acc[db][4 * r4] * mul, acc[db][4 * r4 + 1] * mul),
+                       pack_bf16x2(acc[db][4 * r4 + 2] * mul, acc[db][4 * r4 + 3] * mul)};
+            *reinterpret_cast<u32x2*>(row_ptr + 32 * db + 8 * r4 + 4 * lg) = w;
+        }
+}
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void store_rows_f32(const f32x16 (&acc)[4], float* row_ptr, int lg, float mul) {
+    if (!row_ptr) return;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+            f32x4 w = {acc[db][4 * r4] * mul, acc[db][4 * r4 + 1] * mul, acc[db][4 * r4 + 2] * mul,
+                       acc[db][4 * r4 + 3] * mul};
+            *reinterpret_cast<f32x4*>(row_ptr + 32 * db + 8 * r4 + 4 * lg) = w;
+        }
+}
+
+// =================================================================================================
+// dQ: queries stationary
+// =================================================================================================
+struct DqSmem {
+    char k[BWD_NBUF][BWD_TILE_B];
+    char v[BWD_NBUF][BWD_TILE_B];
+};
+
+__global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
+    const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
+    const bf16_t* __restrict__ zk, const bf16_t* __restrict__ zv, const bf16_t* __restrict__ d_o,
+    const float* __restrict__ lse2, const float* __restrict__ delta, bf16_t* __restrict__ dq, int B,
+    int S, int Hq, int Hkv, int P, float c, float scale) {
+    __shared__ DqSmem sm;
+    const int G = Hq / Hkv;
+    const int nQt = (S + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
+    int id = blockIdx.x;
+    const int hk = id % Hkv; id /= Hkv;
+    const int g_ = id % G; id /= G;
+    const int b = id % B; id /= B;
+    const int qt = nQt - 1 - id;
+    const int h = hk * G + g_;
+    const int lane = threadIdx.x & 63, lg = lane >> 5, lc = lane & 31;
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int q0 = qt * BWD_WG_ROWS, wrow0 = q0 + 64 * wv;
+
+    bf16x8 qf[2][8], gf[2][8];     // B operands: column = query, k = head element
+    float l2[2], dl[2];
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) {
+        int qi = wrow0 + 32 * cb + lc;
+        qi = qi < S ? qi : S - 1;
+        const size_t row = (static_cast<size_t>(b) * S + qi) * Hq + h;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            qf[cb][t] = *reinterpret_cast<const bf16x8*>(q + row * HD + 8 * lg + 16 * t);
+            gf[cb][t] = *reinterpret_cast<const bf16x8*>(d_o + row * HD + 8 * lg + 16 * t);
+        }
+        const size_t st = (static_cast<size_t>(b) * Hq + h) * S + qi;
+        l2[cb] = lse2[st];
+        dl[cb] = delta[st];
+    }
+
+    const int nPt = (P + BWD_TILE - 1) / BWD_TILE;
+    const int own_end = min(S, q0 + BWD_WG_ROWS);
+    const int nT = nPt + (own_end + BWD_TILE - 1) / BWD_TILE;
+    const char* zk_b = reinterpret_cast<const char*>(zk) + static_cast<size_t>(hk) * P * ROW_B;
+    const char* zv_b = reinterpret_cast<const char*>(zv) + static_cast<size_t>(hk) * P * ROW_B;
+    const size_t own_pitch = static_cast<size_t>(Hkv) * ROW_B;
+    const char* k_b = reinterpret_cast<const char*>(k) + (static_cast<size_t>(b) * S * Hkv + hk) * ROW_B;
+    const char* v_b = reinterpret_cast<const char*>(v) + (static_cast<size_t>(b) * S * Hkv + hk) * ROW_B;
+
+    auto issue = [&](int t, int buf) __attribute__((always_inline)) {
+        const bool pre = t < nPt;
+        const int j0 = (pre ? t : t - nPt) * BWD_TILE;
+        const int last = (pre ? P : S) - 1;
+        const size_t pitch = pre ? static_cast<size_t>(ROW_B) : own_pitch;
+        const char* kb = pre ? zk_b : k_b;
+        const char* vb = pre ? zv_b : v_b;
+        tile_load_async<BWD_TILE>(sm.k[buf], [&](int r) { return kb + min(j0 + r, last) * pitch; });
+        tile_load_async<BWD_TILE>(sm.v[buf], [&](int r) { return vb + min(j0 + r, last) * pitch; });
+    };
+
+    f32x16 acc[4][2];   // dQ^T: [head-element block][query block]
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[db][cb][r] = 0.f;
+    f32x16 s[2], dp[2];
+
+    auto scores = [&](const char* kt, const char* vt, int kr0) __attribute__((always_inline)) {
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { s[cb][r] = 0.f; dp[cb][r] = 0.f; }
+#pragma unroll
+        for (int t8 = 0; t8 < 8; ++t8) {
+            bf16x8 a = lds_frag_n(kt, kr0 + lc, 16 * t8 + 8 * lg);
+            s[0] = mma(a, qf[0][t8], s[0]);
+            s[1] = mma(a, qf[1][t8], s[1]);
+            bf16x8 a2 = lds_frag_n(vt, kr0 + lc, 16 * t8 + 8 * lg);
+            dp[0] = mma(a2, gf[0][t8], dp[0]);
+            dp[1] = mma(a2, gf[1][t8], dp[1]);
+        }
+    };
+    auto needs_mask = [&](int t, int hb) __attribute__((always_inline)) {
+        return t < nPt ? (t * BWD_TILE + 32 * hb + 32 > P) : ((t - nPt) * BWD_TILE + 32 * hb + 31 > wrow0);
+    };
+    auto mask = [&](int t, int hb) __attribute__((always_inline)) {
+        const bool own = t >= nPt;
+        const int j0 = (own ? t - nPt : t) * BWD_TILE + 32 * hb;
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) {
+            const int thr = (own ? wrow0 + 32 * cb + lc : P - 1) - j0 - 4 * lg;
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                if (8 * (r >> 2) + (r & 3) > thr) s[cb][r] = NEG_BIG;
+        }
+    };
+
+    issue(0, 0);
+    __syncthreads();
+    issue(min(1, nT - 1), 1);
+    scores(sm.k[0], sm.v[0], 0);
+    if (needs_mask(0, 0)) mask(0, 0);
+    const int nU = 2 * nT;
+    int buf = 0;
+    for (int u = 0; u < nU; ++u) {
+        const int hb = u & 1, t = u >> 1;
+        const int nbuf = buf + 1 == BWD_NBUF ? 0 : buf + 1;
+        const char* kt = sm.k[0] + buf * BWD_TILE_B;
+        const int nb = hb ? nbuf : buf;
+        bf16x8 dsf[2][2];   // [query block][k-step]: dS^T as B-operand fragments
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) {
+            f32x16 x;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float p = fast_exp2(fmaf(s[cb][r], c, -l2[cb]));
+                x[r] = p * (dp[cb][r] - dl[cb]);
+            }
+            dsf[cb][0] = pack_frag(x, 0);
+            dsf[cb][1] = pack_frag(x, 8);
+        }
+        scores(sm.k[0] + nb * BWD_TILE_B, sm.v[0] + nb * BWD_TILE_B, hb ? 0 : 32);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int db = 0; db < 4; ++db) {
+                bf16x8 a = lds_frag_t(kt, 32 * hb + 16 * ks, 32 * db, lane);
+                acc[db][0] = mma(a, dsf[0][ks], acc[db][0]);
+                acc[db][1] = mma(a, dsf[1][ks], acc[db][1]);
+            }
+        const int tn = (u + 1) >> 1, hn = (u + 1) & 1;
+        if (u + 1 < nU && needs_mask(tn, hn)) mask(tn, hn);
+        if (!hb) {
+            __syncthreads();
+            issue(min(t + 2, nT - 1), nbuf + 1 == BWD_NBUF ? 0 : nbuf + 1);
+        } else {
+            buf = nbuf;
+        }
+    }
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) {
+        const int qi = wrow0 + 32 * cb + lc;
+        f32x16 col[4] = {acc[0][cb], acc[1][cb], acc[2][cb], acc[3][cb]};
+        store_rows_bf16(col, qi < S ? dq + ((static_cast<size_t>(b) * S + qi) * Hq + h) * HD : nullptr, lg, scale);
+    }
+}
+
+// =================================================================================================
+// dK / dV: keys stationary
+// =================================================================================================
+struct KsSmem {
+    char q[BWD_NBUF][BWD_TILE_B];
+    char g[BWD_NBUF][BWD_TILE_B];
+    float l2[BWD_NBUF][BWD_TILE];
+    float dl[BWD_NBUF][BWD_TILE];
+};
+
+// One workgroup = 256 keys of one (sequence, KV head): a block of prefix slots, or a block of the
+// sequence's own tokens.  It streams the queries that see those keys: all tokens of all heads of
+// the group for prefix slots, tokens at or after the block for own keys.
+template <bool IS_DK>
+__global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
+    const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
+    const bf16_t* __restrict__ zk, const bf16_t* __restrict__ zv, const bf16_t* __restrict__ d_o,
+    const float* __restrict__ lse2, const float* __restrict__ delta, bf16_t* __restrict__ out_own,
+    float* __restrict__ part, int B, int S, int Hq, int Hkv, int P, float c, float scale) {
+    __shared__ KsSmem sm;
+    const int G = Hq / Hkv;
+    const int nPb = (P + BWD_WG_ROWS - 1) / BWD_WG_ROWS, nOb = (S + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
+    const int nKb = nPb + nOb;
+    int id = blockIdx.x;
+    const int hk = id % Hkv; id /= Hkv;
+    const int kb = id % nKb;
+    const int b = id / nKb;
+    const bool pre = kb < nPb;
+    const int key0 = (pre ? kb : kb - nPb) * BWD_WG_ROWS;
+    const int nkeys = pre ? P : S;
+    const int lane = threadIdx.x & 63, lg = lane >> 5, lc = lane & 31;
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wkey0 = key0 + 64 * wv;
+
+    // this wavefront's 64 keys as B operands: column = key, k = head element
+    bf16x8 kf[2][8], vf[2][8];
+#pragma unroll
+    for (int kc = 0; kc < 2; ++kc) {
+        const int key = min(wkey0 + 32 * kc + lc, nkeys - 1);
+        const size_t row = pre ? static_cast<size_t>(hk) * P + key
+                               : (static_cast<size_t>(b) * S + key) * Hkv + hk;
+        const bf16_t* kp = (pre ? zk : k) + row * HD + 8 * lg;
+        const bf16_t* vp = (pre ? zv : v) + row * HD + 8 * lg;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            kf[kc][t] = *reinterpret_cast<const bf16x8*>(kp + 16 * t);
+            if (IS_DK) vf[kc][t] = *reinterpret_cast<const bf16x8*>(vp + 16 * t);
+        }
+    }
+
+    const int nQtAll = (S + BWD_TILE - 1) / BWD_TILE;
+    const int qt0 = pre ? 0 : key0 / BWD_TILE;
+    const int nq = nQtAll - qt0;
+    const int nT = G * nq;            // query tiles streamed: head-major, token tiles inside
+    const char* q_c = reinterpret_cast<const char*>(q);
+    const char* g_c = reinterpret_cast<const char*>(d_o);
+    const size_t q_pitch = static_cast<size_t>(Hq) * ROW_B;
+
+    auto issue = [&](int T, int buf) __attribute__((always_inline)) {
+        const int gi = T / nq, qt = qt0 + T - gi * nq;
+        const int h = hk * G + gi;
+        const int i0 = qt * BWD_TILE;
+        const size_t base = (static_cast<size_t>(b) * S * Hq + h) * ROW_B;
+        tile_load_async<BWD_TILE>(sm.q[buf], [&](int r) { return q_c + base + min(i0 + r, S - 1) * q_pitch; });
+        tile_load_async<BWD_TILE>(sm.g[buf], [&](int r) { return g_c + base + min(i0 + r, S - 1) * q_pitch; });
+        // the tile's 64 lse2 / delta values: one 4-byte direct-to-LDS load per lane
+        if (wv < 2) {
+            const float* src = (wv == 0 ? lse2 : delta) + (static_cast<size_t>(b) * Hq + h) * S + min(i0 + lane, S - 1);
+            float* dst = wv == 0 ? sm.l2[buf] : sm.dl[buf];
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                             (__attribute__((address_space(3))) void*)dst, 4, 0, 0);
+        }
+    };
+    auto tile_i0 = [&](int T) __attribute__((always_inline)) {
+        const int gi = T / nq;
+        return (qt0 + T - gi * nq) * BWD_TILE;
+    };
+
+    f32x16 acc[4][2];   // dK^T or dV^T: [head-element block][key block]
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int kc = 0; kc < 2; ++kc)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[db][kc][r] = 0.f;
+    f32x16 s[2], dp[2];   // [key block]: rows = 32 queries of the sub-tile
+
+    auto scores = [&](const char* qt_, const char* gt_, int qr0) __attribute__((always_inline)) {
+#pragma unroll
+        for (int kc = 0; kc < 2; ++kc)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { s[kc][r] = 0.f; if (IS_DK) dp[kc][r] = 0.f; }
+#pragma unroll
+        for (int t8 = 0; t8 < 8; ++t8) {
+            bf16x8 a = lds_frag_n(qt_, qr0 + lc, 16 * t8 + 8 * lg);
+            s[0] = mma(a, kf[0][t8], s[0]);
+            s[1] = mma(a, kf[1][t8], s[1]);
+            if (IS_DK) {
+                bf16x8 a2 = lds_frag_n(gt_, qr0 + lc, 16 * t8 + 8 * lg);
+                dp[0] = mma(a2, vf[0][t8], dp[0]);
+                dp[1] = mma(a2, vf[1][t8], dp[1]);
+            }
+        }
+    };
+    // a query row of the sub-tile is hidden from a key when it precedes it (own keys) or lies
+    // past the end of the sequence (clamped tile rows)
+    auto needs_mask = [&](int T, int hb) __attribute__((always_inline)) {
+        const int i0 = tile_i0(T) + 32 * hb;
+        return (!pre && i0 < wkey0 + 63) || (i0 + 32 > S);
+    };
+    auto mask = [&](int T, int hb) __attribute__((always_inline)) {
+        const int i0 = tile_i0(T) + 32 * hb;
+#pragma unroll
+        for (int kc = 0; kc < 2; ++kc) {
+            // row i0 + d_row(r, lg) is visible iff it is >= the lane's key (own) and < S
+            const int lo = (pre ? 0 : wkey0 + 32 * kc + lc) - i0 - 4 * lg;
+            const int hi = S - i0 - 4 * lg;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int rr = 8 * (r >> 2) + (r & 3);
+                if (rr < lo || rr >= hi) s[kc][r] = NEG_BIG;
+            }
+        }
+    };
+
+    issue(0, 0);
+    __syncthreads();
+    issue(min(1, nT - 1), 1);
+    scores(sm.q[0], sm.g[0], 0);
+    if (needs_mask(0, 0)) mask(0, 0);
+    const int nU = 2 * nT;
+    int buf = 0;
+    for (int u = 0; u < nU; ++u) {
+        const int hb = u & 1, T = u >> 1;
+        const int nbuf = buf + 1 == BWD_NBUF ? 0 : buf + 1;
+        const int nb = hb ? nbuf : buf;
+        const char* at = (IS_DK ? sm.q[0] : sm.g[0]) + buf * BWD_TILE_B;   // transposed-read operand
+        // per-row lse2 / delta of this sub-tile: rows 8 j + 4 g + (0..3)
+        f32x4 lr[4], dr[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            lr[j] = *reinterpret_cast<const f32x4*>(&sm.l2[buf][32 * hb + 8 * j + 4 * lg]);
+            if (IS_DK) dr[j] = *reinterpret_cast<const f32x4*>(&sm.dl[buf][32 * hb + 8 * j + 4 * lg]);
+        }
+        bf16x8 xf[2][2];   // [key block][k-step]: P or dS as B-operand fragments
+#pragma unroll
+        for (int kc = 0; kc < 2; ++kc) {
+            f32x16 x;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float p = fast_exp2(fmaf(s[kc][r], c, -lr[r >> 2][r & 3]));
+                x[r] = IS_DK ? p * (dp[kc][r] - dr[r >> 2][r & 3]) : p;
+            }
+            xf[kc][0] = pack_frag(x, 0);
+            xf[kc][1] = pack_frag(x, 8);
+        }
+        scores(sm.q[0] + nb * BWD_TILE_B, sm.g[0] + nb * BWD_TILE_B, hb ? 0 : 32);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int db = 0; db < 4; ++db) {
+                bf16x8 a = lds_frag_t(at, 32 * hb + 16 * ks, 32 * db, lane);
+                acc[db][0] = mma(a, xf[0][ks], acc[db][0]);
+                acc[db][1] = mma(a, xf[1][ks], acc[db][1]);
+            }
+        const int Tn = (u + 1) >> 1, hn = (u + 1) & 1;
+        if (u + 1 < nU && needs_mask(Tn, hn)) mask(Tn, hn);
+        if (!hb) {
+            __syncthreads();
+            issue(min(T + 2, nT - 1), nbuf + 1 == BWD_NBUF ? 0 : nbuf + 1);
+        } else {
+            buf = nbuf;
+        }
+    }
+    const float mul = IS_DK ? scale : 1.f;
+#pragma unroll
+    for (int kc = 0; kc < 2; ++kc) {
+        const int key = wkey0 + 32 * kc + lc;
+        f32x16 col[4] = {acc[0][kc], acc[1][kc], acc[2][kc], acc[3][kc]};
+        if (pre)
+            store_rows_f32(col, key < P ? part + ((static_cast<size_t>(b) * Hkv + hk) * P + key) * HD : nullptr, lg, mul);
+        else
+            store_rows_bf16(col, key < S ? out_own + ((static_cast<size_t>(b) * S + key) * Hkv + hk) * HD : nullptr, lg, mul);
+    }
+}
+
+// dZ[hk,slot,:] = sum_b part[b,hk,slot,:] in order of b (+ the previous value when accumulating);
+// rows below n_frozen are 0 / left alone.  One 16-byte vector per thread.
+__global__ __launch_bounds__(256) void dz_reduce_kernel(const float* __restrict__ part,
+                                                        float* __restrict__ dz, int B, long n4,
+                                                        int P, int n_frozen, int accumulate) {
+    const long i = static_cast<long>(blockIdx.x) * 256 + threadIdx.x;
+    if (i >= n4) return;
+    const int slot = (i / (HD / 4)) % P;
+    const f32x4* src = reinterpret_cast<const f32x4*>(part);
+    f32x4 a = {0.f, 0.f, 0.f, 0.f};
+    if (slot >= n_frozen)
+        for (int b = 0; b < B; ++b) a += src[static_cast<long>(b) * n4 + i];
+    f32x4* dst = reinterpret_cast<f32x4*>(dz);
+    if (accumulate) a += dst[i];
+    dst[i] = a;
+}
+
+bool attn_mfma_bwd_supported(const cart_attn_desc& d) { return d.dtype == CART_BF16 && d.D == 128; }
+
+static size_t r256(size_t n) { return (n + 255) & ~static_cast<size_t>(255); }
+
+// beyond the delta array: lse2 [B,Hq,S] and the two per-sequence dZ partial buffers [B,Hkv,P,128]
+size_t attn_mfma_bwd_workspace(const cart_attn_desc& d) {
+    const size_t rows = r256(static_cast<size_t>(d.B) * d.Hq * d.S * sizeof(float));
+    const size_t part = r256(static_cast<size_t>(d.B) * d.Hkv * d.P * HD * sizeof(float));
+    return rows + 2 * part;
+}
+
+int launch_attn_bwd_mfma(const cart_attn_desc& d, float scale, const void* q, const void* k,
+                         const void* v, const void* zk, const void* zv, const void* o,
+                         const float* lse, const void* d_o, void* dq, void* dk, void* dv,
+                         float* dzk, float* dzv, void* ws, hipStream_t st) {
+    const size_t rows_b = r256(static_cast<size_t>(d.B) * d.Hq * d.S * sizeof(float));
+    const size_t part_b = r256(static_cast<size_t>(d.B) * d.Hkv * d.P * HD * sizeof(float));
+    char* w = static_cast<char*>(ws);
+    float* delta = reinterpret_cast<float*>(w);
+    float* lse2 = reinterpret_cast<float*>(w + rows_b);
+    float* part_k = reinterpret_cast<float*>(w + 2 * rows_b);
+    float* part_v = reinterpret_cast<float*>(w + 2 * rows_b + part_b);
+    const bf16_t *Q = static_cast<const bf16_t*>(q), *K = static_cast<const bf16_t*>(k),
+                 *V = static_cast<const bf16_t*>(v), *ZK = static_cast<const bf16_t*>(zk),
+                 *ZV = static_cast<const bf16_t*>(zv), *DO = static_cast<const bf16_t*>(d_o);
+    const float c = scale * CART_LOG2E;
+    const long rows = static_cast<long>(d.B) * d.S * d.Hq;
+    hipLaunchKernelGGL(attn_bwd_prep_kernel, dim3(static_cast<unsigned>((rows + 15) / 16)), dim3(256), 0, st,
+                       static_cast<const bf16_t*>(o), DO, lse, delta, lse2, d.B, d.S, d.Hq);
+    const int nQt = (d.S + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
+    hipLaunchKernelGGL(attn_bwd_dq_kernel, dim3(static_cast<unsigned>(static_cast<long>(nQt) * d.B * d.Hq)), dim3(256),
+                       0, st, Q, K, V, ZK, ZV, DO, lse2, delta, static_cast<bf16_t*>(dq), d.B, d.S, d.Hq,
+                       d.Hkv, d.P, c, scale);
+    const int nKb = (d.P + BWD_WG_ROWS - 1) / BWD_WG_ROWS + (d.S + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
+    const unsigned kgrid = static_cast<unsigned>(static_cast<long>(nKb) * d.B * d.Hkv);
+    hipLaunchKernelGGL(attn_bwd_kstat_kernel<true>, dim3(kgrid), dim3(256), 0, st, Q, K, V, ZK, ZV, DO, lse2,
+                       delta, static_cast<bf16_t*>(dk), part_k, d.B, d.S, d.Hq, d.Hkv, d.P, c, scale);
+    hipLaunchKernelGGL(attn_bwd_kstat_kernel<false>, dim3(kgrid), dim3(256), 0, st, Q, K, V, ZK, ZV, DO, lse2,
+                       delta, static_cast<bf16_t*>(dv), part_v, d.B, d.S, d.Hq, d.Hkv, d.P, c, scale);
+    if (d.P > 0) {
+        const long n4 = static_cast<long>(d.Hkv) * d.P * HD / 4;
+        const unsigned rg = static_cast<unsigned>((n4 + 255) / 256);
+        hipLaunchKernelGGL(dz_reduce_kernel, dim3(rg), dim3(256), 0, st, part_k, dzk, d.B, n4, d.P, d.n_frozen, d.dz_accumulate);
+        hipLaunchKernelGGL(dz_reduce_kernel, dim3(rg), dim3(256), 0, st, part_v, dzv, d.B, n4, d.P, d.n_frozen, d.dz_accumulate);
+    }
+    return static_cast<int>(hipGetLastError());
+}
+
+}  // namespace cart
