@@ -1,0 +1,202 @@
+#!/usr/bin/env python3
+"""Benchmark of the Cartridge hot path on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch of synthetic inputs already
+resident in HBM: cartridge attention forward + backward at the Llama-8B-shaped layer (cfg3), the
+fused context-distillation loss (cfg4) and one serve-time decode step over a shared cartridge
+(cfg5).  Prints ONE JSON line.  `value` is the attention forward+backward throughput in
+algorithmic TFLOP/s (4*D flops per visible (query,key) pair forward, 10*D backward); the loss
+and decode rates in algorithmic GB/s ride along in "parts".
+
+python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def attn_pairs(cfg) -> int:
+    return cfg.S * cfg.P + cfg.S * (cfg.S + 1) // 2
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only (no collectives, no sharding); "
+              "run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2506_06266_amd import binding as cb
+    from paper_2506_06266_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    cb.load()   # fails loudly when the HIP library is missing
+    dev = "cuda"
+    acfg, kcfg, dcfg = synth.ATTN_CONFIGS["cfg3"], synth.KL_CONFIGS["cfg4"], synth.DECODE_CONFIGS["cfg5"]
+
+    # ---- inputs and every output / workspace buffer, allocated before the timed region ----
+    a = synth.attn_inputs(acfg, dev)
+    o = torch.empty_like(a["q"])
+    lse = torch.empty(acfg.B, acfg.Hq, acfg.S, dtype=torch.float32, device=dev)
+    dq, dk, dv = torch.empty_like(a["q"]), torch.empty_like(a["k_own"]), torch.empty_like(a["v_own"])
+    dzk = torch.empty(a["z_k"].shape, dtype=torch.float32, device=dev)
+    dzv = torch.empty(a["z_v"].shape, dtype=torch.float32, device=dev)
+    import ctypes as C
+    lib = cb.load()
+    ad = cb.attn_desc(a["q"], a["k_own"], acfg.P)
+    ws_attn = torch.empty(max(lib.cart_attn_bwd_workspace(C.byref(ad)), lib.cart_attn_fwd_workspace(C.byref(ad)), 16),
+                          dtype=torch.uint8, device=dev)
+    kl = synth.kl_inputs(kcfg, dev)
+    dlogits = torch.empty_like(kl["logits"])
+    loss = torch.empty(1, dtype=torch.float32, device=dev)
+    ws_kl = torch.empty(kcfg.N * 4 + 256, dtype=torch.uint8, device=dev)
+    dc = synth.decode_inputs(dcfg, dev)
+    dec_o = torch.empty_like(dc["q"])
+    dec_lse = torch.empty(dcfg.B, dcfg.Hq, dtype=torch.float32, device=dev)
+    dd = cb.DecodeDesc(dcfg.B, dcfg.Hq, dcfg.Hkv, dcfg.D, dcfg.P, dc["k_own"].shape[0], dcfg.max_len,
+                       cb.CART_BF16, 0.0, cb.IMPL_AUTO)
+    ws_dec = torch.empty(max(lib.cart_decode_workspace(C.byref(dd)), 16), dtype=torch.uint8, device=dev)
+    own_tokens = int(dc["k_own"].shape[0])
+
+    def attn_fwd():
+        cb.cart_attn_fwd(a["q"], a["k_own"], a["v_own"], a["z_k"], a["z_v"], o=o, lse=lse, workspace=ws_attn)
+
+    def attn_bwd():
+        cb.cart_attn_bwd(a["q"], a["k_own"], a["v_own"], a["z_k"], a["z_v"], o, lse, a["d_o"], d_q=dq,
+                         d_k_own=dk, d_v_own=dv, d_z_k=dzk, d_z_v=dzv, workspace=ws_attn)
+
+    def kl_step():
+        cb.cart_distill_kl_fwd_bwd(kl["logits"], kl["teacher_idx"], kl["teacher_logp"], kcfg.scale,
+                                   d_logits=dlogits, loss=loss, workspace=ws_kl)
+
+    def dec_step():
+        cb.cart_decode(dc["q"], dc["z_k"], dc["z_v"], dc["k_own"], dc["v_own"], dc["cu_lens"], dcfg.max_len,
+                       o=dec_o, lse=dec_lse, workspace=ws_dec)
+
+    parts = [("attn_fwd", attn_fwd), ("attn_bwd", attn_bwd), ("kl", kl_step), ("decode", dec_step)]
+
+    for _ in range(args.warmup):
+        for _, f in parts:
+            f()
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly K steps; events on the launch stream bracket every part, and
+    # the library records an event at every kernel boundary of the backward call (trace hook)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(parts) + 1)] for _ in range(args.steps)]
+    traces = [cb.KernelTrace(8) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        ev[s][0].record()
+        for i, (name, f) in enumerate(parts):
+            if name == "attn_bwd":
+                with traces[s]:
+                    f()
+            else:
+                f()
+            ev[s][i + 1].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    part_ms = {name: sum(ev[s][i].elapsed_time(ev[s][i + 1]) for s in range(args.steps)) / args.steps
+               for i, (name, _) in enumerate(parts)}
+    bwd_kernels = ["prep", "dq", "dk", "dv", "dz_reduce"]
+    k_ms = {n: 0.0 for n in bwd_kernels}
+    for tr in traces:
+        iv = tr.intervals_ms(6)
+        for n, v in zip(bwd_kernels, iv):
+            k_ms[n] += v / args.steps
+        tr.close()
+
+    pairs = attn_pairs(acfg) * acfg.B * acfg.Hq
+    fwd_flop, bwd_flop = pairs * 4 * acfg.D, pairs * 10 * acfg.D
+    attn_ms = part_ms["attn_fwd"] + part_ms["attn_bwd"]
+    attn_tflops = (fwd_flop + bwd_flop) / (attn_ms * 1e-3) / 1e12
+    kl_bytes = 2 * kcfg.N * kcfg.V * 2 + kcfg.N * kcfg.K * 8 + 4
+    dec_bytes = (2 * dcfg.Hkv * dcfg.P * dcfg.D * 2 + 2 * own_tokens * dcfg.Hkv * dcfg.D * 2
+                 + 2 * dcfg.B * dcfg.Hq * dcfg.D * 2)
+    kl_gbs = kl_bytes / (part_ms["kl"] * 1e-3) / 1e9
+    dec_gbs = dec_bytes / (part_ms["decode"] * 1e-3) / 1e9
+
+    # dominant kernel of the step = the slowest of the three backward kernels, priced on the
+    # contractions it must perform over every visible pair: dq and dk kernels 3 (S, dP, and dQ
+    # or dK) = 6*D flops per pair, dv kernel 2 (S, dV) = 4*D.
+    dom = max(("dq", "dk", "dv"), key=lambda n: k_ms[n])
+    per_pair = {"dq": 6, "dk": 6, "dv": 4}[dom] * acfg.D
+    dom_tflops = pairs * per_pair / (k_ms[dom] * 1e-3) / 1e12
+    roofline = {"kernel": {"dq": "attn_bwd_dq_kernel", "dk": "attn_bwd_kstat_kernel<true>",
+                           "dv": "attn_bwd_kstat_kernel<false>"}[dom],
+                "bound": "mfma", "achieved": round(dom_tflops, 1), "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(dom_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "avg_launch_ms": round(k_ms[dom], 4)}
+
+    out = {
+        "metric": "cartridge attn fwd+bwd TFLOP/s (MFMA util) @Llama-8B shape; KL loss HBM GB/s",
+        "value": round(attn_tflops, 1), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "cfg3 attention B16 S2048 Hq32 Hkv8 D128 P4096 fwd+bwd; cfg4 loss N16384 "
+                               "V128256 K20; cfg5 decode B128 P8192 own U[1,1024]"},
+        "parts": {"attn_fwd_ms": round(part_ms["attn_fwd"], 4), "attn_bwd_ms": round(part_ms["attn_bwd"], 4),
+                  "attn_fwd_tflops": round(fwd_flop / part_ms["attn_fwd"] / 1e9, 1),
+                  "attn_bwd_tflops": round(bwd_flop / part_ms["attn_bwd"] / 1e9, 1),
+                  "attn_mfma_frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4),
+                  "bwd_kernel_ms": {n: round(v, 4) for n, v in k_ms.items()},
+                  "kl_ms": round(part_ms["kl"], 4), "kl_gbs": round(kl_gbs, 1),
+                  "kl_hbm_frac": round(kl_gbs / PEAK_HBM_GBS, 4),
+                  "decode_ms": round(part_ms["decode"], 4), "decode_gbs": round(dec_gbs, 1),
+                  "decode_hbm_frac": round(dec_gbs / PEAK_HBM_GBS, 4)},
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(a, acfg)
+    print(json.dumps(out))
+    return 0
+
+
+def cpu_baseline(a, acfg):
+    """The fp64 oracle, as it stands, timed on the host cores on a bounded sample of cfg3: one
+    sequence x the 4 query heads of one KV group, forward + backward."""
+    import numpy as np
+    from oracle import cartridge_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    G = acfg.Hq // acfg.Hkv
+    f64 = lambda t: t.detach().to("cpu").double().numpy()
+    q = f64(a["q"][:1, :, :G]); do = f64(a["d_o"][:1, :, :G])
+    k = f64(a["k_own"][:1, :, :1]); v = f64(a["v_own"][:1, :, :1])
+    zk = f64(a["z_k"][:1]); zv = f64(a["z_v"][:1])
+    t0 = time.perf_counter()
+    orc.attn_fwd(q, k, v, zk, zv)
+    orc.attn_bwd(q, k, v, zk, zv, do)
+    dt = time.perf_counter() - t0
+    flop = attn_pairs(acfg) * G * 14 * acfg.D
+    return {"value": round(flop / dt / 1e12, 5), "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": "cfg3 shape, 1 of 16 sequences x 4 of 32 query heads (one KV group), fwd+bwd, "
+                      "%.1f s" % dt}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -147,6 +147,17 @@ cart_status cart_decode(const cart_decode_desc *desc, const void *q, const void 
                         const int32_t *cu_lens, void *o, float *lse, void *workspace,
                         size_t workspace_bytes, void *stream);
 
+/*
+ * cart_trace_events -- optional per-kernel timing hook for benchmarks (not part of the paper).
+ * `events` is a host array of `count` hipEvent_t handles (passed as void*), or NULL to switch
+ * the hook off.  While set, every later cart_attn_fwd / cart_attn_bwd / cart_distill_kl_fwd_bwd /
+ * cart_decode call records events[0] on its stream before its first kernel and events[i] after
+ * its i-th kernel (as many as `count` allows; the call's kernel order is listed in the library's
+ * design notes).  The array must stay valid while the hook is set.  Process-global, not
+ * thread-safe; the caller owns the events and reads them after synchronising the stream.
+ */
+cart_status cart_trace_events(void *const *events, int32_t count);
+
 const char *cart_status_str(cart_status status);
 int cart_version(void);
 

@@ -22,7 +22,7 @@ STATUS_NAMES = ["CART_OK", "CART_ERR_NULL", "CART_ERR_SHAPE", "CART_ERR_UNSUPPOR
 
 EXPORTS = ["cart_attn_fwd_workspace", "cart_attn_bwd_workspace", "cart_kl_workspace",
            "cart_decode_workspace", "cart_attn_fwd", "cart_attn_bwd", "cart_distill_kl_fwd_bwd",
-           "cart_decode", "cart_status_str", "cart_version"]
+           "cart_decode", "cart_trace_events", "cart_status_str", "cart_version"]
 
 
 class AttnDesc(C.Structure):
@@ -74,6 +74,8 @@ def load() -> C.CDLL:
     lib.cart_distill_kl_fwd_bwd.argtypes = [C.POINTER(KlDesc)] + [vp] * 7 + [sz, vp]
     lib.cart_decode.restype = C.c_int
     lib.cart_decode.argtypes = [C.POINTER(DecodeDesc)] + [vp] * 9 + [sz, vp]
+    lib.cart_trace_events.restype = C.c_int
+    lib.cart_trace_events.argtypes = [C.POINTER(C.c_void_p), C.c_int32]
     lib.cart_status_str.restype, lib.cart_status_str.argtypes = C.c_char_p, [C.c_int]
     lib.cart_version.restype, lib.cart_version.argtypes = C.c_int, []
     _lib = lib
@@ -205,3 +207,49 @@ def cart_decode(q, z_k, z_v, k_own, v_own, cu_lens, max_own_len: int, *, scale: 
                          0 if ws is None else ws.numel(), _stream(stream))
     _check(st, "cart_decode")
     return o, lse
+
+
+# ------------------------------------------------------------------------------------------------
+class KernelTrace:
+    """HIP events recorded by the library at kernel boundaries (cart_trace_events).
+
+    with KernelTrace(6) as tr:  cart_attn_bwd(...);  torch.cuda.synchronize();  tr.intervals_ms()
+    """
+
+    def __init__(self, count: int):
+        self.count = count
+        self._hip = C.CDLL("libamdhip64.so")
+        self._hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        self._hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        self._hip.hipEventDestroy.argtypes = [C.c_void_p]
+        self._hip.hipEventQuery.argtypes = [C.c_void_p]
+        self.events = (C.c_void_p * count)()
+        for i in range(count):
+            ev = C.c_void_p()
+            if self._hip.hipEventCreate(C.byref(ev)) != 0:
+                raise RuntimeError("hipEventCreate failed")
+            self.events[i] = ev
+
+    def __enter__(self):
+        _check(load().cart_trace_events(self.events, self.count), "cart_trace_events")
+        return self
+
+    def __exit__(self, *exc):
+        load().cart_trace_events(None, 0)
+        return False
+
+    def intervals_ms(self, n: Optional[int] = None):
+        """Elapsed ms between consecutive events 0..n (call after synchronising the stream)."""
+        n = self.count if n is None else n
+        out = []
+        for i in range(n - 1):
+            ms = C.c_float()
+            rc = self._hip.hipEventElapsedTime(C.byref(ms), self.events[i], self.events[i + 1])
+            if rc != 0:
+                raise RuntimeError("hipEventElapsedTime failed (%d): event %d not recorded?" % (rc, i + 1))
+            out.append(ms.value)
+        return out
+
+    def close(self):
+        for i in range(self.count):
+            self._hip.hipEventDestroy(self.events[i])

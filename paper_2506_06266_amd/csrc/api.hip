@@ -4,6 +4,13 @@
 
 #include "cart_common.h"
 
+namespace cart {
+Trace& trace() {
+    static Trace t;
+    return t;
+}
+}  // namespace cart
+
 namespace {
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -160,6 +167,15 @@ cart_status cart_decode(const cart_decode_desc* d, const void* q, const void* z_
                 ? cart::launch_decode_mfma(*d, scale, q, z_k, z_v, k_own, v_own, cu_lens, o, lse, workspace, st)
                 : cart::launch_decode_vector(*d, scale, q, z_k, z_v, k_own, v_own, cu_lens, o, lse, st);
     return e == 0 ? CART_OK : CART_ERR_LAUNCH;
+}
+
+cart_status cart_trace_events(void* const* events, int32_t count) {
+    if (events && count < 1) return CART_ERR_SHAPE;
+    cart::Trace& t = cart::trace();
+    t.events = events;
+    t.count = events ? count : 0;
+    t.next = 0;
+    return CART_OK;
 }
 
 const char* cart_status_str(cart_status s) {

@@ -460,23 +460,29 @@ int launch_attn_bwd_mfma(const cart_attn_desc& d, float scale, const void* q, co
                  *ZV = static_cast<const bf16_t*>(zv), *DO = static_cast<const bf16_t*>(d_o);
     const float c = scale * CART_LOG2E;
     const long rows = static_cast<long>(d.B) * d.S * d.Hq;
+    trace_begin(st);   // kernel order: prep, dq, dk, dv, dz reduce (k, v)
     hipLaunchKernelGGL(attn_bwd_prep_kernel, dim3(static_cast<unsigned>((rows + 15) / 16)), dim3(256), 0, st,
                        static_cast<const bf16_t*>(o), DO, lse, delta, lse2, d.B, d.S, d.Hq);
+    trace_mark(st);
     const int nQt = (d.S + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
     hipLaunchKernelGGL(attn_bwd_dq_kernel, dim3(static_cast<unsigned>(static_cast<long>(nQt) * d.B * d.Hq)), dim3(256),
                        0, st, Q, K, V, ZK, ZV, DO, lse2, delta, static_cast<bf16_t*>(dq), d.B, d.S, d.Hq,
                        d.Hkv, d.P, c, scale);
+    trace_mark(st);
     const int nKb = (d.P + BWD_WG_ROWS - 1) / BWD_WG_ROWS + (d.S + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
     const unsigned kgrid = static_cast<unsigned>(static_cast<long>(nKb) * d.B * d.Hkv);
     hipLaunchKernelGGL(attn_bwd_kstat_kernel<true>, dim3(kgrid), dim3(256), 0, st, Q, K, V, ZK, ZV, DO, lse2,
                        delta, static_cast<bf16_t*>(dk), part_k, d.B, d.S, d.Hq, d.Hkv, d.P, c, scale);
+    trace_mark(st);
     hipLaunchKernelGGL(attn_bwd_kstat_kernel<false>, dim3(kgrid), dim3(256), 0, st, Q, K, V, ZK, ZV, DO, lse2,
                        delta, static_cast<bf16_t*>(dv), part_v, d.B, d.S, d.Hq, d.Hkv, d.P, c, scale);
+    trace_mark(st);
     if (d.P > 0) {
         const long n4 = static_cast<long>(d.Hkv) * d.P * HD / 4;
         const unsigned rg = static_cast<unsigned>((n4 + 255) / 256);
         hipLaunchKernelGGL(dz_reduce_kernel, dim3(rg), dim3(256), 0, st, part_k, dzk, d.B, n4, d.P, d.n_frozen, d.dz_accumulate);
         hipLaunchKernelGGL(dz_reduce_kernel, dim3(rg), dim3(256), 0, st, part_v, dzv, d.B, n4, d.P, d.n_frozen, d.dz_accumulate);
+        trace_mark(st);
     }
     return static_cast<int>(hipGetLastError());
 }

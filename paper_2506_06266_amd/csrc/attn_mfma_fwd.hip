@@ -244,11 +244,13 @@ int launch_attn_fwd_mfma(const cart_attn_desc& d, float scale, const void* q, co
                          void*, hipStream_t st) {
     const int nQt = (d.S + FWD_BM - 1) / FWD_BM;
     const long grid = static_cast<long>(nQt) * d.B * d.Hq;
+    trace_begin(st);
     hipLaunchKernelGGL(attn_fwd_mfma_kernel, dim3(static_cast<unsigned>(grid)), dim3(256), 0, st,
                        static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(k),
                        static_cast<const bf16_t*>(v), static_cast<const bf16_t*>(zk),
                        static_cast<const bf16_t*>(zv), static_cast<bf16_t*>(o), lse, d.B, d.S, d.Hq,
                        d.Hkv, d.P, scale * CART_LOG2E);
+    trace_mark(st);
     return static_cast<int>(hipGetLastError());
 }
 

@@ -246,8 +246,10 @@ static void fwd_t(const cart_attn_desc& d, float scale, const void* q, const voi
 int launch_attn_fwd_vector(const cart_attn_desc& d, float scale, const void* q, const void* k,
                            const void* v, const void* zk, const void* zv, void* o, float* lse,
                            hipStream_t st) {
+    trace_begin(st);
     if (d.dtype == CART_F32) fwd_t<float>(d, scale, q, k, v, zk, zv, o, lse, st);
     else fwd_t<bf16_t>(d, scale, q, k, v, zk, zv, o, lse, st);
+    trace_mark(st);
     return static_cast<int>(hipGetLastError());
 }
 
@@ -258,16 +260,20 @@ static void bwd_t(const cart_attn_desc& d, float scale, const void* q, const voi
     const long rows = static_cast<long>(d.B) * d.S * d.Hq;
     const long keys = static_cast<long>(d.Hkv) * d.P + static_cast<long>(d.B) * d.S * d.Hkv;
     float* delta = static_cast<float*>(ws);
+    trace_begin(st);   // kernel order: delta, dq, dk/dv/dz
     CART_DISPATCH_E(d.D, {
         hipLaunchKernelGGL((attn_delta_vector<T, E>), dim3(blocks_for(rows)), dim3(64 * VEC_WAVES),
                            0, st, (const T*)o, (const T*)d_o, delta, d.B, d.S, d.Hq, d.D);
+        trace_mark(st);
         hipLaunchKernelGGL((attn_bwd_dq_vector<T, E>), dim3(blocks_for(rows)), dim3(64 * VEC_WAVES),
                            0, st, (const T*)q, (const T*)k, (const T*)v, (const T*)zk, (const T*)zv,
                            lse, delta, (const T*)d_o, (T*)dq, d.B, d.S, d.Hq, d.Hkv, d.D, d.P, scale);
+        trace_mark(st);
         hipLaunchKernelGGL((attn_bwd_dkv_vector<T, E>), dim3(blocks_for(keys)), dim3(64 * VEC_WAVES),
                            0, st, (const T*)q, (const T*)k, (const T*)v, (const T*)zk, (const T*)zv,
                            lse, delta, (const T*)d_o, (T*)dk, (T*)dv, dzk, dzv, d.B, d.S, d.Hq,
                            d.Hkv, d.D, d.P, scale, d.n_frozen, d.dz_accumulate);
+        trace_mark(st);
     });
 }
 
@@ -293,8 +299,10 @@ static void dec_t(const cart_decode_desc& d, float scale, const void* q, const v
 int launch_decode_vector(const cart_decode_desc& d, float scale, const void* q, const void* zk,
                          const void* zv, const void* k, const void* v, const int32_t* cu,
                          void* o, float* lse, hipStream_t st) {
+    trace_begin(st);
     if (d.dtype == CART_F32) dec_t<float>(d, scale, q, zk, zv, k, v, cu, o, lse, st);
     else dec_t<bf16_t>(d, scale, q, zk, zv, k, v, cu, o, lse, st);
+    trace_mark(st);
     return static_cast<int>(hipGetLastError());
 }
 

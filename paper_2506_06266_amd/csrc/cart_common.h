@@ -62,6 +62,23 @@ __device__ __forceinline__ float wave_max(float v) {
     return v;
 }
 
+// Benchmark hook (cart_trace_events): records the next event of the caller's array on `st`.
+struct Trace {
+    void* const* events = nullptr;
+    int count = 0;
+    int next = 0;
+};
+Trace& trace();
+inline void trace_begin(hipStream_t st) {
+    Trace& t = trace();
+    t.next = 0;
+    if (t.events && t.count > 0) { hipEventRecord(static_cast<hipEvent_t>(t.events[0]), st); t.next = 1; }
+}
+inline void trace_mark(hipStream_t st) {
+    Trace& t = trace();
+    if (t.events && t.next < t.count) hipEventRecord(static_cast<hipEvent_t>(t.events[t.next++]), st);
+}
+
 // ---- internal launchers (host side), one per kernel family; all return hipError_t as int ----
 int launch_kl(const cart_kl_desc& d, const void* logits, const int32_t* idx, const float* logp,
               float* loss, void* d_logits, float* row_kl, void* ws, hipStream_t st);

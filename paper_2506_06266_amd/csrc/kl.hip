@@ -226,6 +226,7 @@ __global__ __launch_bounds__(1024) void kl_reduce_rows(const float* row_kl, int 
 int launch_kl(const cart_kl_desc& d, const void* logits, const int32_t* idx, const float* logp,
               float* loss, void* d_logits, float* row_kl, void* ws, hipStream_t st) {
     float* rows = row_kl ? row_kl : static_cast<float*>(ws);
+    trace_begin(st);   // kernel order: row kernel, loss reduce
     const bool resident = d.logits_dtype == CART_BF16 && (d.V % 8) == 0 && d.V <= 1024 * 16 * 8;
     if (resident) {
         const bf16_t* x = static_cast<const bf16_t*>(logits);
@@ -246,7 +247,9 @@ int launch_kl(const cart_kl_desc& d, const void* logits, const int32_t* idx, con
                            static_cast<const float*>(logits), idx, logp,
                            static_cast<float*>(d_logits), rows, d.V, d.K, d.scale);
     }
+    trace_mark(st);
     hipLaunchKernelGGL(kl_reduce_rows, dim3(1), dim3(1024), 0, st, rows, d.N, d.scale, loss);
+    trace_mark(st);
     return static_cast<int>(hipGetLastError());
 }
 
