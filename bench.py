@@ -174,8 +174,8 @@ def main() -> int:
 
 
 def cpu_baseline(a, acfg):
-    """The fp64 oracle, as it stands, timed on the host cores on a bounded sample of cfg3: one
-    sequence x the 4 query heads of one KV group, forward + backward."""
+    """The fp64 oracle, as it stands, timed on the host cores on a bounded sample of cfg3: four
+    sequences x four KV groups (16 query heads), forward + backward."""
     import numpy as np
     from oracle import cartridge_oracle as orc
     try:
@@ -185,16 +185,17 @@ def cpu_baseline(a, acfg):
         cores = os.cpu_count() or 1
     G = acfg.Hq // acfg.Hkv
     f64 = lambda t: t.detach().to("cpu").double().numpy()
-    q = f64(a["q"][:1, :, :G]); do = f64(a["d_o"][:1, :, :G])
-    k = f64(a["k_own"][:1, :, :1]); v = f64(a["v_own"][:1, :, :1])
-    zk = f64(a["z_k"][:1]); zv = f64(a["z_v"][:1])
+    NB, NK = 4, 4                      # sequences x KV groups in the sample
+    q = f64(a["q"][:NB, :, :NK * G]); do = f64(a["d_o"][:NB, :, :NK * G])
+    k = f64(a["k_own"][:NB, :, :NK]); v = f64(a["v_own"][:NB, :, :NK])
+    zk = f64(a["z_k"][:NK]); zv = f64(a["z_v"][:NK])
     t0 = time.perf_counter()
     orc.attn_fwd(q, k, v, zk, zv)
     orc.attn_bwd(q, k, v, zk, zv, do)
     dt = time.perf_counter() - t0
-    flop = attn_pairs(acfg) * G * 14 * acfg.D
+    flop = attn_pairs(acfg) * NB * NK * G * 14 * acfg.D
     return {"value": round(flop / dt / 1e12, 5), "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
-            "sample": "cfg3 shape, 1 of 16 sequences x 4 of 32 query heads (one KV group), fwd+bwd, "
+            "sample": "cfg3 shape, 4 of 16 sequences x 16 of 32 query heads (4 KV groups), fwd+bwd, "
                       "%.1f s" % dt}
 
 
