@@ -1,0 +1,111 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+The GPU runs the whole problem; the oracle recomputes a sample that is complete for the outputs
+it checks: for attention one whole KV group (every sequence, its G query heads), which fixes
+O / LSE / dQ for those heads, dK_own / dV_own for that KV head and -- because the sum over the
+whole batch is inside the sample -- dZ_k / dZ_v of that head, every element.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import cartridge_oracle as orc
+from paper_2506_06266_amd import binding as cb
+from paper_2506_06266_amd import synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+TOL = 2e-2
+
+
+def rel_err(x, ref) -> float:
+    x = np.asarray(x, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert x.shape == ref.shape and np.isfinite(x).all()
+    return float(np.abs(x - ref).max() / np.abs(ref).max())
+
+
+def f64(t):
+    return t.detach().to("cpu", torch.float64).numpy()
+
+
+@pytest.mark.parametrize("name,hk", [("cfg2", 5), ("cfg3", 2)])
+def test_attention_full_shape_one_kv_group(name, hk):
+    cfg = synth.ATTN_CONFIGS[name]
+    print("case", name, "kv head", hk, flush=True)
+    g = synth.attn_inputs(cfg, DEV)
+    o, lse = cb.cart_attn_fwd(g["q"], g["k_own"], g["v_own"], g["z_k"], g["z_v"])
+    dq, dk, dv, dzk, dzv = cb.cart_attn_bwd(g["q"], g["k_own"], g["v_own"], g["z_k"], g["z_v"], o, lse, g["d_o"])
+    torch.cuda.synchronize()
+    G = cfg.Hq // cfg.Hkv
+    hs = slice(hk * G, (hk + 1) * G)
+    q, do = f64(g["q"][:, :, hs]), f64(g["d_o"][:, :, hs])
+    k, v = f64(g["k_own"][:, :, hk:hk + 1]), f64(g["v_own"][:, :, hk:hk + 1])
+    zk, zv = f64(g["z_k"][hk:hk + 1]), f64(g["z_v"][hk:hk + 1])
+    o_ref, lse_ref = orc.attn_fwd(q, k, v, zk, zv)
+    r = orc.attn_bwd(q, k, v, zk, zv, do)
+    errs = {
+        "o": rel_err(f64(o[:, :, hs]), o_ref), "lse": rel_err(f64(lse[:, hs]), lse_ref),
+        "dq": rel_err(f64(dq[:, :, hs]), r[0]), "dk": rel_err(f64(dk[:, :, hk:hk + 1]), r[1]),
+        "dv": rel_err(f64(dv[:, :, hk:hk + 1]), r[2]), "dzk": rel_err(f64(dzk[hk:hk + 1]), r[3]),
+        "dzv": rel_err(f64(dzv[hk:hk + 1]), r[4]),
+    }
+    print(name, errs, flush=True)
+    for kk, e in errs.items():
+        assert e <= TOL, (name, kk, e)
+    # the backward pass is bit-reproducible (no atomics): a second run gives the same bits
+    again = cb.cart_attn_bwd(g["q"], g["k_own"], g["v_own"], g["z_k"], g["z_v"], o, lse, g["d_o"])
+    torch.cuda.synchronize()
+    for a, b in zip((dq, dk, dv, dzk, dzv), again):
+        assert torch.equal(a, b)
+
+
+def test_distill_kl_full_size_sampled_rows():
+    cfg = synth.KL_CONFIGS["cfg4"]
+    print("case cfg4", flush=True)
+    g = synth.kl_inputs(cfg, DEV)
+    row_kl = torch.empty(cfg.N, dtype=torch.float32, device=DEV)
+    loss, dl = cb.cart_distill_kl_fwd_bwd(g["logits"], g["teacher_idx"], g["teacher_logp"], cfg.scale, row_kl=row_kl)
+    torch.cuda.synchronize()
+    rows = torch.tensor(sorted({0, 1, 777, 4095, 4096, 8191, 12345, 16383} |
+                               set(np.random.default_rng(7).integers(0, cfg.N, 40).tolist())), device=DEV)
+    z = f64(g["logits"][rows])
+    idx = g["teacher_idx"][rows].cpu().numpy()
+    lp = f64(g["teacher_logp"][rows])
+    _, dl_ref, row_ref = orc.distill_kl(z, idx, lp, cfg.scale)
+    e_dl = rel_err(f64(dl[rows]), dl_ref)
+    e_row = rel_err(f64(row_kl[rows]), row_ref)
+    print("cfg4", {"dl": e_dl, "row_kl": e_row}, flush=True)
+    assert e_dl <= TOL and e_row <= 1e-4
+    # the recorded tokens carry the only negative gradients of a row, exactly at teacher_idx
+    neg = (dl[rows].float() < 0).cpu()
+    assert torch.equal(neg, torch.tensor(dl_ref < 0))
+    # scalar = scale * sum of the per-row values (fixed-order fp64 reduce in the library)
+    expect = cfg.scale * float(row_kl.double().sum().item())
+    assert abs(loss.item() - expect) <= 1e-6 * abs(expect)
+    # in place (d_logits aliases logits): same bits
+    buf = g["logits"].clone()
+    loss2, dl2 = cb.cart_distill_kl_fwd_bwd(buf, g["teacher_idx"], g["teacher_logp"], cfg.scale, d_logits=buf)
+    torch.cuda.synchronize()
+    assert torch.equal(dl2[rows], dl[rows]) and torch.equal(dl2[::97], dl[::97]) and loss2.item() == loss.item()
+
+
+@pytest.mark.parametrize("name,reqs", [("cfg5", [0, 1, 17, 63, 64, 100, 127]), ("cfg5_long", [0, 5])])
+def test_decode_full_size_sampled_requests(name, reqs):
+    cfg = synth.DECODE_CONFIGS[name]
+    print("case", name, flush=True)
+    g = synth.decode_inputs(cfg, DEV)
+    o, lse = cb.cart_decode(g["q"], g["z_k"], g["z_v"], g["k_own"], g["v_own"], g["cu_lens"], cfg.max_len)
+    torch.cuda.synchronize()
+    cu = g["cu_lens"].cpu().numpy()
+    zk, zv = f64(g["z_k"]), f64(g["z_v"])
+    worst = 0.0
+    for b in reqs:
+        lo, hi = int(cu[b]), int(cu[b + 1])
+        o_ref, l_ref = orc.decode(f64(g["q"][b:b + 1]), zk, zv, f64(g["k_own"][lo:hi]), f64(g["v_own"][lo:hi]),
+                                  np.array([0, hi - lo]))
+        e = max(rel_err(f64(o[b:b + 1]), o_ref), rel_err(f64(lse[b:b + 1]), l_ref))
+        worst = max(worst, e)
+    print(name, "worst", worst, flush=True)
+    assert worst <= TOL
+    assert torch.isfinite(o.float()).all() and torch.isfinite(lse).all()
