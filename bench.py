@@ -35,6 +35,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (no collectives, no sharding); "
@@ -92,6 +94,13 @@ def main() -> int:
                        o=dec_o, lse=dec_lse, workspace=ws_dec)
 
     parts = [("attn_fwd", attn_fwd), ("attn_bwd", attn_bwd), ("kl", kl_step), ("decode", dec_step)]
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)          # a plain copy kernel: 1 GiB read, 1 GiB written
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         for _, f in parts:

@@ -14,8 +14,8 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 ROOT = os.path.dirname(HERE)
-LIB = os.path.join(HERE, "libcartridge.so")
-OBJ_DIR = os.path.join(HERE, "_build")
+LIB = os.environ.get("CART_LIB_OUT", os.path.join(HERE, "libcartridge.so"))
+OBJ_DIR = os.environ.get("CART_OBJ_DIR", os.path.join(HERE, "_build"))
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -23,7 +23,7 @@ FLAGS = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option",
     "-I", os.path.join(ROOT, "include"),
-]
+] + os.environ.get("CART_EXTRA_FLAGS", "").split()
 
 
 def _newest_header() -> float:
