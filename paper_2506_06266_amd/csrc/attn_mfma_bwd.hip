@@ -265,6 +265,263 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
     const int wkey0 = key0 + 64 * wv;
 
     // this wavefront's 64 keys as B operands: column = key, k = head element
+    u32x4 kf[2][8], vf[2][8];
+#pragma unroll
+    for (int kc = 0; kc < 2; ++kc) {
+        const int key = min(wkey0 + 32 * kc + lc, nkeys - 1);
+        const size_t row = pre ? static_cast<size_t>(hk) * P + key
+                               : (static_cast<size_t>(b) * S + key) * Hkv + hk;
+        const bf16_t* kp = (pre ? zk : k) + row * HD + 8 * lg;
+        const bf16_t* vp = (pre ? zv : v) + row * HD + 8 * lg;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            kf[kc][t] = *reinterpret_cast<const u32x4*>(kp + 16 * t);
+            if (IS_DK) vf[kc][t] = *reinterpret_cast<const u32x4*>(vp + 16 * t);
+        }
+    }
+
+    const int nQtAll = (S + BWD_TILE - 1) / BWD_TILE;
+    const int qt0 = pre ? 0 : key0 / BWD_TILE;
+    const int nq = nQtAll - qt0;
+    const int nT = G * nq;            // query tiles streamed: head-major, token tiles inside
+    const char* q_c = reinterpret_cast<const char*>(q);
+    const char* g_c = reinterpret_cast<const char*>(d_o);
+    const size_t q_pitch = static_cast<size_t>(Hq) * ROW_B;
+
+    auto issue = [&](int T, int buf) __attribute__((always_inline)) {
+        const int gi = T / nq, qt = qt0 + T - gi * nq;
+        const int h = hk * G + gi;
+        const int i0 = qt * BWD_TILE;
+        const size_t base = (static_cast<size_t>(b) * S * Hq + h) * ROW_B;
+        tile_load_async<BWD_TILE>(sm.q[buf], [&](int r) { return q_c + base + min(i0 + r, S - 1) * q_pitch; });
+        tile_load_async<BWD_TILE>(sm.g[buf], [&](int r) { return g_c + base + min(i0 + r, S - 1) * q_pitch; });
+        // the tile's 64 lse2 / delta values: one 4-byte direct-to-LDS load per lane
+        if (wv < 2) {
+            const float* src = (wv == 0 ? lse2 : delta) + (static_cast<size_t>(b) * Hq + h) * S + min(i0 + lane, S - 1);
+            float* dst = wv == 0 ? sm.l2[buf] : sm.dl[buf];
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                             (__attribute__((address_space(3))) void*)dst, 4, 0, 0);
+        }
+    };
+    auto tile_i0 = [&](int T) __attribute__((always_inline)) {
+        const int gi = T / nq;
+        return (qt0 + T - gi * nq) * BWD_TILE;
+    };
+
+    f32x16 acc[4][2];   // dK^T or dV^T: [head-element block][key block]
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int kc = 0; kc < 2; ++kc)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[db][kc][r] = 0.f;
+    f32x16 s[2], dp[2];   // [key block]: rows = 32 queries of the sub-tile, one iteration ahead
+    bf16x8 xf[2][2];      // P or dS of sub-tile u-1 as B-operand fragments [key block][k-step]
+#pragma unroll
+    for (int kc = 0; kc < 2; ++kc)
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) xf[kc][ks] = bf16x8{};
+
+    // a query row of the sub-tile is hidden from a key when it precedes it (own keys) or lies
+    // past the end of the sequence (clamped tile rows)
+    auto needs_mask = [&](int T, int hb) __attribute__((always_inline)) {
+        const int i0 = tile_i0(T) + 32 * hb;
+        return (!pre && i0 < wkey0 + 63) || (i0 + 32 > S);
+    };
+    auto mask = [&](f32x16 (&x)[2], int T, int hb) __attribute__((always_inline)) {
+        const int i0 = tile_i0(T) + 32 * hb;
+#pragma unroll
+        for (int kc = 0; kc < 2; ++kc) {
+            // row i0 + d_row(r, lg) is visible iff it is >= the lane's key (own) and < S
+            const int lo = (pre ? 0 : wkey0 + 32 * kc + lc) - i0 - 4 * lg;
+            const int hi = S - i0 - 4 * lg;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int rr = 8 * (r >> 2) + (r & 3);
+                if (rr < lo || rr >= hi) x[kc][r] = NEG_BIG;
+            }
+        }
+    };
+    // the stationary fragments live in accumulation registers (read directly as B operands)
+#ifndef CART_DK_PIN_K
+#define CART_DK_PIN_K 1
+#endif
+#ifndef CART_DK_PREFETCH_TR
+#define CART_DK_PREFETCH_TR 0
+#endif
+    constexpr bool PIN_K = !IS_DK || CART_DK_PIN_K;
+    constexpr bool PREFETCH_TR = !IS_DK || CART_DK_PREFETCH_TR;
+    auto pin = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int kc = 0; kc < 2; ++kc)
+#pragma unroll
+            for (int t = 0; t < 8; ++t)
+                if (PIN_K) asm volatile("" : "+a"(kf[kc][t]));
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int kc = 0; kc < 2; ++kc) asm volatile("" : "+a"(acc[db][kc]));
+    };
+#define KF_(kc, t) __builtin_bit_cast(bf16x8, kf[kc][t])
+#define VF_(kc, t) __builtin_bit_cast(bf16x8, vf[kc][t])
+
+    // LDS -> register fragments run one iteration ahead of their use (loop-carried): row-wise Q
+    // (and dO) of sub-tile u+1, transposed dO (or Q) of sub-tile u-1
+    bf16x8 qa[8], ga[8], ta[2][4];
+    auto load_nat = [&](int buf, int r0) __attribute__((always_inline)) {
+#pragma unroll
+        for (int t8 = 0; t8 < 8; ++t8) {
+            qa[t8] = lds_frag_n(sm.q[0] + buf * BWD_TILE_B, r0 + lc, 16 * t8 + 8 * lg);
+            if (IS_DK) ga[t8] = lds_frag_n(sm.g[0] + buf * BWD_TILE_B, r0 + lc, 16 * t8 + 8 * lg);
+        }
+    };
+    auto load_tr = [&](int buf, int r0) __attribute__((always_inline)) {
+        const char* at = (IS_DK ? sm.q[0] : sm.g[0]) + buf * BWD_TILE_B;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int db = 0; db < 4; ++db) ta[ks][db] = lds_frag_t(at, r0 + 16 * ks, 32 * db, lane);
+    };
+    auto scores = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int kc = 0; kc < 2; ++kc)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { s[kc][r] = 0.f; if (IS_DK) dp[kc][r] = 0.f; }
+#pragma unroll
+        for (int t8 = 0; t8 < 8; ++t8) {
+            s[0] = mma(qa[t8], KF_(0, t8), s[0]);
+            s[1] = mma(qa[t8], KF_(1, t8), s[1]);
+            if (IS_DK) {
+                dp[0] = mma(ga[t8], VF_(0, t8), dp[0]);
+                dp[1] = mma(ga[t8], VF_(1, t8), dp[1]);
+            }
+        }
+    };
+    // Iteration u (sub-tile hb of streamed tile T, in LDS buffer buf; nbuf holds tile T+1).  On
+    // entry: s (dp) = scores of sub-tile u, qa (ga) = row-wise fragments of sub-tile u+1,
+    // ta = transposed fragments of sub-tile u-1, xf = P / dS of sub-tile u-1.
+    auto stage = [&](int T, int hb, int buf, int nbuf) __attribute__((always_inline)) {
+        // scores of sub-tile u move to ordinary registers (their accumulators are reused); the
+        // rare masked sub-tile is patched here, outside the main block
+        f32x16 x[2] = {s[0], s[1]};
+        f32x16 y[2];
+        if (IS_DK) { y[0] = dp[0]; y[1] = dp[1]; }
+        if (needs_mask(T, hb)) mask(x, T, hb);
+        pin();
+        // per-row lse2 / delta of this sub-tile: rows 8 j + 4 g + (0..3)
+        f32x4 lr[4], dr[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            lr[j] = *reinterpret_cast<const f32x4*>(&sm.l2[buf][32 * hb + 8 * j + 4 * lg]);
+            if (IS_DK) dr[j] = *reinterpret_cast<const f32x4*>(&sm.dl[buf][32 * hb + 8 * j + 4 * lg]);
+        }
+        scores();
+        if (!PREFETCH_TR) load_tr(hb ? buf : (buf == 0 ? BWD_NBUF - 1 : buf - 1), hb ? 0 : 32);   // sub-tile u-1
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int db = 0; db < 4; ++db) {
+                acc[db][0] = mma(ta[ks][db], xf[0][ks], acc[db][0]);
+                acc[db][1] = mma(ta[ks][db], xf[1][ks], acc[db][1]);
+            }
+        // fragments for the next iteration: row-wise of sub-tile u+2, transposed of sub-tile u
+        load_nat(nbuf, 32 * hb);
+        if (PREFETCH_TR) load_tr(buf, 32 * hb);
+#pragma unroll
+        for (int kc = 0; kc < 2; ++kc) {
+            f32x16 w;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float p = fast_exp2(fmaf(x[kc][r], c, -lr[r >> 2][r & 3]));
+                w[r] = IS_DK ? p * (y[kc][r] - dr[r >> 2][r & 3]) : p;
+            }
+            xf[kc][0] = pack_frag(w, 0);
+            xf[kc][1] = pack_frag(w, 8);
+        }
+        // consumed only by the next iteration: anchored here so that their instructions stay in
+        // this block, next to the matrix-core work
+#pragma unroll
+        for (int kc = 0; kc < 2; ++kc) asm volatile("" : "+v"(xf[kc][0]), "+v"(xf[kc][1]));
+#pragma unroll
+        for (int t8 = 0; t8 < 8; ++t8) {
+            asm volatile("" : "+v"(qa[t8]));
+            if (IS_DK) asm volatile("" : "+v"(ga[t8]));
+        }
+        if (PREFETCH_TR) {
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                for (int db = 0; db < 4; ++db) asm volatile("" : "+v"(ta[ks][db]));
+        }
+    };
+
+    issue(0, 0);
+    __syncthreads();
+    issue(min(1, nT - 1), 1);
+    pin();
+    load_nat(0, 0);
+    scores();                 // sub-tile 0
+    load_nat(0, 32);          // row-wise fragments of sub-tile 1
+    if (PREFETCH_TR) load_tr(0, 0);   // placeholder for "sub-tile -1": multiplied by xf = 0
+    // Three LDS buffers, streamed tile T in buffer T % 3.  The one barrier per tile opens the
+    // iteration of the tile's first sub-tile: it publishes tile T+1 and retires tile T-1's buffer,
+    // which then receives tile T+2.
+    int buf = 0;
+    for (int T = 0; T < nT; ++T) {
+        const int nbuf = buf + 1 == BWD_NBUF ? 0 : buf + 1;
+        __syncthreads();
+        issue(min(T + 2, nT - 1), nbuf + 1 == BWD_NBUF ? 0 : nbuf + 1);
+        stage(T, 0, buf, nbuf);
+        stage(T, 1, buf, nbuf);
+        buf = nbuf;
+    }
+    if (!PREFETCH_TR) load_tr(buf == 0 ? BWD_NBUF - 1 : buf - 1, 32);
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)      // drain: the last sub-tile's contribution
+#pragma unroll
+        for (int db = 0; db < 4; ++db) {
+            acc[db][0] = mma(ta[ks][db], xf[0][ks], acc[db][0]);
+            acc[db][1] = mma(ta[ks][db], xf[1][ks], acc[db][1]);
+        }
+    const float mul = IS_DK ? scale : 1.f;
+#pragma unroll
+    for (int kc = 0; kc < 2; ++kc) {
+        const int key = wkey0 + 32 * kc + lc;
+        f32x16 col[4] = {acc[0][kc], acc[1][kc], acc[2][kc], acc[3][kc]};
+        if (pre)
+            store_rows_f32(col, key < P ? part + ((static_cast<size_t>(b) * Hkv + hk) * P + key) * HD : nullptr, lg, mul);
+        else
+            store_rows_bf16(col, key < S ? out_own + ((static_cast<size_t>(b) * S + key) * Hkv + hk) * HD : nullptr, lg, mul);
+    }
+}
+
+// First-generation key-stationary kernel (two-stage pipeline, fragments fetched where used);
+// still serves dK, whose register budget does not admit the deeper pipeline below.
+// One workgroup = 256 keys of one (sequence, KV head): a block of prefix slots, or a block of the
+// sequence's own tokens.  It streams the queries that see those keys: all tokens of all heads of
+// the group for prefix slots, tokens at or after the block for own keys.
+template <bool IS_DK>
+__global__ __launch_bounds__(256, 1) void attn_bwd_kstat_v1_kernel(
+    const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
+    const bf16_t* __restrict__ zk, const bf16_t* __restrict__ zv, const bf16_t* __restrict__ d_o,
+    const float* __restrict__ lse2, const float* __restrict__ delta, bf16_t* __restrict__ out_own,
+    float* __restrict__ part, int B, int S, int Hq, int Hkv, int P, float c, float scale) {
+    __shared__ KsSmem sm;
+    const int G = Hq / Hkv;
+    const int nPb = (P + BWD_WG_ROWS - 1) / BWD_WG_ROWS, nOb = (S + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
+    const int nKb = nPb + nOb;
+    int id = blockIdx.x;
+    const int hk = id % Hkv; id /= Hkv;
+    const int kb = id % nKb;
+    const int b = id / nKb;
+    const bool pre = kb < nPb;
+    const int key0 = (pre ? kb : kb - nPb) * BWD_WG_ROWS;
+    const int nkeys = pre ? P : S;
+    const int lane = threadIdx.x & 63, lg = lane >> 5, lc = lane & 31;
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wkey0 = key0 + 64 * wv;
+
+    // this wavefront's 64 keys as B operands: column = key, k = head element
     bf16x8 kf[2][8], vf[2][8];
 #pragma unroll
     for (int kc = 0; kc < 2; ++kc) {
@@ -471,7 +728,7 @@ int launch_attn_bwd_mfma(const cart_attn_desc& d, float scale, const void* q, co
     trace_mark(st);
     const int nKb = (d.P + BWD_WG_ROWS - 1) / BWD_WG_ROWS + (d.S + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
     const unsigned kgrid = static_cast<unsigned>(static_cast<long>(nKb) * d.B * d.Hkv);
-    hipLaunchKernelGGL(attn_bwd_kstat_kernel<true>, dim3(kgrid), dim3(256), 0, st, Q, K, V, ZK, ZV, DO, lse2,
+    hipLaunchKernelGGL(attn_bwd_kstat_v1_kernel<true>, dim3(kgrid), dim3(256), 0, st, Q, K, V, ZK, ZV, DO, lse2,
                        delta, static_cast<bf16_t*>(dk), part_k, d.B, d.S, d.Hq, d.Hkv, d.P, c, scale);
     trace_mark(st);
     hipLaunchKernelGGL(attn_bwd_kstat_kernel<false>, dim3(kgrid), dim3(256), 0, st, Q, K, V, ZK, ZV, DO, lse2,
