@@ -81,9 +81,13 @@ __device__ __forceinline__ void store_rows_f32(const f32x16 (&acc)[4], float* ro
 // =================================================================================================
 // dQ: queries stationary
 // =================================================================================================
+// four buffers: the transposed K fragments of a tile's last sub-tile are fetched one iteration
+// after the tile's other reads, so a tile's buffer is retired one tile later than in the other
+// kernels
+constexpr int DQ_NBUF = 4;
 struct DqSmem {
-    char k[BWD_NBUF][BWD_TILE_B];
-    char v[BWD_NBUF][BWD_TILE_B];
+    char k[DQ_NBUF][BWD_TILE_B];
+    char v[DQ_NBUF][BWD_TILE_B];
 };
 
 __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
@@ -104,7 +108,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int q0 = qt * BWD_WG_ROWS, wrow0 = q0 + 64 * wv;
 
-    bf16x8 qf[2][8], gf[2][8];     // B operands: column = query, k = head element
+    u32x4 qf[2][8], gf[2][8];     // B operands: column = query, k = head element
     float l2[2], dl[2];
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb) {
@@ -113,13 +117,15 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
         const size_t row = (static_cast<size_t>(b) * S + qi) * Hq + h;
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
-            qf[cb][t] = *reinterpret_cast<const bf16x8*>(q + row * HD + 8 * lg + 16 * t);
-            gf[cb][t] = *reinterpret_cast<const bf16x8*>(d_o + row * HD + 8 * lg + 16 * t);
+            qf[cb][t] = *reinterpret_cast<const u32x4*>(q + row * HD + 8 * lg + 16 * t);
+            gf[cb][t] = *reinterpret_cast<const u32x4*>(d_o + row * HD + 8 * lg + 16 * t);
         }
         const size_t st = (static_cast<size_t>(b) * Hq + h) * S + qi;
         l2[cb] = lse2[st];
         dl[cb] = delta[st];
     }
+#define QF_(cb, t) __builtin_bit_cast(bf16x8, qf[cb][t])
+#define GF_(cb, t) __builtin_bit_cast(bf16x8, gf[cb][t])
 
     const int nPt = (P + BWD_TILE - 1) / BWD_TILE;
     const int own_end = min(S, q0 + BWD_WG_ROWS);
@@ -149,26 +155,16 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[db][cb][r] = 0.f;
     f32x16 s[2], dp[2];
+    bf16x8 dsf[2][2];     // dS^T of sub-tile u-1 as B-operand fragments [query block][k-step]
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) dsf[cb][ks] = bf16x8{};
 
-    auto scores = [&](const char* kt, const char* vt, int kr0) __attribute__((always_inline)) {
-#pragma unroll
-        for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) { s[cb][r] = 0.f; dp[cb][r] = 0.f; }
-#pragma unroll
-        for (int t8 = 0; t8 < 8; ++t8) {
-            bf16x8 a = lds_frag_n(kt, kr0 + lc, 16 * t8 + 8 * lg);
-            s[0] = mma(a, qf[0][t8], s[0]);
-            s[1] = mma(a, qf[1][t8], s[1]);
-            bf16x8 a2 = lds_frag_n(vt, kr0 + lc, 16 * t8 + 8 * lg);
-            dp[0] = mma(a2, gf[0][t8], dp[0]);
-            dp[1] = mma(a2, gf[1][t8], dp[1]);
-        }
-    };
     auto needs_mask = [&](int t, int hb) __attribute__((always_inline)) {
         return t < nPt ? (t * BWD_TILE + 32 * hb + 32 > P) : ((t - nPt) * BWD_TILE + 32 * hb + 31 > wrow0);
     };
-    auto mask = [&](int t, int hb) __attribute__((always_inline)) {
+    auto mask = [&](f32x16 (&x)[2], int t, int hb) __attribute__((always_inline)) {
         const bool own = t >= nPt;
         const int j0 = (own ? t - nPt : t) * BWD_TILE + 32 * hb;
 #pragma unroll
@@ -176,51 +172,129 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
             const int thr = (own ? wrow0 + 32 * cb + lc : P - 1) - j0 - 4 * lg;
 #pragma unroll
             for (int r = 0; r < 16; ++r)
-                if (8 * (r >> 2) + (r & 3) > thr) s[cb][r] = NEG_BIG;
+                if (8 * (r >> 2) + (r & 3) > thr) x[cb][r] = NEG_BIG;
+        }
+    };
+#ifndef CART_DQ_PIN_Q
+#define CART_DQ_PIN_Q 1
+#endif
+#ifndef CART_DQ_PREFETCH_V
+#define CART_DQ_PREFETCH_V 1
+#endif
+    auto pin = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+#if CART_DQ_PIN_Q
+                asm volatile("" : "+a"(qf[cb][t]));
+#endif
+            }
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int cb = 0; cb < 2; ++cb) asm volatile("" : "+a"(acc[db][cb]));
+    };
+    // row-wise K (and V) fragments of sub-tile u+1 are fetched one iteration ahead (loop-carried)
+    bf16x8 ka[8], va[8];
+    auto load_nat = [&](int buf, int r0, bool with_v) __attribute__((always_inline)) {
+#pragma unroll
+        for (int t8 = 0; t8 < 8; ++t8) {
+            ka[t8] = lds_frag_n(sm.k[0] + buf * BWD_TILE_B, r0 + lc, 16 * t8 + 8 * lg);
+            if (with_v) va[t8] = lds_frag_n(sm.v[0] + buf * BWD_TILE_B, r0 + lc, 16 * t8 + 8 * lg);
+        }
+    };
+    auto scores = [&](int vbuf, int vr0) __attribute__((always_inline)) {
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { s[cb][r] = 0.f; dp[cb][r] = 0.f; }
+#pragma unroll
+        for (int t8 = 0; t8 < 8; ++t8) {
+            s[0] = mma(ka[t8], QF_(0, t8), s[0]);
+            s[1] = mma(ka[t8], QF_(1, t8), s[1]);
+#if CART_DQ_PREFETCH_V
+            const bf16x8 a2 = va[t8];
+#else
+            const bf16x8 a2 = lds_frag_n(sm.v[0] + vbuf * BWD_TILE_B, vr0 + lc, 16 * t8 + 8 * lg);
+#endif
+            dp[0] = mma(a2, GF_(0, t8), dp[0]);
+            dp[1] = mma(a2, GF_(1, t8), dp[1]);
+        }
+    };
+    // Iteration u (sub-tile hb of tile t in buffer buf; nbuf holds tile t+1).  On entry: s, dp =
+    // scores of sub-tile u; ka (va) = row-wise fragments of sub-tile u+1; dsf = dS^T(u-1).
+    auto stage = [&](int t, int hb, int buf, int nbuf) __attribute__((always_inline)) {
+        f32x16 x[2] = {s[0], s[1]};
+        f32x16 y[2] = {dp[0], dp[1]};
+        if (needs_mask(t, hb)) mask(x, t, hb);
+        pin();
+        // matrix cores: scores of sub-tile u+1, dQ^T += K^T(u-1) dS^T(u-1)
+        scores(hb ? nbuf : buf, hb ? 0 : 32);
+        // (the very first iteration has no predecessor: it multiplies tile 0 by dS = 0)
+        const char* kt_prev = sm.k[0] + ((hb || t == 0) ? buf : ((buf + DQ_NBUF - 1) & (DQ_NBUF - 1))) * BWD_TILE_B;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int db = 0; db < 4; ++db) {
+                const bf16x8 a = lds_frag_t(kt_prev, (hb ? 0 : 32) + 16 * ks, 32 * db, lane);
+                acc[db][0] = mma(a, dsf[0][ks], acc[db][0]);
+                acc[db][1] = mma(a, dsf[1][ks], acc[db][1]);
+            }
+        // row-wise fragments of sub-tile u+2
+        load_nat(nbuf, 32 * hb, CART_DQ_PREFETCH_V);
+        // vector ALU: dS^T of sub-tile u
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) {
+            f32x16 w;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float p = fast_exp2(fmaf(x[cb][r], c, -l2[cb]));
+                w[r] = p * (y[cb][r] - dl[cb]);
+            }
+            dsf[cb][0] = pack_frag(w, 0);
+            dsf[cb][1] = pack_frag(w, 8);
+        }
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) asm volatile("" : "+v"(dsf[cb][0]), "+v"(dsf[cb][1]));
+#pragma unroll
+        for (int t8 = 0; t8 < 8; ++t8) {
+            asm volatile("" : "+v"(ka[t8]));
+#if CART_DQ_PREFETCH_V
+            asm volatile("" : "+v"(va[t8]));
+#endif
         }
     };
 
     issue(0, 0);
     __syncthreads();
     issue(min(1, nT - 1), 1);
-    scores(sm.k[0], sm.v[0], 0);
-    if (needs_mask(0, 0)) mask(0, 0);
-    const int nU = 2 * nT;
+    pin();
+    load_nat(0, 0, CART_DQ_PREFETCH_V);
+    scores(0, 0);                          // sub-tile 0
+    load_nat(0, 32, CART_DQ_PREFETCH_V);   // sub-tile 1
+    // Tile t lives in buffer t % 4.  The one barrier per tile opens the iteration of the tile's
+    // first sub-tile: it publishes tile t+1 and retires tile t-2's buffer (tile t-1's transposed
+    // K is still read in this iteration), which then receives tile t+2.
     int buf = 0;
-    for (int u = 0; u < nU; ++u) {
-        const int hb = u & 1, t = u >> 1;
-        const int nbuf = buf + 1 == BWD_NBUF ? 0 : buf + 1;
-        const char* kt = sm.k[0] + buf * BWD_TILE_B;
-        const int nb = hb ? nbuf : buf;
-        bf16x8 dsf[2][2];   // [query block][k-step]: dS^T as B-operand fragments
-#pragma unroll
-        for (int cb = 0; cb < 2; ++cb) {
-            f32x16 x;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float p = fast_exp2(fmaf(s[cb][r], c, -l2[cb]));
-                x[r] = p * (dp[cb][r] - dl[cb]);
-            }
-            dsf[cb][0] = pack_frag(x, 0);
-            dsf[cb][1] = pack_frag(x, 8);
-        }
-        scores(sm.k[0] + nb * BWD_TILE_B, sm.v[0] + nb * BWD_TILE_B, hb ? 0 : 32);
+    for (int t = 0; t < nT; ++t) {
+        const int nbuf = (buf + 1) & (DQ_NBUF - 1);
+        __syncthreads();
+        issue(min(t + 2, nT - 1), (buf + 2) & (DQ_NBUF - 1));
+        stage(t, 0, buf, nbuf);
+        stage(t, 1, buf, nbuf);
+        buf = nbuf;
+    }
+    {   // drain: dQ^T += K^T dS^T of the last sub-tile
+        const char* kt_prev = sm.k[0] + ((buf + DQ_NBUF - 1) & (DQ_NBUF - 1)) * BWD_TILE_B;
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
             for (int db = 0; db < 4; ++db) {
-                bf16x8 a = lds_frag_t(kt, 32 * hb + 16 * ks, 32 * db, lane);
+                const bf16x8 a = lds_frag_t(kt_prev, 32 + 16 * ks, 32 * db, lane);
                 acc[db][0] = mma(a, dsf[0][ks], acc[db][0]);
                 acc[db][1] = mma(a, dsf[1][ks], acc[db][1]);
             }
-        const int tn = (u + 1) >> 1, hn = (u + 1) & 1;
-        if (u + 1 < nU && needs_mask(tn, hn)) mask(tn, hn);
-        if (!hb) {
-            __syncthreads();
-            issue(min(t + 2, nT - 1), nbuf + 1 == BWD_NBUF ? 0 : nbuf + 1);
-        } else {
-            buf = nbuf;
-        }
     }
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb) {
@@ -349,8 +423,8 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
 #ifndef CART_DK_PREFETCH_TR
 #define CART_DK_PREFETCH_TR 0
 #endif
-    constexpr bool PIN_K = !IS_DK || CART_DK_PIN_K;
-    constexpr bool PREFETCH_TR = !IS_DK || CART_DK_PREFETCH_TR;
+    constexpr bool PIN_K = true;
+    constexpr bool PREFETCH_TR = true;   // required: a tile's buffer is retired right after its last sub-tile
     auto pin = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int kc = 0; kc < 2; ++kc)
