@@ -179,7 +179,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
 #define CART_DQ_PIN_Q 1
 #endif
 #ifndef CART_DQ_PREFETCH_V
-#define CART_DQ_PREFETCH_V 1
+#define CART_DQ_PREFETCH_V 0
 #endif
     auto pin = [&]() __attribute__((always_inline)) {
 #pragma unroll
@@ -307,11 +307,16 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
 // =================================================================================================
 // dK / dV: keys stationary
 // =================================================================================================
+// The dV kernel fetches every LDS fragment one iteration ahead and needs three tile buffers.  The
+// dK kernel holds twice the stationary fragments (K and V) and twice the score accumulators, has
+// no registers left for prefetched fragments, reads them where used, and therefore retires a
+// tile's buffer one tile later: four buffers.
+template <int NBUF>
 struct KsSmem {
-    char q[BWD_NBUF][BWD_TILE_B];
-    char g[BWD_NBUF][BWD_TILE_B];
-    float l2[BWD_NBUF][BWD_TILE];
-    float dl[BWD_NBUF][BWD_TILE];
+    char q[NBUF][BWD_TILE_B];
+    char g[NBUF][BWD_TILE_B];
+    float l2[NBUF][BWD_TILE];
+    float dl[NBUF][BWD_TILE];
 };
 
 // One workgroup = 256 keys of one (sequence, KV head): a block of prefix slots, or a block of the
@@ -323,7 +328,9 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
     const bf16_t* __restrict__ zk, const bf16_t* __restrict__ zv, const bf16_t* __restrict__ d_o,
     const float* __restrict__ lse2, const float* __restrict__ delta, bf16_t* __restrict__ out_own,
     float* __restrict__ part, int B, int S, int Hq, int Hkv, int P, float c, float scale) {
-    __shared__ KsSmem sm;
+    constexpr int NBUF = IS_DK ? 4 : 3;
+    constexpr bool PREFETCH = !IS_DK;
+    __shared__ KsSmem<NBUF> sm;
     const int G = Hq / Hkv;
     const int nPb = (P + BWD_WG_ROWS - 1) / BWD_WG_ROWS, nOb = (S + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
     const int nKb = nPb + nOb;
@@ -417,14 +424,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
         }
     };
     // the stationary fragments live in accumulation registers (read directly as B operands)
-#ifndef CART_DK_PIN_K
-#define CART_DK_PIN_K 1
-#endif
-#ifndef CART_DK_PREFETCH_TR
-#define CART_DK_PREFETCH_TR 0
-#endif
     constexpr bool PIN_K = true;
-    constexpr bool PREFETCH_TR = true;   // required: a tile's buffer is retired right after its last sub-tile
     auto pin = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int kc = 0; kc < 2; ++kc)
@@ -441,12 +441,11 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
 
     // LDS -> register fragments run one iteration ahead of their use (loop-carried): row-wise Q
     // (and dO) of sub-tile u+1, transposed dO (or Q) of sub-tile u-1
-    bf16x8 qa[8], ga[8], ta[2][4];
+    bf16x8 qa[8], ta[2][4];
     auto load_nat = [&](int buf, int r0) __attribute__((always_inline)) {
 #pragma unroll
         for (int t8 = 0; t8 < 8; ++t8) {
             qa[t8] = lds_frag_n(sm.q[0] + buf * BWD_TILE_B, r0 + lc, 16 * t8 + 8 * lg);
-            if (IS_DK) ga[t8] = lds_frag_n(sm.g[0] + buf * BWD_TILE_B, r0 + lc, 16 * t8 + 8 * lg);
         }
     };
     auto load_tr = [&](int buf, int r0) __attribute__((always_inline)) {
@@ -456,18 +455,22 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
 #pragma unroll
             for (int db = 0; db < 4; ++db) ta[ks][db] = lds_frag_t(at, r0 + 16 * ks, 32 * db, lane);
     };
-    auto scores = [&]() __attribute__((always_inline)) {
+    // scores of one sub-tile: from the prefetched fragments, or (dK) straight from LDS buffer
+    // nb, rows r0..
+    auto scores = [&](int nb, int r0) __attribute__((always_inline)) {
 #pragma unroll
         for (int kc = 0; kc < 2; ++kc)
 #pragma unroll
             for (int r = 0; r < 16; ++r) { s[kc][r] = 0.f; if (IS_DK) dp[kc][r] = 0.f; }
 #pragma unroll
         for (int t8 = 0; t8 < 8; ++t8) {
-            s[0] = mma(qa[t8], KF_(0, t8), s[0]);
-            s[1] = mma(qa[t8], KF_(1, t8), s[1]);
+            const bf16x8 a = PREFETCH ? qa[t8] : lds_frag_n(sm.q[0] + nb * BWD_TILE_B, r0 + lc, 16 * t8 + 8 * lg);
+            s[0] = mma(a, KF_(0, t8), s[0]);
+            s[1] = mma(a, KF_(1, t8), s[1]);
             if (IS_DK) {
-                dp[0] = mma(ga[t8], VF_(0, t8), dp[0]);
-                dp[1] = mma(ga[t8], VF_(1, t8), dp[1]);
+                const bf16x8 a2 = lds_frag_n(sm.g[0] + nb * BWD_TILE_B, r0 + lc, 16 * t8 + 8 * lg);
+                dp[0] = mma(a2, VF_(0, t8), dp[0]);
+                dp[1] = mma(a2, VF_(1, t8), dp[1]);
             }
         }
     };
@@ -482,15 +485,10 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
         if (IS_DK) { y[0] = dp[0]; y[1] = dp[1]; }
         if (needs_mask(T, hb)) mask(x, T, hb);
         pin();
-        // per-row lse2 / delta of this sub-tile: rows 8 j + 4 g + (0..3)
-        f32x4 lr[4], dr[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            lr[j] = *reinterpret_cast<const f32x4*>(&sm.l2[buf][32 * hb + 8 * j + 4 * lg]);
-            if (IS_DK) dr[j] = *reinterpret_cast<const f32x4*>(&sm.dl[buf][32 * hb + 8 * j + 4 * lg]);
-        }
-        scores();
-        if (!PREFETCH_TR) load_tr(hb ? buf : (buf == 0 ? BWD_NBUF - 1 : buf - 1), hb ? 0 : 32);   // sub-tile u-1
+        scores(hb ? nbuf : buf, hb ? 0 : 32);
+        // (dK: transposed fragments of sub-tile u-1 read here; the very first iteration has no
+        // predecessor and multiplies tile 0 by xf = 0)
+        if (!PREFETCH) load_tr((hb || T == 0) ? buf : (buf + NBUF - 1) % NBUF, hb ? 0 : 32);
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
@@ -499,29 +497,39 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
                 acc[db][1] = mma(ta[ks][db], xf[1][ks], acc[db][1]);
             }
         // fragments for the next iteration: row-wise of sub-tile u+2, transposed of sub-tile u
-        load_nat(nbuf, 32 * hb);
-        if (PREFETCH_TR) load_tr(buf, 32 * hb);
+        if (PREFETCH) {
+            load_nat(nbuf, 32 * hb);
+            load_tr(buf, 32 * hb);
+        }
+        // per-row lse2 / delta of this sub-tile (rows 8 j + 4 g + (0..3)) are read from LDS four
+        // rows at a time, right where they are used
+        f32x16 w[2];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const f32x4 lr = *reinterpret_cast<const f32x4*>(&sm.l2[buf][32 * hb + 8 * j + 4 * lg]);
+            f32x4 dr = {0.f, 0.f, 0.f, 0.f};
+            if (IS_DK) dr = *reinterpret_cast<const f32x4*>(&sm.dl[buf][32 * hb + 8 * j + 4 * lg]);
+#pragma unroll
+            for (int kc = 0; kc < 2; ++kc)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int r = 4 * j + e;
+                    const float p = fast_exp2(fmaf(x[kc][r], c, -lr[e]));
+                    w[kc][r] = IS_DK ? p * (y[kc][r] - dr[e]) : p;
+                }
+        }
 #pragma unroll
         for (int kc = 0; kc < 2; ++kc) {
-            f32x16 w;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float p = fast_exp2(fmaf(x[kc][r], c, -lr[r >> 2][r & 3]));
-                w[r] = IS_DK ? p * (y[kc][r] - dr[r >> 2][r & 3]) : p;
-            }
-            xf[kc][0] = pack_frag(w, 0);
-            xf[kc][1] = pack_frag(w, 8);
+            xf[kc][0] = pack_frag(w[kc], 0);
+            xf[kc][1] = pack_frag(w[kc], 8);
         }
         // consumed only by the next iteration: anchored here so that their instructions stay in
         // this block, next to the matrix-core work
 #pragma unroll
         for (int kc = 0; kc < 2; ++kc) asm volatile("" : "+v"(xf[kc][0]), "+v"(xf[kc][1]));
+        if (PREFETCH) {
 #pragma unroll
-        for (int t8 = 0; t8 < 8; ++t8) {
-            asm volatile("" : "+v"(qa[t8]));
-            if (IS_DK) asm volatile("" : "+v"(ga[t8]));
-        }
-        if (PREFETCH_TR) {
+            for (int t8 = 0; t8 < 8; ++t8) asm volatile("" : "+v"(qa[t8]));
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
@@ -533,23 +541,25 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
     __syncthreads();
     issue(min(1, nT - 1), 1);
     pin();
-    load_nat(0, 0);
-    scores();                 // sub-tile 0
-    load_nat(0, 32);          // row-wise fragments of sub-tile 1
-    if (PREFETCH_TR) load_tr(0, 0);   // placeholder for "sub-tile -1": multiplied by xf = 0
-    // Three LDS buffers, streamed tile T in buffer T % 3.  The one barrier per tile opens the
-    // iteration of the tile's first sub-tile: it publishes tile T+1 and retires tile T-1's buffer,
-    // which then receives tile T+2.
+    if (PREFETCH) load_nat(0, 0);
+    scores(0, 0);             // sub-tile 0
+    if (PREFETCH) {
+        load_nat(0, 32);      // row-wise fragments of sub-tile 1
+        load_tr(0, 0);        // placeholder for "sub-tile -1": multiplied by xf = 0
+    }
+    // Streamed tile T lives in buffer T % NBUF.  The one barrier per tile opens the iteration of
+    // the tile's first sub-tile: it publishes tile T+1 and retires the buffer of the oldest tile
+    // no longer read (T-1 with prefetched fragments, T-2 without), which receives tile T+2.
     int buf = 0;
     for (int T = 0; T < nT; ++T) {
-        const int nbuf = buf + 1 == BWD_NBUF ? 0 : buf + 1;
+        const int nbuf = (buf + 1) % NBUF;
         __syncthreads();
-        issue(min(T + 2, nT - 1), nbuf + 1 == BWD_NBUF ? 0 : nbuf + 1);
+        issue(min(T + 2, nT - 1), (buf + 2) % NBUF);
         stage(T, 0, buf, nbuf);
         stage(T, 1, buf, nbuf);
         buf = nbuf;
     }
-    if (!PREFETCH_TR) load_tr(buf == 0 ? BWD_NBUF - 1 : buf - 1, 32);
+    if (!PREFETCH) load_tr((buf + NBUF - 1) % NBUF, 32);
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks)      // drain: the last sub-tile's contribution
 #pragma unroll
@@ -569,6 +579,13 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
     }
 }
 
+struct KsSmemV1 {
+    char q[BWD_NBUF][BWD_TILE_B];
+    char g[BWD_NBUF][BWD_TILE_B];
+    float l2[BWD_NBUF][BWD_TILE];
+    float dl[BWD_NBUF][BWD_TILE];
+};
+
 // First-generation key-stationary kernel (two-stage pipeline, fragments fetched where used);
 // still serves dK, whose register budget does not admit the deeper pipeline below.
 // One workgroup = 256 keys of one (sequence, KV head): a block of prefix slots, or a block of the
@@ -580,7 +597,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_v1_kernel(
     const bf16_t* __restrict__ zk, const bf16_t* __restrict__ zv, const bf16_t* __restrict__ d_o,
     const float* __restrict__ lse2, const float* __restrict__ delta, bf16_t* __restrict__ out_own,
     float* __restrict__ part, int B, int S, int Hq, int Hkv, int P, float c, float scale) {
-    __shared__ KsSmem sm;
+    __shared__ KsSmemV1 sm;
     const int G = Hq / Hkv;
     const int nPb = (P + BWD_WG_ROWS - 1) / BWD_WG_ROWS, nOb = (S + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
     const int nKb = nPb + nOb;
@@ -802,7 +819,7 @@ int launch_attn_bwd_mfma(const cart_attn_desc& d, float scale, const void* q, co
     trace_mark(st);
     const int nKb = (d.P + BWD_WG_ROWS - 1) / BWD_WG_ROWS + (d.S + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
     const unsigned kgrid = static_cast<unsigned>(static_cast<long>(nKb) * d.B * d.Hkv);
-    hipLaunchKernelGGL(attn_bwd_kstat_v1_kernel<true>, dim3(kgrid), dim3(256), 0, st, Q, K, V, ZK, ZV, DO, lse2,
+    hipLaunchKernelGGL(attn_bwd_kstat_kernel<true>, dim3(kgrid), dim3(256), 0, st, Q, K, V, ZK, ZV, DO, lse2,
                        delta, static_cast<bf16_t*>(dk), part_k, d.B, d.S, d.Hq, d.Hkv, d.P, c, scale);
     trace_mark(st);
     hipLaunchKernelGGL(attn_bwd_kstat_kernel<false>, dim3(kgrid), dim3(256), 0, st, Q, K, V, ZK, ZV, DO, lse2,
