@@ -84,25 +84,47 @@ __device__ __forceinline__ bf16x8 pack_frag(const f32x16& s, int r0) {
     return __builtin_bit_cast(bf16x8, w);
 }
 
-// Streams a ROWS x 128 bf16 tile from global memory straight into LDS (no register staging)
-// with the 4 wavefronts of a 256-thread workgroup.  One global_load_lds_dwordx4 moves 64 chunks
-// of 16 bytes = 4 tile rows; lane i's chunk lands at (wave-uniform base) + 16 i, so the lane
-// fetches the logical chunk that belongs at that position under the swizzle.  row_ptr(r) returns
-// the global address of tile row r (callers clamp rows past the end onto a valid row; such
-// rows are masked out of the softmax, so their contents never reach a result).
-template <int ROWS, typename RowPtr>
-__device__ __forceinline__ void tile_load_async(char* tile, RowPtr row_ptr) {
+// ---- direct-to-LDS loads --------------------------------------------------------------------
+// The loads are written as inline assembly so that the wait for them sits where the pipeline
+// wants it (one s_waitcnt vmcnt(0) in front of the barrier that publishes the tile, a whole
+// iteration after the loads went out) and not in front of the next LDS read of any address.
+// M0 carries the wave-uniform LDS byte address; lane i's 16 (4) bytes land at M0 + 16 i (4 i).
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+    return static_cast<uint32_t>(reinterpret_cast<uintptr_t>((const __attribute__((address_space(3))) void*)p));
+}
+// base: wave-uniform global address; voff: per-lane unsigned byte offset from it
+__device__ __forceinline__ void dma16(const char* base, uint32_t voff, uint32_t lds) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(voff), "s"(base), "s"(lds) : "memory", "m0");
+}
+__device__ __forceinline__ void dma4(const char* base, uint32_t voff, uint32_t lds) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+                 :: "v"(voff), "s"(base), "s"(lds) : "memory", "m0");
+}
+// every direct-to-LDS load of this wavefront has landed
+__device__ __forceinline__ void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// Tile of ROWS rows x 256 bytes -> LDS (row r at 256 r, 16-byte chunks swizzled), cooperatively
+// by the 4 wavefronts of a 256-thread workgroup.  One load instruction moves 64 chunks = 4 tile
+// rows; lane i's chunk lands at (wave-uniform base) + 16 i, so the lane fetches the logical
+// chunk that belongs at that position under the swizzle.  Tile row r comes from tensor row
+// min(j0 + r, last) of a slice that starts at `base` with `pitch` bytes between rows (base, j0,
+// last, pitch wave-uniform; j0 <= last; rows past `last` repeat it and are masked by the
+// caller, so their contents never reach a result; 64 * pitch < 2^32).
+template <int ROWS>
+__device__ __forceinline__ void tile_load_async(char* tile, const char* base, int j0, int last, uint32_t pitch) {
     const int lane = threadIdx.x & 63;
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     constexpr int PER_WAVE = ROWS / 16;      // instructions per wavefront
+    const char* tb = base + static_cast<size_t>(j0) * pitch;
+    const int lim = last - j0;
+    const uint32_t lds0 = lds_addr(tile);
 #pragma unroll
     for (int i = 0; i < PER_WAVE; ++i) {
         const int r0 = (PER_WAVE * wv + i) * 4;
         const int r = r0 + (lane >> 4);
-        const char* src = row_ptr(r) + (((lane & 15) ^ swz(r)) << 4);
-        __builtin_amdgcn_global_load_lds(
-            (const __attribute__((address_space(1))) void*)src,
-            (__attribute__((address_space(3))) void*)(tile + r0 * ROW_B), 16, 0, 0);
+        const uint32_t voff = static_cast<uint32_t>(min(r, lim)) * pitch + (((lane & 15) ^ swz(r)) << 4);
+        dma16(tb, voff, lds0 + r0 * ROW_B);
     }
 }
 

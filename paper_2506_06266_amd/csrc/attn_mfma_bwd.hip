@@ -140,11 +140,11 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
         const bool pre = t < nPt;
         const int j0 = (pre ? t : t - nPt) * BWD_TILE;
         const int last = (pre ? P : S) - 1;
-        const size_t pitch = pre ? static_cast<size_t>(ROW_B) : own_pitch;
+        const uint32_t pitch = pre ? static_cast<uint32_t>(ROW_B) : static_cast<uint32_t>(own_pitch);
         const char* kb = pre ? zk_b : k_b;
         const char* vb = pre ? zv_b : v_b;
-        tile_load_async<BWD_TILE>(sm.k[buf], [&](int r) { return kb + min(j0 + r, last) * pitch; });
-        tile_load_async<BWD_TILE>(sm.v[buf], [&](int r) { return vb + min(j0 + r, last) * pitch; });
+        tile_load_async<BWD_TILE>(sm.k[buf], kb, j0, last, pitch);
+        tile_load_async<BWD_TILE>(sm.v[buf], vb, j0, last, pitch);
     };
 
     f32x16 acc[4][2];   // dQ^T: [head-element block][query block]
@@ -267,6 +267,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
     };
 
     issue(0, 0);
+    dma_wait();
     __syncthreads();
     issue(min(1, nT - 1), 1);
     pin();
@@ -279,6 +280,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
     int buf = 0;
     for (int t = 0; t < nT; ++t) {
         const int nbuf = (buf + 1) & (DQ_NBUF - 1);
+        dma_wait();
         __syncthreads();
         issue(min(t + 2, nT - 1), (buf + 2) & (DQ_NBUF - 1));
         stage(t, 0, buf, nbuf);
@@ -374,14 +376,13 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
         const int h = hk * G + gi;
         const int i0 = qt * BWD_TILE;
         const size_t base = (static_cast<size_t>(b) * S * Hq + h) * ROW_B;
-        tile_load_async<BWD_TILE>(sm.q[buf], [&](int r) { return q_c + base + min(i0 + r, S - 1) * q_pitch; });
-        tile_load_async<BWD_TILE>(sm.g[buf], [&](int r) { return g_c + base + min(i0 + r, S - 1) * q_pitch; });
+        tile_load_async<BWD_TILE>(sm.q[buf], q_c + base, i0, S - 1, static_cast<uint32_t>(q_pitch));
+        tile_load_async<BWD_TILE>(sm.g[buf], g_c + base, i0, S - 1, static_cast<uint32_t>(q_pitch));
         // the tile's 64 lse2 / delta values: one 4-byte direct-to-LDS load per lane
         if (wv < 2) {
-            const float* src = (wv == 0 ? lse2 : delta) + (static_cast<size_t>(b) * Hq + h) * S + min(i0 + lane, S - 1);
+            const float* src = (wv == 0 ? lse2 : delta) + (static_cast<size_t>(b) * Hq + h) * S;
             float* dst = wv == 0 ? sm.l2[buf] : sm.dl[buf];
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                             (__attribute__((address_space(3))) void*)dst, 4, 0, 0);
+            dma4(reinterpret_cast<const char*>(src), static_cast<uint32_t>(min(i0 + lane, S - 1)) * 4u, lds_addr(dst));
         }
     };
     auto tile_i0 = [&](int T) __attribute__((always_inline)) {
@@ -538,6 +539,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
     };
 
     issue(0, 0);
+    dma_wait();
     __syncthreads();
     issue(min(1, nT - 1), 1);
     pin();
@@ -553,6 +555,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
     int buf = 0;
     for (int T = 0; T < nT; ++T) {
         const int nbuf = (buf + 1) % NBUF;
+        dma_wait();
         __syncthreads();
         issue(min(T + 2, nT - 1), (buf + 2) % NBUF);
         stage(T, 0, buf, nbuf);
@@ -567,191 +570,6 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
             acc[db][0] = mma(ta[ks][db], xf[0][ks], acc[db][0]);
             acc[db][1] = mma(ta[ks][db], xf[1][ks], acc[db][1]);
         }
-    const float mul = IS_DK ? scale : 1.f;
-#pragma unroll
-    for (int kc = 0; kc < 2; ++kc) {
-        const int key = wkey0 + 32 * kc + lc;
-        f32x16 col[4] = {acc[0][kc], acc[1][kc], acc[2][kc], acc[3][kc]};
-        if (pre)
-            store_rows_f32(col, key < P ? part + ((static_cast<size_t>(b) * Hkv + hk) * P + key) * HD : nullptr, lg, mul);
-        else
-            store_rows_bf16(col, key < S ? out_own + ((static_cast<size_t>(b) * S + key) * Hkv + hk) * HD : nullptr, lg, mul);
-    }
-}
-
-struct KsSmemV1 {
-    char q[BWD_NBUF][BWD_TILE_B];
-    char g[BWD_NBUF][BWD_TILE_B];
-    float l2[BWD_NBUF][BWD_TILE];
-    float dl[BWD_NBUF][BWD_TILE];
-};
-
-// First-generation key-stationary kernel (two-stage pipeline, fragments fetched where used);
-// still serves dK, whose register budget does not admit the deeper pipeline below.
-// One workgroup = 256 keys of one (sequence, KV head): a block of prefix slots, or a block of the
-// sequence's own tokens.  It streams the queries that see those keys: all tokens of all heads of
-// the group for prefix slots, tokens at or after the block for own keys.
-template <bool IS_DK>
-__global__ __launch_bounds__(256, 1) void attn_bwd_kstat_v1_kernel(
-    const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
-    const bf16_t* __restrict__ zk, const bf16_t* __restrict__ zv, const bf16_t* __restrict__ d_o,
-    const float* __restrict__ lse2, const float* __restrict__ delta, bf16_t* __restrict__ out_own,
-    float* __restrict__ part, int B, int S, int Hq, int Hkv, int P, float c, float scale) {
-    __shared__ KsSmemV1 sm;
-    const int G = Hq / Hkv;
-    const int nPb = (P + BWD_WG_ROWS - 1) / BWD_WG_ROWS, nOb = (S + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
-    const int nKb = nPb + nOb;
-    int id = blockIdx.x;
-    const int hk = id % Hkv; id /= Hkv;
-    const int kb = id % nKb;
-    const int b = id / nKb;
-    const bool pre = kb < nPb;
-    const int key0 = (pre ? kb : kb - nPb) * BWD_WG_ROWS;
-    const int nkeys = pre ? P : S;
-    const int lane = threadIdx.x & 63, lg = lane >> 5, lc = lane & 31;
-    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int wkey0 = key0 + 64 * wv;
-
-    // this wavefront's 64 keys as B operands: column = key, k = head element
-    bf16x8 kf[2][8], vf[2][8];
-#pragma unroll
-    for (int kc = 0; kc < 2; ++kc) {
-        const int key = min(wkey0 + 32 * kc + lc, nkeys - 1);
-        const size_t row = pre ? static_cast<size_t>(hk) * P + key
-                               : (static_cast<size_t>(b) * S + key) * Hkv + hk;
-        const bf16_t* kp = (pre ? zk : k) + row * HD + 8 * lg;
-        const bf16_t* vp = (pre ? zv : v) + row * HD + 8 * lg;
-#pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            kf[kc][t] = *reinterpret_cast<const bf16x8*>(kp + 16 * t);
-            if (IS_DK) vf[kc][t] = *reinterpret_cast<const bf16x8*>(vp + 16 * t);
-        }
-    }
-
-    const int nQtAll = (S + BWD_TILE - 1) / BWD_TILE;
-    const int qt0 = pre ? 0 : key0 / BWD_TILE;
-    const int nq = nQtAll - qt0;
-    const int nT = G * nq;            // query tiles streamed: head-major, token tiles inside
-    const char* q_c = reinterpret_cast<const char*>(q);
-    const char* g_c = reinterpret_cast<const char*>(d_o);
-    const size_t q_pitch = static_cast<size_t>(Hq) * ROW_B;
-
-    auto issue = [&](int T, int buf) __attribute__((always_inline)) {
-        const int gi = T / nq, qt = qt0 + T - gi * nq;
-        const int h = hk * G + gi;
-        const int i0 = qt * BWD_TILE;
-        const size_t base = (static_cast<size_t>(b) * S * Hq + h) * ROW_B;
-        tile_load_async<BWD_TILE>(sm.q[buf], [&](int r) { return q_c + base + min(i0 + r, S - 1) * q_pitch; });
-        tile_load_async<BWD_TILE>(sm.g[buf], [&](int r) { return g_c + base + min(i0 + r, S - 1) * q_pitch; });
-        // the tile's 64 lse2 / delta values: one 4-byte direct-to-LDS load per lane
-        if (wv < 2) {
-            const float* src = (wv == 0 ? lse2 : delta) + (static_cast<size_t>(b) * Hq + h) * S + min(i0 + lane, S - 1);
-            float* dst = wv == 0 ? sm.l2[buf] : sm.dl[buf];
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                             (__attribute__((address_space(3))) void*)dst, 4, 0, 0);
-        }
-    };
-    auto tile_i0 = [&](int T) __attribute__((always_inline)) {
-        const int gi = T / nq;
-        return (qt0 + T - gi * nq) * BWD_TILE;
-    };
-
-    f32x16 acc[4][2];   // dK^T or dV^T: [head-element block][key block]
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int kc = 0; kc < 2; ++kc)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[db][kc][r] = 0.f;
-    f32x16 s[2], dp[2];   // [key block]: rows = 32 queries of the sub-tile
-
-    auto scores = [&](const char* qt_, const char* gt_, int qr0) __attribute__((always_inline)) {
-#pragma unroll
-        for (int kc = 0; kc < 2; ++kc)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) { s[kc][r] = 0.f; if (IS_DK) dp[kc][r] = 0.f; }
-#pragma unroll
-        for (int t8 = 0; t8 < 8; ++t8) {
-            bf16x8 a = lds_frag_n(qt_, qr0 + lc, 16 * t8 + 8 * lg);
-            s[0] = mma(a, kf[0][t8], s[0]);
-            s[1] = mma(a, kf[1][t8], s[1]);
-            if (IS_DK) {
-                bf16x8 a2 = lds_frag_n(gt_, qr0 + lc, 16 * t8 + 8 * lg);
-                dp[0] = mma(a2, vf[0][t8], dp[0]);
-                dp[1] = mma(a2, vf[1][t8], dp[1]);
-            }
-        }
-    };
-    // a query row of the sub-tile is hidden from a key when it precedes it (own keys) or lies
-    // past the end of the sequence (clamped tile rows)
-    auto needs_mask = [&](int T, int hb) __attribute__((always_inline)) {
-        const int i0 = tile_i0(T) + 32 * hb;
-        return (!pre && i0 < wkey0 + 63) || (i0 + 32 > S);
-    };
-    auto mask = [&](int T, int hb) __attribute__((always_inline)) {
-        const int i0 = tile_i0(T) + 32 * hb;
-#pragma unroll
-        for (int kc = 0; kc < 2; ++kc) {
-            // row i0 + d_row(r, lg) is visible iff it is >= the lane's key (own) and < S
-            const int lo = (pre ? 0 : wkey0 + 32 * kc + lc) - i0 - 4 * lg;
-            const int hi = S - i0 - 4 * lg;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int rr = 8 * (r >> 2) + (r & 3);
-                if (rr < lo || rr >= hi) s[kc][r] = NEG_BIG;
-            }
-        }
-    };
-
-    issue(0, 0);
-    __syncthreads();
-    issue(min(1, nT - 1), 1);
-    scores(sm.q[0], sm.g[0], 0);
-    if (needs_mask(0, 0)) mask(0, 0);
-    const int nU = 2 * nT;
-    int buf = 0;
-    for (int u = 0; u < nU; ++u) {
-        const int hb = u & 1, T = u >> 1;
-        const int nbuf = buf + 1 == BWD_NBUF ? 0 : buf + 1;
-        const int nb = hb ? nbuf : buf;
-        const char* at = (IS_DK ? sm.q[0] : sm.g[0]) + buf * BWD_TILE_B;   // transposed-read operand
-        // per-row lse2 / delta of this sub-tile: rows 8 j + 4 g + (0..3)
-        f32x4 lr[4], dr[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            lr[j] = *reinterpret_cast<const f32x4*>(&sm.l2[buf][32 * hb + 8 * j + 4 * lg]);
-            if (IS_DK) dr[j] = *reinterpret_cast<const f32x4*>(&sm.dl[buf][32 * hb + 8 * j + 4 * lg]);
-        }
-        bf16x8 xf[2][2];   // [key block][k-step]: P or dS as B-operand fragments
-#pragma unroll
-        for (int kc = 0; kc < 2; ++kc) {
-            f32x16 x;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float p = fast_exp2(fmaf(s[kc][r], c, -lr[r >> 2][r & 3]));
-                x[r] = IS_DK ? p * (dp[kc][r] - dr[r >> 2][r & 3]) : p;
-            }
-            xf[kc][0] = pack_frag(x, 0);
-            xf[kc][1] = pack_frag(x, 8);
-        }
-        scores(sm.q[0] + nb * BWD_TILE_B, sm.g[0] + nb * BWD_TILE_B, hb ? 0 : 32);
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-            for (int db = 0; db < 4; ++db) {
-                bf16x8 a = lds_frag_t(at, 32 * hb + 16 * ks, 32 * db, lane);
-                acc[db][0] = mma(a, xf[0][ks], acc[db][0]);
-                acc[db][1] = mma(a, xf[1][ks], acc[db][1]);
-            }
-        const int Tn = (u + 1) >> 1, hn = (u + 1) & 1;
-        if (u + 1 < nU && needs_mask(Tn, hn)) mask(Tn, hn);
-        if (!hb) {
-            __syncthreads();
-            issue(min(T + 2, nT - 1), nbuf + 1 == BWD_NBUF ? 0 : nbuf + 1);
-        } else {
-            buf = nbuf;
-        }
-    }
     const float mul = IS_DK ? scale : 1.f;
 #pragma unroll
     for (int kc = 0; kc < 2; ++kc) {

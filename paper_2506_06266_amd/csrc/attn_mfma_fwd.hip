@@ -98,11 +98,11 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_mfma_kernel(
         const bool pre = t < nPt;
         const int j0 = (pre ? t : t - nPt) * FWD_BN;
         const int last = (pre ? P : S) - 1;
-        const size_t pitch = pre ? static_cast<size_t>(ROW_B) : own_pitch;
+        const uint32_t pitch = pre ? static_cast<uint32_t>(ROW_B) : static_cast<uint32_t>(own_pitch);
         const char* kb = pre ? zk_b : k_b;
         const char* vb = pre ? zv_b : v_b;
-        tile_load_async<FWD_BN>(sm.k[buf], [&](int r) { return kb + min(j0 + r, last) * pitch; });
-        tile_load_async<FWD_BN>(sm.v[buf], [&](int r) { return vb + min(j0 + r, last) * pitch; });
+        tile_load_async<FWD_BN>(sm.k[buf], kb, j0, last, pitch);
+        tile_load_async<FWD_BN>(sm.v[buf], vb, j0, last, pitch);
     };
     // does sub-tile (tile t, half hb) hold a key that some query of this wavefront must not see?
     auto needs_mask = [&](int t, int hb) __attribute__((always_inline)) {
@@ -219,6 +219,7 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_mfma_kernel(
     };
 
     issue(0, 0);
+    dma_wait();
     __syncthreads();
     issue(min(1, nT - 1), 1);
     {   // scores of sub-tile 0 and the softmax reference of every query: its maximum there
@@ -251,6 +252,7 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_mfma_kernel(
     int buf = 0;
     for (int t = 0; t < nT; ++t) {
         const int nbuf = buf + 1 == FWD_NBUF ? 0 : buf + 1;
+        dma_wait();
         __syncthreads();
         issue(min(t + 2, nT - 1), nbuf + 1 == FWD_NBUF ? 0 : nbuf + 1);
         stage(2 * t, buf, nbuf);

@@ -96,8 +96,8 @@ __global__ __launch_bounds__(256, 1) void decode_prefix_kernel(
     const char* zv_b = reinterpret_cast<const char*>(zv) + static_cast<size_t>(hk) * P * ROW_B;
     auto issue = [&](int t, int buf) __attribute__((always_inline)) {
         const int j0 = (t_lo + t) * DEC_BN;
-        tile_load_async<DEC_BN>(sm.k[buf], [&](int r) { return zk_b + static_cast<size_t>(min(j0 + r, P - 1)) * ROW_B; });
-        tile_load_async<DEC_BN>(sm.v[buf], [&](int r) { return zv_b + static_cast<size_t>(min(j0 + r, P - 1)) * ROW_B; });
+        tile_load_async<DEC_BN>(sm.k[buf], zk_b, j0, P - 1, ROW_B);
+        tile_load_async<DEC_BN>(sm.v[buf], zv_b, j0, P - 1, ROW_B);
     };
 
     f32x16 acc[4][2];
@@ -161,6 +161,7 @@ __global__ __launch_bounds__(256, 1) void decode_prefix_kernel(
     };
 
     issue(0, 0);
+    dma_wait();
     __syncthreads();
     issue(min(1, nT - 1), 1);
     scores(sm.k[0], 0);
@@ -197,6 +198,7 @@ __global__ __launch_bounds__(256, 1) void decode_prefix_kernel(
             }
         prepare((u + 1) >> 1, (u + 1) & 1, u + 1 < nU);
         if (!hb) {
+            dma_wait();
             __syncthreads();
             issue(min(t + 2, nT - 1), nbuf + 1 == DEC_NBUF ? 0 : nbuf + 1);
         } else {
@@ -253,19 +255,19 @@ __global__ __launch_bounds__(256, 2) void decode_own_kernel(
     }
     char* kt = sm[wv][0];
     char* vt = sm[wv][1];
-    const size_t pitch = static_cast<size_t>(Hkv) * ROW_B;
+    const uint32_t pitch = static_cast<uint32_t>(Hkv) * ROW_B;
     const char* k_b = reinterpret_cast<const char*>(k) + (static_cast<size_t>(t0 + k0) * Hkv + hk) * ROW_B;
     const char* v_b = reinterpret_cast<const char*>(v) + (static_cast<size_t>(t0 + k0) * Hkv + hk) * ROW_B;
     // 32 rows x 256 B = 8 direct-to-LDS loads of 4 rows each, per tensor, by this wavefront alone
     auto issue = [&](int j0) __attribute__((always_inline)) {
+        const size_t step = static_cast<size_t>(j0) * pitch;
+        const int lim = nk - 1 - j0;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int r = 4 * i + (lane >> 4);
-            const size_t off = static_cast<size_t>(min(j0 + r, nk - 1)) * pitch + (((lane & 15) ^ swz(r)) << 4);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(k_b + off),
-                                             (__attribute__((address_space(3))) void*)(kt + 4 * i * ROW_B), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(v_b + off),
-                                             (__attribute__((address_space(3))) void*)(vt + 4 * i * ROW_B), 16, 0, 0);
+            const uint32_t off = static_cast<uint32_t>(min(r, lim)) * pitch + (((lane & 15) ^ swz(r)) << 4);
+            dma16(k_b + step, off, lds_addr(kt) + 4 * i * ROW_B);
+            dma16(v_b + step, off, lds_addr(vt) + 4 * i * ROW_B);
         }
     };
 
@@ -280,7 +282,7 @@ __global__ __launch_bounds__(256, 2) void decode_own_kernel(
         // fragments of this step into registers, then the next step's loads overwrite the slot
         // while the matrix cores work
         bf16x8 ka[8], va[2][4];
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this step's direct-to-LDS loads have landed
+        dma_wait();   // this step's direct-to-LDS loads have landed
 #pragma unroll
         for (int t8 = 0; t8 < 8; ++t8) ka[t8] = lds_frag_n(kt, lc, 16 * t8 + 8 * lg);
 #pragma unroll
