@@ -30,6 +30,21 @@ __device__ __forceinline__ f32x16 mma(bf16x8 a, bf16x8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
+// The same product with the result in ordinary vector registers (the compiler's own choice for
+// the builtin is an accumulation register whenever a kernel uses those at all) and the B operand
+// read from an accumulation register.  The compiler does not know these are matrix-core
+// instructions: a consumer on the vector ALU must be at least 20 wait states away.
+__device__ __forceinline__ void mma_vd_zero(f32x16& d, bf16x8 a, const u32x4& b) {
+    asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b));
+}
+// d = a b + init (init in its own registers, left unchanged)
+__device__ __forceinline__ void mma_vd_first(f32x16& d, bf16x8 a, const u32x4& b, const f32x16& init) {
+    asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(d) : "v"(a), "a"(b), "v"(init));
+}
+__device__ __forceinline__ void mma_vd(f32x16& d, bf16x8 a, const u32x4& b) {
+    asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b));
+}
+
 // LDS tiles are [rows][128] bf16, 256 bytes per row, unpadded; the 16-byte chunk c of row r is
 // stored at chunk position c ^ swz(r).  swz is a bijection of r % 16 (16 consecutive rows read
 // at one logical chunk hit 16 distinct positions: row-wise ds_read_b128 is conflict-free) whose

@@ -67,61 +67,15 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_mfma_kernel(
         qi = qi < S ? qi : S - 1;
         const bf16_t* qp = q + ((static_cast<size_t>(b) * S + qi) * Hq + h) * HD + 8 * lg;
 #pragma unroll
-        for (int t = 0; t < 8; ++t) qraw[cb][t] = *reinterpret_cast<const u32x4*>(qp + 16 * t);
-    }
-#ifndef CART_PIN_Q
-#define CART_PIN_Q 1
-#endif
-    auto pin_q = [&]() __attribute__((always_inline)) {
-#if CART_PIN_Q
+        for (int t = 0; t < 8; ++t) {
+            // Q enters every product scaled by c = softmax_scale * log2(e), rounded to bf16 once
+            // here: the scores then come out of the matrix cores in log2 units
+            const u32x4 w = *reinterpret_cast<const u32x4*>(qp + 16 * t);
 #pragma unroll
-        for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-            for (int t = 0; t < 8; ++t) asm volatile("" : "+a"(qraw[cb][t]));
-#endif
-    };
-#define qf_(cb, t) __builtin_bit_cast(bf16x8, qraw[cb][t])
-    pin_q();
-
-    const int nPt = (P + FWD_BN - 1) / FWD_BN;
-    const int own_end = min(S, q0 + FWD_BM);
-    const int nT = nPt + (own_end + FWD_BN - 1) / FWD_BN;
-    const char* zk_b = reinterpret_cast<const char*>(zk) + static_cast<size_t>(hk) * P * ROW_B;
-    const char* zv_b = reinterpret_cast<const char*>(zv) + static_cast<size_t>(hk) * P * ROW_B;
-    const size_t own_pitch = static_cast<size_t>(Hkv) * ROW_B;
-    const char* k_b = reinterpret_cast<const char*>(k) + (static_cast<size_t>(b) * S * Hkv + hk) * ROW_B;
-    const char* v_b = reinterpret_cast<const char*>(v) + (static_cast<size_t>(b) * S * Hkv + hk) * ROW_B;
-
-    // tile t -> LDS buffer; branch-free (prefix or own is a scalar select).  Rows past the end
-    // of the prefix / the sequence are clamped onto the last valid row and masked later.
-    auto issue = [&](int t, int buf) __attribute__((always_inline)) {
-        const bool pre = t < nPt;
-        const int j0 = (pre ? t : t - nPt) * FWD_BN;
-        const int last = (pre ? P : S) - 1;
-        const uint32_t pitch = pre ? static_cast<uint32_t>(ROW_B) : static_cast<uint32_t>(own_pitch);
-        const char* kb = pre ? zk_b : k_b;
-        const char* vb = pre ? zv_b : v_b;
-        tile_load_async<FWD_BN>(sm.k[buf], kb, j0, last, pitch);
-        tile_load_async<FWD_BN>(sm.v[buf], vb, j0, last, pitch);
-    };
-    // does sub-tile (tile t, half hb) hold a key that some query of this wavefront must not see?
-    auto needs_mask = [&](int t, int hb) __attribute__((always_inline)) {
-        return t < nPt ? (t * FWD_BN + 32 * hb + 32 > P) : ((t - nPt) * FWD_BN + 32 * hb + 31 > wrow0);
-    };
-    // hidden entries of the scores of sub-tile (t, hb) -> NEG_BIG
-    auto mask = [&](f32x16 (&x)[2], int t, int hb) __attribute__((always_inline)) {
-        const bool own = t >= nPt;
-        const int j0 = (own ? t - nPt : t) * FWD_BN + 32 * hb;
-#pragma unroll
-        for (int cb = 0; cb < 2; ++cb) {
-            // key j0 + d_row(r, lg) is hidden when it exceeds the lane's last visible key
-            const int thr = (own ? wrow0 + 32 * cb + lc : P - 1) - j0 - 4 * lg;
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-                if (8 * (r >> 2) + (r & 3) > thr) x[cb][r] = NEG_BIG;
+            for (int i = 0; i < 4; ++i)
+                qraw[cb][t][i] = pack_bf16x2(__uint_as_float(w[i] << 16) * c, __uint_as_float(w[i] & 0xffff0000u) * c);
         }
-    };
-
+    }
     f32x16 acc[4][2];   // O^T: [head-element block][query block]
 #pragma unroll
     for (int db = 0; db < 4; ++db)
@@ -129,145 +83,253 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_mfma_kernel(
         for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[db][cb][r] = 0.f;
-    // keeps the O accumulators in accumulation registers across the loop's control flow
-    auto pin_acc = [&]() __attribute__((always_inline)) {
-#ifndef CART_PIN_ACC
-#define CART_PIN_ACC 1
-#endif
-#if CART_PIN_ACC
+    // keeps Q and the O accumulators in accumulation registers across the loops' control flow
+    auto pin = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+            for (int t = 0; t < 8; ++t) asm volatile("" : "+a"(qraw[cb][t]));
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
             for (int cb = 0; cb < 2; ++cb) asm volatile("" : "+a"(acc[db][cb]));
-#endif
     };
-    float m_ref[2], l_run[2] = {0.f, 0.f};
-    f32x16 s[2];              // scores, produced by the matrix cores one iteration ahead
-    bf16x8 pf[2][2];          // P^T(u-1) as B-operand fragments [query block][k-step]
+    pin();
+
+    // Tile order.  The softmax reference is fixed, so key tiles may come in any order: first every
+    // tile all of whose keys are visible to all 256 queries (whole prefix tiles, own tiles below
+    // the first query), through a loop without masking code; then the ragged last prefix tile and
+    // the (at most four) own tiles on the diagonal, through a copy of the loop that masks.
+    const int nPf = P / FWD_BN;                        // whole prefix tiles
+    const int rag = (P % FWD_BN) ? 1 : 0;              // ragged prefix tile
+    const int nOf = q0 / FWD_BN;                       // own tiles below the first query
+    const int own_end = min(S, q0 + FWD_BM);
+    const int nMain = nPf + nOf;
+    const int nT = nMain + rag + (own_end + FWD_BN - 1) / FWD_BN - nOf;
+    const char* zk_b = reinterpret_cast<const char*>(zk) + static_cast<size_t>(hk) * P * ROW_B;
+    const char* zv_b = reinterpret_cast<const char*>(zv) + static_cast<size_t>(hk) * P * ROW_B;
+    const uint32_t own_pitch = static_cast<uint32_t>(Hkv) * ROW_B;
+    const char* k_b = reinterpret_cast<const char*>(k) + (static_cast<size_t>(b) * S * Hkv + hk) * ROW_B;
+    const char* v_b = reinterpret_cast<const char*>(v) + (static_cast<size_t>(b) * S * Hkv + hk) * ROW_B;
+    // tile t of that order: prefix or own, first key (all scalar)
+    auto tile_pre = [&](int t) __attribute__((always_inline)) {
+        return t < nPf || (rag && t == nMain);
+    };
+    auto tile_j0 = [&](int t) __attribute__((always_inline)) {
+        return (t < nPf ? t : t < nMain ? t - nPf : (rag && t == nMain) ? nPf : t - nPf - rag) * FWD_BN;
+    };
+
+    // Direct-to-LDS load of one tile, eight instructions per wavefront (K rows, then V rows),
+    // handed out one per matrix-core instruction by the stage below.
+    const uint32_t dma_c0 = (lane & 15) ^ (((lane >> 4) & 3) << 2);   // chunk under the swizzle, before ^ i
+    struct TileSrc { const char* kb; const char* vb; int lim; uint32_t pitch; uint32_t lds_k, lds_v; };
+    auto tile_src = [&](int t, int buf) __attribute__((always_inline)) {
+        const bool pre = tile_pre(t);
+        const int j0 = tile_j0(t);
+        TileSrc ts;
+        ts.pitch = pre ? static_cast<uint32_t>(ROW_B) : own_pitch;
+        ts.kb = (pre ? zk_b : k_b) + static_cast<size_t>(j0) * ts.pitch;
+        ts.vb = (pre ? zv_b : v_b) + static_cast<size_t>(j0) * ts.pitch;
+        ts.lim = (pre ? P : S) - 1 - j0;    // rows past the end repeat the last valid row
+        ts.lds_k = lds_addr(sm.k[buf]);
+        ts.lds_v = lds_addr(sm.v[buf]);
+        return ts;
+    };
+    auto dma_piece = [&](const TileSrc& ts, int n) __attribute__((always_inline)) {
+        const int i = n & 3;
+        const int r0 = (4 * wv + i) * 4;
+        const uint32_t voff = __umul24(min(r0 + (lane >> 4), ts.lim), ts.pitch) + ((dma_c0 ^ i) << 4);
+        if (n < 4) dma16(ts.kb, voff, ts.lds_k + r0 * ROW_B);
+        else       dma16(ts.vb, voff, ts.lds_v + r0 * ROW_B);
+    };
+    // hidden entries of the scores of the sub-tile whose first key is j0 (prefix or own) -> NEG_BIG
+    auto mask = [&](f32x16 (&x)[2], bool pre, int j0) __attribute__((always_inline)) {
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) {
+            // key j0 + d_row(r, lg) is hidden when it exceeds the lane's last visible key
+            const int thr = (pre ? P - 1 : wrow0 + 32 * cb + lc) - j0 - 4 * lg;
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                if (8 * (r >> 2) + (r & 3) > thr) x[cb][r] = NEG_BIG;
+        }
+    };
+
+    // Per-lane LDS addresses of the operand fragments, complete except for compile-time offsets;
+    // they move from buffer to buffer once per tile (K fragments are fetched one tile ahead of V).
+    uint32_t kofs[8], vofs[4][2];
+    {
+        const uint32_t lk = lds_addr(sm.k[1]), lv = lds_addr(sm.v[0]);
+#pragma unroll
+        for (int t8 = 0; t8 < 8; ++t8) kofs[t8] = lk + lc * ROW_B + (((2 * t8 + lg) ^ swz(lc)) << 4);
+        const int s16 = lane & 15;
+        const int row = 4 * lg + (s16 >> 2);
+        const int col0 = 16 * ((lane >> 4) & 1) + 4 * (s16 & 3);
+        const int half = ((col0 >> 2) & 1) * 8;
+#pragma unroll
+        for (int db = 0; db < 4; ++db) {
+            const int ch = (32 * db + col0) >> 3;
+            vofs[db][0] = lv + row * ROW_B + ((ch ^ swz(row)) << 4) + half;
+            vofs[db][1] = lv + (row + 8) * ROW_B + ((ch ^ swz(row + 8)) << 4) + half;
+        }
+    }
+    typedef const bf16x8 __attribute__((address_space(3))) * lds_b128;
+    typedef s16x4 __attribute__((address_space(3))) * lds_b64;
+    // row-wise K fragment t8 of the 32-row half hb of the buffer kofs points at
+    auto ld_k = [&](int t8, int hb) __attribute__((always_inline)) {
+        return *(lds_b128)(kofs[t8] + hb * 32 * ROW_B);
+    };
+    // transposed V fragment (k-step ks, head-element block db) of half hb of the buffer at vofs
+    auto ld_v = [&](int ks, int db, int hb) __attribute__((always_inline)) {
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_b64)(vofs[db][0] + (32 * hb + 16 * ks) * ROW_B));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_b64)(vofs[db][1] + (32 * hb + 16 * ks) * ROW_B));
+        return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+
+    // -m (the softmax reference of the lane's query) in all 16 registers of a set: the first
+    // product of every score chain starts from it, so S arrives as the exponent c s - m
+    f32x16 ninit[2];
+    float l_run[2] = {0.f, 0.f};
+    // Scores live in ordinary vector registers, in two sets used alternately: while the vector
+    // ALU reads S(u) from one set the matrix cores write S(u+1) into the other, so no copy sits
+    // between the matrix cores' results and the softmax arithmetic.
+    f32x16 sa[2], sb[2];
+    u32x4 pf[2][2];           // P^T(u-1) as B-operand fragments [query block][k-step]
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) pf[cb][ks] = bf16x8{};
+        for (int ks = 0; ks < 2; ++ks) pf[cb][ks] = u32x4{0u, 0u, 0u, 0u};
+    bf16x8 ka[8], va[2][4];   // K fragments of sub-tile u+1, V fragments of sub-tile u-1
 
-    // Iteration u.  Matrix cores: S^T(u+1) = K Q^T and O^T += V^T(u-1) P^T(u-1).  Vector ALU:
-    // P(u) = 2^(c S(u) - m), row sums, bf16 fragments.  The two streams are independent.
-    // LDS -> register fragments run one iteration ahead of their use (loop-carried), so their
-    // latency is covered by a whole iteration of work whatever the instruction order inside it
-    bf16x8 ka[8], va[2][4];
-    auto load_k = [&](const char* kt, int r0) __attribute__((always_inline)) {
+    // Iteration u (sub-tile hb of a tile; MASKED: it may hold hidden keys).  On entry: x = S(u),
+    // ka = K fragments of sub-tile u+1, va = V fragments of sub-tile u-1, pf = P(u-1); on exit
+    // y = S(u+1).  The work is laid out as 32 groups of one matrix-core instruction plus one
+    // softmax element and the odd jobs that go with it, fenced so that the scheduler keeps the
+    // spread: the matrix cores run S^T(u+1) = K Q^T (groups 0-15) and O^T += V^T P^T(u-1)
+    // (groups 16-31) while the vector ALU turns S(u) into P(u); each fragment register is
+    // refilled from LDS for the next iteration right after its last use, and the eight
+    // direct-to-LDS loads of tile t+2 (DMA, first sub-tile only) ride along in groups 0-7.
+    auto stage = [&](auto hb_tag, auto masked_tag, bool pre, int j0, f32x16 (&x)[2], f32x16 (&y)[2],
+                     const TileSrc& ts) __attribute__((always_inline)) {
+        constexpr int hb = decltype(hb_tag)::value;
+        constexpr bool MASKED = decltype(masked_tag)::value;
+        if (MASKED) mask(x, pre, j0 + 32 * hb);
+        pin();
+        float pe[32];
+        u32x4 pn[2][2];
 #pragma unroll
-        for (int t8 = 0; t8 < 8; ++t8) ka[t8] = lds_frag_n(kt, r0 + lc, 16 * t8 + 8 * lg);
-    };
-    auto load_v = [&](const char* vt, int r0) __attribute__((always_inline)) {
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-            for (int db = 0; db < 4; ++db) va[ks][db] = lds_frag_t(vt, r0 + 16 * ks, 32 * db, lane);
-    };
-    // Iteration u, on entry: s = S(u), ka = K fragments of sub-tile u+1, va = V fragments of
-    // sub-tile u-1, pf = P(u-1).  buf / nbuf = LDS buffers of the tiles of sub-tiles u / u+2.
-    auto stage = [&](int u, int buf, int nbuf) __attribute__((always_inline)) {
-        const int hb = u & 1;
-        // the scores of sub-tile u move to ordinary registers (their accumulators are reused by
-        // the next sub-tile); the rare masked sub-tile is patched here, outside the main block
-        f32x16 x[2] = {s[0], s[1]};
-        if (needs_mask(u >> 1, hb)) mask(x, u >> 1, hb);
-        pin_q();
-        pin_acc();
+        for (int g = 0; g < 32; ++g) {
+            if (g < 16) {
+                const int t8 = g >> 1, cb = g & 1;
+                if (t8 == 0) mma_vd_first(y[cb], ka[0], qraw[cb][0], ninit[cb]);
+                else         mma_vd(y[cb], ka[t8], qraw[cb][t8]);
+            } else {
+                const int i = g - 16, ks = i >> 3, db = (i >> 1) & 3, cb = i & 1;
+                acc[db][cb] = mma(va[ks][db], __builtin_bit_cast(bf16x8, pf[cb][ks]), acc[db][cb]);
+            }
+            __builtin_amdgcn_sched_barrier(0);   // the matrix-core instruction leads its group
+            if (hb == 0 && g < 8) dma_piece(ts, g);
+            // refill the fragment register the previous two groups used last
+            if (g >= 2 && g <= 16 && !(g & 1)) ka[(g - 2) >> 1] = ld_k((g - 2) >> 1, hb);
+            if (g >= 18 && !(g & 1)) {
+                const int i = g - 18;
+                va[i >> 3][(i >> 1) & 3] = ld_v(i >> 3, (i >> 1) & 3, hb);
+            }
+            {   // softmax element g; the pair before it is rounded, packed and summed
+                const int cb = g >> 4, r = g & 15;
+                pe[g] = fast_exp2(x[cb][r]);
+                if (g >= 2 && !(g & 1)) {
+                    const int e = g - 2, cbe = e >> 4, re = e & 15;
+                    pn[cbe][re >> 3][(re & 7) >> 1] = pack_bf16x2(pe[e], pe[e + 1]);
+                    l_run[cbe] += pe[e] + pe[e + 1];
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        va[1][3] = ld_v(1, 3, hb);
+        pn[1][1][3] = pack_bf16x2(pe[30], pe[31]);
+        l_run[1] += pe[30] + pe[31];
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) s[cb][r] = 0.f;
-#pragma unroll
-        for (int t8 = 0; t8 < 8; ++t8) {
-            s[0] = mma(ka[t8], qf_(0, t8), s[0]);
-            s[1] = mma(ka[t8], qf_(1, t8), s[1]);
-        }
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-            for (int db = 0; db < 4; ++db) {
-                acc[db][0] = mma(va[ks][db], pf[0][ks], acc[db][0]);
-                acc[db][1] = mma(va[ks][db], pf[1][ks], acc[db][1]);
-            }
-        // fragments for the next iteration: K of sub-tile u+2, V of sub-tile u
-        load_k(sm.k[0] + nbuf * FWD_TILE_B, 32 * hb);
-        load_v(sm.v[0] + buf * FWD_TILE_B, 32 * hb);
-#pragma unroll
-        for (int cb = 0; cb < 2; ++cb) {
-            float rs = 0.f;
-            f32x16 p;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                p[r] = fast_exp2(fmaf(x[cb][r], c, -m_ref[cb]));
-                rs += p[r];
-            }
-            l_run[cb] += rs;
-            pf[cb][0] = pack_frag(p, 0);
-            pf[cb][1] = pack_frag(p, 8);
-        }
-        // P(u) and the prefetched fragments are consumed only by the next iteration; anchoring
-        // them here keeps their instructions in this block, next to the matrix-core work
-#pragma unroll
-        for (int cb = 0; cb < 2; ++cb) asm volatile("" : "+v"(pf[cb][0]), "+v"(pf[cb][1]), "+v"(l_run[cb]));
-#pragma unroll
-        for (int t8 = 0; t8 < 8; ++t8) asm volatile("" : "+v"(ka[t8]));
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-            for (int db = 0; db < 4; ++db) asm volatile("" : "+v"(va[ks][db]));
+            for (int ks = 0; ks < 2; ++ks) pf[cb][ks] = pn[cb][ks];
+        __builtin_amdgcn_sched_barrier(0);
     };
+    // the matrix-core results of the inline-assembly products are not tracked by the compiler's
+    // hazard logic: before the vector ALU touches them, let the last one retire
+    auto settle = [&]() __attribute__((always_inline)) { asm volatile("s_nop 15\n\ts_nop 7" ::: "memory"); };
 
-    issue(0, 0);
-    dma_wait();
-    __syncthreads();
-    issue(min(1, nT - 1), 1);
-    {   // scores of sub-tile 0 and the softmax reference of every query: its maximum there
-        load_k(sm.k[0], 0);
+    {   // tiles 0 and 1 on their way; scores of sub-tile 0 and the softmax reference of every
+        // query: its maximum over that sub-tile (which holds a visible key for every query)
+        const TileSrc t0 = tile_src(0, 0);
 #pragma unroll
-        for (int cb = 0; cb < 2; ++cb)
+        for (int n = 0; n < 8; ++n) dma_piece(t0, n);
+        dma_wait();
+        __syncthreads();
+        const TileSrc t1 = tile_src(min(1, nT - 1), 1);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) s[cb][r] = 0.f;
+        for (int n = 0; n < 8; ++n) dma_piece(t1, n);
+#pragma unroll
+        for (int t8 = 0; t8 < 8; ++t8) ka[t8] = lds_frag_n(sm.k[0], lc, 16 * t8 + 8 * lg);
 #pragma unroll
         for (int t8 = 0; t8 < 8; ++t8) {
-            s[0] = mma(ka[t8], qf_(0, t8), s[0]);
-            s[1] = mma(ka[t8], qf_(1, t8), s[1]);
+            if (t8 == 0) { mma_vd_zero(sa[0], ka[0], qraw[0][0]); mma_vd_zero(sa[1], ka[0], qraw[1][0]); }
+            else         { mma_vd(sa[0], ka[t8], qraw[0][t8]);    mma_vd(sa[1], ka[t8], qraw[1][t8]); }
         }
-        f32x16 x[2] = {s[0], s[1]};
-        if (needs_mask(0, 0)) mask(x, 0, 0);
+        settle();
+        mask(sa, tile_pre(0), tile_j0(0));
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb) {
-            float tm = x[cb][0];
+            float tm = sa[cb][0];
 #pragma unroll
-            for (int r = 1; r < 16; ++r) tm = fmaxf(tm, x[cb][r]);
-            m_ref[cb] = partner_max(tm) * c;
+            for (int r = 1; r < 16; ++r) tm = fmaxf(tm, sa[cb][r]);
+            const float nm = -partner_max(tm);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { ninit[cb][r] = nm; sa[cb][r] += nm; }
         }
-        load_k(sm.k[0], 32);      // K of sub-tile 1
-        load_v(sm.v[0], 0);       // placeholder for "V of sub-tile -1": multiplied by P = 0
+#pragma unroll
+        for (int t8 = 0; t8 < 8; ++t8) ka[t8] = lds_frag_n(sm.k[0], 32 + lc, 16 * t8 + 8 * lg);   // sub-tile 1
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)     // placeholder for "V of sub-tile -1": multiplied by P = 0
+#pragma unroll
+            for (int db = 0; db < 4; ++db) va[ks][db] = lds_frag_t(sm.v[0], 16 * ks, 32 * db, lane);
     }
     // Three LDS buffers, tile t in buffer t % 3.  The one barrier per tile opens the iteration
     // of the tile's first sub-tile: it publishes tile t+1 (read from this iteration on) and
     // retires tile t-1's buffer (its last fragments were fetched in the previous iteration),
     // which then receives tile t+2.
     int buf = 0;
-    for (int t = 0; t < nT; ++t) {
+    auto tile_iter = [&](int t, auto masked_tag) __attribute__((always_inline)) {
         const int nbuf = buf + 1 == FWD_NBUF ? 0 : buf + 1;
+        const int nnbuf = nbuf + 1 == FWD_NBUF ? 0 : nbuf + 1;
+        const TileSrc ts = tile_src(min(t + 2, nT - 1), nnbuf);
+        const bool pre = tile_pre(t);
+        const int j0 = tile_j0(t);
         dma_wait();
         __syncthreads();
-        issue(min(t + 2, nT - 1), nbuf + 1 == FWD_NBUF ? 0 : nbuf + 1);
-        stage(2 * t, buf, nbuf);
-        stage(2 * t + 1, buf, nbuf);
+        stage(std::integral_constant<int, 0>{}, masked_tag, pre, j0, sa, sb, ts);
+        stage(std::integral_constant<int, 1>{}, masked_tag, pre, j0, sb, sa, ts);
+        // fragment addresses follow the buffers: K to tile t+2's, V to tile t+1's
+        const uint32_t dk = nnbuf == 0 ? static_cast<uint32_t>(-2 * FWD_TILE_B) : static_cast<uint32_t>(FWD_TILE_B);
+        const uint32_t dv = nbuf == 0 ? static_cast<uint32_t>(-2 * FWD_TILE_B) : static_cast<uint32_t>(FWD_TILE_B);
+#pragma unroll
+        for (int t8 = 0; t8 < 8; ++t8) kofs[t8] += dk;
+#pragma unroll
+        for (int db = 0; db < 4; ++db) { vofs[db][0] += dv; vofs[db][1] += dv; }
         buf = nbuf;
-    }
+    };
+    for (int t = 0; t < nMain; ++t) tile_iter(t, std::false_type{});
+    for (int t = nMain; t < nT; ++t) tile_iter(t, std::true_type{});
     {   // drain: O^T += V^T P^T of the last sub-tile (its V fragments are already in registers)
+        pin();
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
             for (int db = 0; db < 4; ++db) {
-                acc[db][0] = mma(va[ks][db], pf[0][ks], acc[db][0]);
-                acc[db][1] = mma(va[ks][db], pf[1][ks], acc[db][1]);
+                acc[db][0] = mma(va[ks][db], __builtin_bit_cast(bf16x8, pf[0][ks]), acc[db][0]);
+                acc[db][1] = mma(va[ks][db], __builtin_bit_cast(bf16x8, pf[1][ks]), acc[db][1]);
             }
     }
+    float m_ref[2] = {-ninit[0][0], -ninit[1][0]};
 
     // normalise and store: lane holds, for its query, head elements 32db + 8(r/4) + 4g + r%4
     bool bad = false;
