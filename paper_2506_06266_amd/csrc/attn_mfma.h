@@ -11,10 +11,23 @@
 // same permuted order (see k_slot_row below), which a sum does not mind.
 #pragma once
 
+#include <type_traits>
+#include <utility>
+
 #include "cart_common.h"
 
 namespace cart {
 namespace mfma {
+
+// compile-time loop: f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N-1>{})
+template <typename F, int... Is>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, Is...>) {
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+    static_for_impl(static_cast<F&&>(f), std::make_integer_sequence<int, N>{});
+}
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -75,6 +88,35 @@ __device__ __forceinline__ bf16x8 lds_frag_t(const char* tile, int k0, int n0, i
         (lds_ptr)(tile + (row + 8) * ROW_B + (((col >> 3) ^ swz(row + 8)) << 4) + half));
     s16x8 r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, r);
+}
+
+// The same two fragment kinds from precomputed 32-bit LDS byte addresses (per-lane part computed
+// once, compile-time offsets added at the use): frag_n_ofs / frag_t_ofs give the per-lane offset
+// of a fragment inside a tile whose first row is a multiple of 16.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint32_t frag_n_ofs(int lane, int t8) {
+    const int lc = lane & 31, lg = lane >> 5;
+    return lc * ROW_B + (((2 * t8 + lg) ^ swz(lc)) << 4);
+}
+__device__ __forceinline__ void frag_t_ofs(int lane, int db, uint32_t& lo, uint32_t& hi) {
+    const int s = lane & 15, g = lane >> 5;
+    const int row = 4 * g + (s >> 2);
+    const int col = 32 * db + 16 * ((lane >> 4) & 1) + 4 * (s & 3);
+    const int half = ((col >> 2) & 1) * 8;
+    lo = row * ROW_B + (((col >> 3) ^ swz(row)) << 4) + half;
+    hi = (row + 8) * ROW_B + (((col >> 3) ^ swz(row + 8)) << 4) + half;
+}
+__device__ __forceinline__ bf16x8 lds_ld_frag(uint32_t addr) {
+    return *(const bf16x8 __attribute__((address_space(3)))*)addr;
+}
+__device__ __forceinline__ f32x4 lds_ld_f32x4(uint32_t addr) {
+    return *(const f32x4 __attribute__((address_space(3)))*)addr;
+}
+__device__ __forceinline__ bf16x8 lds_ld_frag_t(uint32_t lo, uint32_t hi) {
+    typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
+    const s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)lo);
+    const s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)hi);
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
 // D row held in register r of lane-group g (the k index the next product contracts over)

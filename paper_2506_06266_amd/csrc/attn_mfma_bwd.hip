@@ -23,12 +23,13 @@ constexpr int BWD_TILE_B = BWD_TILE * ROW_B;
 constexpr int BWD_NBUF = 3;
 constexpr int BWD_WG_ROWS = 256;                  // stationary rows per workgroup (4 x 64)
 
-// ---- delta = rowsum(dO * O), lse2 = lse * log2(e); 16 lanes per row, 8 elements per lane ----
+// ---- -delta = -rowsum(dO * O), -lse2 = -lse * log2(e) (negated: they enter the products as
+// init values); 16 lanes per row, 8 elements per lane ----
 __global__ __launch_bounds__(256) void attn_bwd_prep_kernel(const bf16_t* __restrict__ o,
                                                             const bf16_t* __restrict__ d_o,
                                                             const float* __restrict__ lse,
-                                                            float* __restrict__ delta,
-                                                            float* __restrict__ lse2, int B, int S,
+                                                            float* __restrict__ ndelta,
+                                                            float* __restrict__ nlse2, int B, int S,
                                                             int Hq) {
     const long row = static_cast<long>(blockIdx.x) * 16 + (threadIdx.x >> 4);
     const long rows = static_cast<long>(B) * S * Hq;
@@ -47,8 +48,8 @@ __global__ __launch_bounds__(256) void attn_bwd_prep_kernel(const bf16_t* __rest
     if (sub == 0) {
         const int h = row % Hq, i = (row / Hq) % S, b = row / (static_cast<long>(Hq) * S);
         const size_t st = (static_cast<size_t>(b) * Hq + h) * S + i;
-        delta[st] = s;
-        lse2[st] = lse[st] * CART_LOG2E;
+        ndelta[st] = -s;
+        nlse2[st] = -lse[st] * CART_LOG2E;
     }
 }
 
@@ -65,7 +66,6 @@ __device__ __forceinline__ void store_rows_bf16(const f32x16 (&acc)[4], bf16_t* 
             *reinterpret_cast<u32x2*>(row_ptr + 32 * db + 8 * r4 + 4 * lg) = w;
         }
 }
-typedef float f32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ void store_rows_f32(const f32x16 (&acc)[4], float* row_ptr, int lg, float mul) {
     if (!row_ptr) return;
 #pragma unroll
@@ -109,7 +109,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
     const int q0 = qt * BWD_WG_ROWS, wrow0 = q0 + 64 * wv;
 
     u32x4 qf[2][8], gf[2][8];     // B operands: column = query, k = head element
-    float l2[2], dl[2];
+    float l2[2], dl[2];     // -lse2, -delta of the lane's queries
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb) {
         int qi = wrow0 + 32 * cb + lc;
@@ -249,8 +249,8 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
             f32x16 w;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const float p = fast_exp2(fmaf(x[cb][r], c, -l2[cb]));
-                w[r] = p * (y[cb][r] - dl[cb]);
+                const float p = fast_exp2(fmaf(x[cb][r], c, l2[cb]));
+                w[r] = p * (y[cb][r] + dl[cb]);
             }
             dsf[cb][0] = pack_frag(w, 0);
             dsf[cb][1] = pack_frag(w, 8);
@@ -309,29 +309,37 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
 // =================================================================================================
 // dK / dV: keys stationary
 // =================================================================================================
-// The dV kernel fetches every LDS fragment one iteration ahead and needs three tile buffers.  The
-// dK kernel holds twice the stationary fragments (K and V) and twice the score accumulators, has
-// no registers left for prefetched fragments, reads them where used, and therefore retires a
-// tile's buffer one tile later: four buffers.
+// One workgroup = 256 keys of one (sequence, KV head): a block of prefix slots, or a block of the
+// sequence's own tokens; each wavefront keeps 64 of them as B-operand fragments in accumulation
+// registers (K scaled by c = softmax_scale * log2(e), so scores come out in log2 units).  It
+// streams the queries that see those keys (all tokens of all heads of the group for prefix slots,
+// tokens at or after the block for own keys) through LDS in tiles of 64 rows of Q and dO plus the
+// rows' -lse2 and -delta, which start the score and dP products as their init values:
+//   S = Q K^T - lse2 -> P = 2^S,   dP = dO V^T - delta,   dS = P dP,
+//   dV^T += dO^T P   (dV kernel),   dK^T += Q^T dS   (dK kernel).
+// Tiles all of whose (query, key) pairs are visible come first, through a loop without masking
+// code; the tiles on the diagonal and the ragged last tile of each head follow through a copy of
+// the loop that masks.  Every iteration is laid out as fenced groups of one matrix-core
+// instruction plus its share of the vector-ALU work, LDS fragment loads and direct-to-LDS loads.
 template <int NBUF>
 struct KsSmem {
-    char q[NBUF][BWD_TILE_B];
-    char g[NBUF][BWD_TILE_B];
-    float l2[NBUF][BWD_TILE];
-    float dl[NBUF][BWD_TILE];
+    struct { char q[BWD_TILE_B]; char g[BWD_TILE_B]; } t[NBUF];
+    float nl2[NBUF][BWD_TILE];
+    float ndl[NBUF][BWD_TILE];
 };
 
-// One workgroup = 256 keys of one (sequence, KV head): a block of prefix slots, or a block of the
-// sequence's own tokens.  It streams the queries that see those keys: all tokens of all heads of
-// the group for prefix slots, tokens at or after the block for own keys.
 template <bool IS_DK>
 __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
     const bf16_t* __restrict__ zk, const bf16_t* __restrict__ zv, const bf16_t* __restrict__ d_o,
-    const float* __restrict__ lse2, const float* __restrict__ delta, bf16_t* __restrict__ out_own,
+    const float* __restrict__ nlse2, const float* __restrict__ ndelta, bf16_t* __restrict__ out_own,
     float* __restrict__ part, int B, int S, int Hq, int Hkv, int P, float c, float scale) {
+    // dV fetches every fragment a whole iteration ahead: a tile is read in two consecutive tile
+    // iterations, three buffers.  dK fetches the transposed fragments of the previous sub-tile a
+    // few groups ahead of their use, i.e. one tile iteration later: four buffers.
     constexpr int NBUF = IS_DK ? 4 : 3;
-    constexpr bool PREFETCH = !IS_DK;
+    constexpr int BUF_B = 2 * BWD_TILE_B;     // one buffer: Q tile, dO tile
+    constexpr int G_OFF = BWD_TILE_B;         // dO tile inside a buffer
     __shared__ KsSmem<NBUF> sm;
     const int G = Hq / Hkv;
     const int nPb = (P + BWD_WG_ROWS - 1) / BWD_WG_ROWS, nOb = (S + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
@@ -358,38 +366,13 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
         const bf16_t* vp = (pre ? zv : v) + row * HD + 8 * lg;
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
-            kf[kc][t] = *reinterpret_cast<const u32x4*>(kp + 16 * t);
+            const u32x4 w = *reinterpret_cast<const u32x4*>(kp + 16 * t);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                kf[kc][t][i] = pack_bf16x2(__uint_as_float(w[i] << 16) * c, __uint_as_float(w[i] & 0xffff0000u) * c);
             if (IS_DK) vf[kc][t] = *reinterpret_cast<const u32x4*>(vp + 16 * t);
         }
     }
-
-    const int nQtAll = (S + BWD_TILE - 1) / BWD_TILE;
-    const int qt0 = pre ? 0 : key0 / BWD_TILE;
-    const int nq = nQtAll - qt0;
-    const int nT = G * nq;            // query tiles streamed: head-major, token tiles inside
-    const char* q_c = reinterpret_cast<const char*>(q);
-    const char* g_c = reinterpret_cast<const char*>(d_o);
-    const size_t q_pitch = static_cast<size_t>(Hq) * ROW_B;
-
-    auto issue = [&](int T, int buf) __attribute__((always_inline)) {
-        const int gi = T / nq, qt = qt0 + T - gi * nq;
-        const int h = hk * G + gi;
-        const int i0 = qt * BWD_TILE;
-        const size_t base = (static_cast<size_t>(b) * S * Hq + h) * ROW_B;
-        tile_load_async<BWD_TILE>(sm.q[buf], q_c + base, i0, S - 1, static_cast<uint32_t>(q_pitch));
-        tile_load_async<BWD_TILE>(sm.g[buf], g_c + base, i0, S - 1, static_cast<uint32_t>(q_pitch));
-        // the tile's 64 lse2 / delta values: one 4-byte direct-to-LDS load per lane
-        if (wv < 2) {
-            const float* src = (wv == 0 ? lse2 : delta) + (static_cast<size_t>(b) * Hq + h) * S;
-            float* dst = wv == 0 ? sm.l2[buf] : sm.dl[buf];
-            dma4(reinterpret_cast<const char*>(src), static_cast<uint32_t>(min(i0 + lane, S - 1)) * 4u, lds_addr(dst));
-        }
-    };
-    auto tile_i0 = [&](int T) __attribute__((always_inline)) {
-        const int gi = T / nq;
-        return (qt0 + T - gi * nq) * BWD_TILE;
-    };
-
     f32x16 acc[4][2];   // dK^T or dV^T: [head-element block][key block]
 #pragma unroll
     for (int db = 0; db < 4; ++db)
@@ -397,179 +380,364 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
         for (int kc = 0; kc < 2; ++kc)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[db][kc][r] = 0.f;
-    f32x16 s[2], dp[2];   // [key block]: rows = 32 queries of the sub-tile, one iteration ahead
-    bf16x8 xf[2][2];      // P or dS of sub-tile u-1 as B-operand fragments [key block][k-step]
-#pragma unroll
-    for (int kc = 0; kc < 2; ++kc)
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) xf[kc][ks] = bf16x8{};
-
-    // a query row of the sub-tile is hidden from a key when it precedes it (own keys) or lies
-    // past the end of the sequence (clamped tile rows)
-    auto needs_mask = [&](int T, int hb) __attribute__((always_inline)) {
-        const int i0 = tile_i0(T) + 32 * hb;
-        return (!pre && i0 < wkey0 + 63) || (i0 + 32 > S);
-    };
-    auto mask = [&](f32x16 (&x)[2], int T, int hb) __attribute__((always_inline)) {
-        const int i0 = tile_i0(T) + 32 * hb;
-#pragma unroll
-        for (int kc = 0; kc < 2; ++kc) {
-            // row i0 + d_row(r, lg) is visible iff it is >= the lane's key (own) and < S
-            const int lo = (pre ? 0 : wkey0 + 32 * kc + lc) - i0 - 4 * lg;
-            const int hi = S - i0 - 4 * lg;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int rr = 8 * (r >> 2) + (r & 3);
-                if (rr < lo || rr >= hi) x[kc][r] = NEG_BIG;
-            }
-        }
-    };
-    // the stationary fragments live in accumulation registers (read directly as B operands)
-    constexpr bool PIN_K = true;
+    // the stationary fragments and the accumulators live in accumulation registers
     auto pin = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int kc = 0; kc < 2; ++kc)
 #pragma unroll
-            for (int t = 0; t < 8; ++t)
-                if (PIN_K) asm volatile("" : "+a"(kf[kc][t]));
+            for (int t = 0; t < 8; ++t) {
+                asm volatile("" : "+a"(kf[kc][t]));
+                if (IS_DK) asm volatile("" : "+a"(vf[kc][t]));
+            }
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
             for (int kc = 0; kc < 2; ++kc) asm volatile("" : "+a"(acc[db][kc]));
     };
-#define KF_(kc, t) __builtin_bit_cast(bf16x8, kf[kc][t])
-#define VF_(kc, t) __builtin_bit_cast(bf16x8, vf[kc][t])
+    pin();
 
-    // LDS -> register fragments run one iteration ahead of their use (loop-carried): row-wise Q
-    // (and dO) of sub-tile u+1, transposed dO (or Q) of sub-tile u-1
-    bf16x8 qa[8], ta[2][4];
-    auto load_nat = [&](int buf, int r0) __attribute__((always_inline)) {
+    // The stream of query tiles (64 token rows of one head).  Per head: whole tiles entirely
+    // after the block's last key [qtF0, nFullEnd) need no mask; the tiles on the diagonal
+    // [qt0, qtF0) and the ragged last tile do.  Order: the unmasked tiles of every head, then the
+    // masked tiles of every head.
+    const int nQtAll = (S + BWD_TILE - 1) / BWD_TILE, nFullEnd = S / BWD_TILE;
+    const int qt0 = pre ? 0 : key0 / BWD_TILE;
+    const int qtF0 = pre ? 0 : qt0 + BWD_WG_ROWS / BWD_TILE;
+    const int nFull = max(0, nFullEnd - qtF0);
+    const int nM1 = min(qtF0, nQtAll) - qt0;
+    const int nM = nM1 + ((nFullEnd < nQtAll && nFullEnd >= qtF0) ? 1 : 0);
+    const int nMain = G * nFull, nT = G * (nFull + nM);
+    const char* q_c = reinterpret_cast<const char*>(q);
+    const char* g_c = reinterpret_cast<const char*>(d_o);
+    const uint32_t q_pitch = static_cast<uint32_t>(Hq) * ROW_B;
+    // iterator over that order (all scalar): phase 0 = unmasked, 1 = masked
+    int it_ph = nFull > 0 ? 0 : 1, it_g = 0, it_n = 0, it_cnt = 0;
+    struct TileSrc { const char* qb; const char* gb; const char* rb; int lim; int i0; uint32_t lds_q, lds_g, lds_r; };
+    const uint32_t dma_c0 = (lane & 15) ^ (((lane >> 4) & 3) << 2);
+    // describes the iterator's tile as the source of a load into buffer buf, then advances
+    auto next_tile = [&](int buf) __attribute__((always_inline)) {
+        const int qt = it_ph == 0 ? qtF0 + it_n : (it_n < nM1 ? qt0 + it_n : nFullEnd);
+        const int h = hk * G + it_g;
+        TileSrc ts;
+        ts.i0 = qt * BWD_TILE;
+        const size_t base = (static_cast<size_t>(b) * S * Hq + h) * ROW_B + static_cast<size_t>(ts.i0) * q_pitch;
+        ts.qb = q_c + base;
+        ts.gb = g_c + base;
+        ts.lim = S - 1 - ts.i0;
+        // wavefronts 0 / 2 fetch the rows' -lse2, 1 / 3 their -delta (twice each: no branch)
+        ts.rb = reinterpret_cast<const char*>(((wv & 1) ? ndelta : nlse2) + (static_cast<size_t>(b) * Hq + h) * S + ts.i0);
+        ts.lds_q = lds_addr(sm.t[buf].q);
+        ts.lds_g = lds_addr(sm.t[buf].g);
+        ts.lds_r = lds_addr((wv & 1) ? sm.ndl[buf] : sm.nl2[buf]);
+        if (it_cnt < nT - 1) {     // past the end the last tile is fetched again, into a retired buffer
+            ++it_cnt;
+            ++it_n;
+            if (it_n == (it_ph == 0 ? nFull : nM)) {
+                it_n = 0;
+                if (++it_g == G) { it_g = 0; ++it_ph; }
+            }
+        }
+        return ts;
+    };
+    // direct-to-LDS loads of a tile, nine per wavefront: 4 x Q rows, 4 x dO rows, 1 x row values
+    auto dma_piece = [&](const TileSrc& ts, int n) __attribute__((always_inline)) {
+        if (n == 8) {
+            dma4(ts.rb, static_cast<uint32_t>(min(lane, ts.lim)) * 4u, ts.lds_r);
+            return;
+        }
+        const int i = n & 3;
+        const int r0 = (4 * wv + i) * 4;
+        const uint32_t voff = __umul24(min(r0 + (lane >> 4), ts.lim), q_pitch) + ((dma_c0 ^ i) << 4);
+        if (n < 4) dma16(ts.qb, voff, ts.lds_q + r0 * ROW_B);
+        else       dma16(ts.gb, voff, ts.lds_g + r0 * ROW_B);
+    };
+    // a query row of the sub-tile starting at token i0 is hidden from a key when it precedes it
+    // (own keys) or lies past the end of the sequence (clamped tile rows)
+    auto mask1 = [&](f32x16& x, int kc, int i0) __attribute__((always_inline)) {
+        const int lo = (pre ? 0 : wkey0 + 32 * kc + lc) - i0 - 4 * lg;
+        const int hi = S - i0 - 4 * lg;
 #pragma unroll
-        for (int t8 = 0; t8 < 8; ++t8) {
-            qa[t8] = lds_frag_n(sm.q[0] + buf * BWD_TILE_B, r0 + lc, 16 * t8 + 8 * lg);
+        for (int r = 0; r < 16; ++r) {
+            const int rr = 8 * (r >> 2) + (r & 3);
+            if (rr < lo || rr >= hi) x[r] = NEG_BIG;
         }
     };
-    auto load_tr = [&](int buf, int r0) __attribute__((always_inline)) {
-        const char* at = (IS_DK ? sm.q[0] : sm.g[0]) + buf * BWD_TILE_B;
+
+    // Per-lane LDS addresses of the fragments, complete except for compile-time offsets; they
+    // move from buffer to buffer once per tile.
+    // dV reads row-wise fragments and row values a whole iteration ahead (tile T+1 throughout tile
+    // iteration T) and transposed fragments of the current sub-tile (tile T); dK reads row-wise
+    // fragments a few groups ahead (tile T in the first half of iteration T, T+1 in the second)
+    // and transposed fragments of the previous sub-tile (tile T-1, then T).
+    uint32_t qofs[8];      // row-wise Q fragment t8 (dO: + G_OFF)
+    uint32_t tofs[4][2];   // transposed fragment of head-element block db: of dO (dV), of Q (dK)
+    uint32_t rofs;         // -lse2 of rows 4 lg .. +3 (-delta: + R_OFF)
+    {
+        const uint32_t t1 = lds_addr(IS_DK ? sm.t[0].q : sm.t[1].q), t0 = lds_addr(IS_DK ? sm.t[0].q : sm.t[0].g);
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
+        for (int t8 = 0; t8 < 8; ++t8) qofs[t8] = t1 + frag_n_ofs(lane, t8);
 #pragma unroll
-            for (int db = 0; db < 4; ++db) ta[ks][db] = lds_frag_t(at, r0 + 16 * ks, 32 * db, lane);
+        for (int db = 0; db < 4; ++db) {
+            frag_t_ofs(lane, db, tofs[db][0], tofs[db][1]);
+            tofs[db][0] += t0;
+            tofs[db][1] += t0;
+        }
+        rofs = lds_addr(&sm.nl2[IS_DK ? 0 : 1][4 * lg]);
+    }
+    constexpr int R_OFF = NBUF * BWD_TILE * 4;     // -delta rows behind the -lse2 rows
+    // fragment loads; hb = which 32-row half of the tile
+    auto ld_q = [&](int t8, int hb) __attribute__((always_inline)) { return lds_ld_frag(qofs[t8] + hb * 32 * ROW_B); };
+    auto ld_g = [&](int t8, int hb) __attribute__((always_inline)) { return lds_ld_frag(qofs[t8] + G_OFF + hb * 32 * ROW_B); };
+    auto ld_t = [&](int p, int hb) __attribute__((always_inline)) {
+        const int ks = p >> 2, db = p & 3;
+        return lds_ld_frag_t(tofs[db][0] + (32 * hb + 16 * ks) * ROW_B, tofs[db][1] + (32 * hb + 16 * ks) * ROW_B);
     };
-    // scores of one sub-tile: from the prefetched fragments, or (dK) straight from LDS buffer
-    // nb, rows r0..
-    auto scores = [&](int nb, int r0) __attribute__((always_inline)) {
+    // init values of the score (dP) products of a sub-tile: register r <-> row 8 (r/4) + 4 lg + r%4
+    auto ld_rows = [&](f32x16& d, int ofs, int hb) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const f32x4 w = lds_ld_f32x4(rofs + ofs + (32 * hb + 8 * j) * 4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) d[4 * j + e] = w[e];
+        }
+    };
+
+    u32x4 xf[2][2];       // P or dS of sub-tile u-1 as B-operand fragments [key block][k-step]
+#pragma unroll
+    for (int kc = 0; kc < 2; ++kc)
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) xf[kc][ks] = u32x4{0u, 0u, 0u, 0u};
+    bf16x8 qa[8], ga[8], ta[8];   // row-wise Q, dO fragments; transposed fragments [2 ks + ... ]
+    f32x16 nl, nd;                // init values (-lse2, -delta rows) of the next score / dP products
+    f32x16 xa[2], xb[2];          // dV: scores, two sets used alternately
+    f32x16 x1, y1, x0a, x0b, y0a, y0b;   // dK: key block 1 single, key block 0 two sets
+
+    // ---------------------------------------------------------------------------------------------
+    // dV iteration u (half hb of tile T): 32 groups.  On entry xin = S(u), qa = Q fragments of
+    // sub-tile u+1, nl = its init values, ta = transposed dO fragments of sub-tile u-1, xf = P(u-1).
+    // Matrix cores: S(u+1) (groups 0-15), dV^T += dO^T P(u-1) (groups 16-31); vector ALU: P(u).
+    // ---------------------------------------------------------------------------------------------
+    auto stage_dv = [&](auto hb_tag, auto masked_tag, int i0, f32x16 (&xin)[2], f32x16 (&xout)[2],
+                        const TileSrc& ts) __attribute__((always_inline)) {
+        constexpr int hb = decltype(hb_tag)::value;
+        constexpr bool MASKED = decltype(masked_tag)::value;
+        if (MASKED) { mask1(xin[0], 0, i0 + 32 * hb); mask1(xin[1], 1, i0 + 32 * hb); }
+        pin();
+        float pe[32];
+        u32x4 xn[2][2];
+        static_for<32>([&](auto gc) __attribute__((always_inline)) {
+            constexpr int g = decltype(gc)::value;
+            if (g < 16) {
+                const int t8 = g >> 1, kc = g & 1;
+                if (t8 == 0) mma_vd_first(xout[kc], qa[0], kf[kc][0], nl);
+                else         mma_vd(xout[kc], qa[t8], kf[kc][t8]);
+            } else {
+                const int i = g - 16, ks = i >> 3, db = (i >> 1) & 3, kc = i & 1;
+                acc[db][kc] = mma(ta[4 * ks + db], __builtin_bit_cast(bf16x8, xf[kc][ks]), acc[db][kc]);
+            }
+            __builtin_amdgcn_sched_barrier(0);   // the matrix-core instruction leads its group
+            if (hb == 0 && g < 9) dma_piece(ts, g);
+            // refill what the previous two groups used last: for sub-tile u+2 / of sub-tile u
+            if (g == 2) ld_rows(nl, 0, hb);
+            if (g >= 2 && g <= 16 && !(g & 1)) qa[(g - 2) >> 1] = ld_q((g - 2) >> 1, hb);
+            if (g >= 18 && !(g & 1)) ta[(g - 18) >> 1] = ld_t((g - 18) >> 1, hb);
+            {
+                const int kc = g >> 4, r = g & 15;
+                pe[g] = fast_exp2(xin[kc][r]);
+                if (g >= 2 && !(g & 1)) {
+                    const int e = g - 2;
+                    xn[e >> 4][(e & 15) >> 3][(e & 7) >> 1] = pack_bf16x2(pe[e], pe[e + 1]);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        ta[7] = ld_t(7, hb);
+        xn[1][1][3] = pack_bf16x2(pe[30], pe[31]);
 #pragma unroll
         for (int kc = 0; kc < 2; ++kc)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) { s[kc][r] = 0.f; if (IS_DK) dp[kc][r] = 0.f; }
+            for (int ks = 0; ks < 2; ++ks) xf[kc][ks] = xn[kc][ks];
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    // ---------------------------------------------------------------------------------------------
+    // dK iteration u: 48 groups.  Key block 1's scores / dP live in one register set, key block
+    // 0's in two used alternately.  Groups 0-15: dK^T += Q^T dS(u-1) on the matrix cores while the
+    // vector ALU turns block 1 of sub-tile u into dS; groups 16-47: S(u+1), dP(u+1) (block 1's
+    // overwrite what was just consumed) while the vector ALU does block 0.  Fragments are fetched
+    // about six groups ahead of their use.
+    // ---------------------------------------------------------------------------------------------
+    auto stage_dk = [&](auto hb_tag, auto masked_tag, int i0, f32x16& x0in, f32x16& y0in, f32x16& x0out,
+                        f32x16& y0out, const TileSrc& ts, uint32_t tbump) __attribute__((always_inline)) {
+        constexpr int hb = decltype(hb_tag)::value;
+        constexpr bool MASKED = decltype(masked_tag)::value;
+        if (MASKED) { mask1(x0in, 0, i0 + 32 * hb); mask1(x1, 1, i0 + 32 * hb); }
+        pin();
+        float w0[16], w1[16];
+        u32x4 xn[2][2];
+        static_for<48>([&](auto gc) __attribute__((always_inline)) {
+            constexpr int g = decltype(gc)::value;
+            if (g < 16) {
+                const int ks = g >> 3, db = (g >> 1) & 3, kc = g & 1;
+                acc[db][kc] = mma(ta[4 * ks + db], __builtin_bit_cast(bf16x8, xf[kc][ks]), acc[db][kc]);
+            } else {
+                const int j = g - 16, t8 = j >> 2, which = j & 3;   // block 1 first: its results are read first
+                if (which == 0)      { if (t8 == 0) mma_vd_first(x1, qa[0], kf[1][0], nl); else mma_vd(x1, qa[t8], kf[1][t8]); }
+                else if (which == 1) { if (t8 == 0) mma_vd_first(y1, ga[0], vf[1][0], nd); else mma_vd(y1, ga[t8], vf[1][t8]); }
+                else if (which == 2) { if (t8 == 0) mma_vd_first(x0out, qa[0], kf[0][0], nl); else mma_vd(x0out, qa[t8], kf[0][t8]); }
+                else                 { if (t8 == 0) mma_vd_first(y0out, ga[0], vf[0][0], nd); else mma_vd(y0out, ga[t8], vf[0][t8]); }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (hb == 0 && g >= 16 && g < 25) dma_piece(ts, g - 16);
+            // transposed Q fragments of sub-tile u-1 (groups 0-8) and, for the next iteration, u
+            if (g <= 8 && !(g & 1)) ta[3 + (g >> 1)] = ld_t(3 + (g >> 1), 1 - hb);
+            if (hb == 0 && g >= 9 && g < 13) {      // then the addresses move on to tile T
+                tofs[g - 9][0] += tbump;
+                tofs[g - 9][1] += tbump;
+            }
+            if (g >= 42 && !(g & 1)) ta[(g - 42) >> 1] = ld_t((g - 42) >> 1, hb);
+            // row-wise fragments and init values of sub-tile u+1
+            if (g == 6) ld_rows(nl, 0, hb ? 0 : 1);
+            if (g == 8) ld_rows(nd, R_OFF, hb ? 0 : 1);
+            if (g >= 10 && g <= 38 && ((g - 10) & 3) == 0) qa[(g - 10) >> 2] = ld_q((g - 10) >> 2, hb ? 0 : 1);
+            if (g >= 12 && g <= 40 && ((g - 12) & 3) == 0) ga[(g - 12) >> 2] = ld_g((g - 12) >> 2, hb ? 0 : 1);
+            // vector ALU: block 1 element g (groups 0-15), block 0 element (g-16)/2 (even groups after)
+            if (g < 16) {
+                w1[g] = fast_exp2(x1[g]) * y1[g];
+                if (g >= 2 && !(g & 1)) xn[1][(g - 2) >> 3][((g - 2) & 7) >> 1] = pack_bf16x2(w1[g - 2], w1[g - 1]);
+            } else if (!(g & 1)) {
+                const int r = (g - 16) >> 1;
+                if (r == 0) xn[1][1][3] = pack_bf16x2(w1[14], w1[15]);
+                w0[r] = fast_exp2(x0in[r]) * y0in[r];
+                if (r >= 2 && !(r & 1)) xn[0][(r - 2) >> 3][((r - 2) & 7) >> 1] = pack_bf16x2(w0[r - 2], w0[r - 1]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        xn[0][1][3] = pack_bf16x2(w0[14], w0[15]);
+#pragma unroll
+        for (int kc = 0; kc < 2; ++kc)
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) xf[kc][ks] = xn[kc][ks];
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto settle = [&]() __attribute__((always_inline)) { asm volatile("s_nop 15\n\ts_nop 7" ::: "memory"); };
+
+    // ---- prologue: tiles 0 and 1 on their way, scores of sub-tile 0, fragments of sub-tile 1 ----
+    int i0_cur, i0_nx;
+    {
+        const TileSrc t0 = next_tile(0);
+        i0_cur = t0.i0;
+#pragma unroll
+        for (int n = 0; n < 9; ++n) dma_piece(t0, n);
+        dma_wait();
+        __syncthreads();
+        const TileSrc t1 = next_tile(1);
+        i0_nx = t1.i0;
+#pragma unroll
+        for (int n = 0; n < 9; ++n) dma_piece(t1, n);
+        // (dV's row-wise addresses point one buffer ahead: step back for tile 0)
+        constexpr int QB = IS_DK ? 0 : BUF_B, RB = IS_DK ? 0 : BWD_TILE * 4;
 #pragma unroll
         for (int t8 = 0; t8 < 8; ++t8) {
-            const bf16x8 a = PREFETCH ? qa[t8] : lds_frag_n(sm.q[0] + nb * BWD_TILE_B, r0 + lc, 16 * t8 + 8 * lg);
-            s[0] = mma(a, KF_(0, t8), s[0]);
-            s[1] = mma(a, KF_(1, t8), s[1]);
+            qa[t8] = lds_ld_frag(qofs[t8] - QB);
+            if (IS_DK) ga[t8] = lds_ld_frag(qofs[t8] + G_OFF);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const f32x4 a = lds_ld_f32x4(rofs - RB + 8 * j * 4);
+            const f32x4 d = lds_ld_f32x4(rofs - RB + R_OFF + 8 * j * 4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { nl[4 * j + e] = a[e]; nd[4 * j + e] = d[e]; }
+        }
+        f32x16 (&s0)[2] = xa;
+#pragma unroll
+        for (int t8 = 0; t8 < 8; ++t8) {
             if (IS_DK) {
-                const bf16x8 a2 = lds_frag_n(sm.g[0] + nb * BWD_TILE_B, r0 + lc, 16 * t8 + 8 * lg);
-                dp[0] = mma(a2, VF_(0, t8), dp[0]);
-                dp[1] = mma(a2, VF_(1, t8), dp[1]);
+                if (t8 == 0) { mma_vd_first(x0a, qa[0], kf[0][0], nl); mma_vd_first(x1, qa[0], kf[1][0], nl);
+                               mma_vd_first(y0a, ga[0], vf[0][0], nd); mma_vd_first(y1, ga[0], vf[1][0], nd); }
+                else         { mma_vd(x0a, qa[t8], kf[0][t8]); mma_vd(x1, qa[t8], kf[1][t8]);
+                               mma_vd(y0a, ga[t8], vf[0][t8]); mma_vd(y1, ga[t8], vf[1][t8]); }
+            } else {
+                if (t8 == 0) { mma_vd_first(s0[0], qa[0], kf[0][0], nl); mma_vd_first(s0[1], qa[0], kf[1][0], nl); }
+                else         { mma_vd(s0[0], qa[t8], kf[0][t8]);         mma_vd(s0[1], qa[t8], kf[1][t8]); }
             }
         }
+        settle();
+        if (IS_DK) {
+            // steady state on entry of the first iteration: fragments of sub-tile u-1 for the
+            // matrix cores (xf = 0: a placeholder tile), nothing else carried
+#pragma unroll
+            for (int p = 0; p < 3; ++p) ta[p] = ld_t(p, 0);
+        } else {
+#pragma unroll
+            for (int t8 = 0; t8 < 8; ++t8) qa[t8] = lds_ld_frag(qofs[t8] - BUF_B + 32 * ROW_B);   // sub-tile 1
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const f32x4 a = lds_ld_f32x4(rofs - BWD_TILE * 4 + (32 + 8 * j) * 4);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) nl[4 * j + e] = a[e];
+            }
+#pragma unroll
+            for (int p = 0; p < 8; ++p) ta[p] = ld_t(p, 0);     // placeholder: multiplied by P = 0
+        }
+    }
+    // Tile T lives in buffer T % NBUF.  The one barrier per tile publishes tile T+1 and retires
+    // the buffer that receives tile T+2.
+    int buf = 0;
+    bool first = true;
+    auto tile_iter = [&](auto masked_tag) __attribute__((always_inline)) {
+        const int nbuf = buf + 1 == NBUF ? 0 : buf + 1;
+        const int nnbuf = nbuf + 1 == NBUF ? 0 : nbuf + 1;
+        const TileSrc ts = next_tile(nnbuf);
+        const uint32_t fwd = static_cast<uint32_t>(BUF_B), back = static_cast<uint32_t>(-(NBUF - 1) * BUF_B);
+        const uint32_t rfwd = static_cast<uint32_t>(BWD_TILE * 4), rback = static_cast<uint32_t>(-(NBUF - 1) * BWD_TILE * 4);
+        dma_wait();
+        __syncthreads();
+        if (IS_DK) {
+            // the transposed reads still address tile T-1 when the iteration starts (the very
+            // first iteration has no predecessor: its placeholder is tile 0 itself)
+            const uint32_t tb = first ? 0u : (buf == 0 ? back : fwd);
+            stage_dk(std::integral_constant<int, 0>{}, masked_tag, i0_cur, x0a, y0a, x0b, y0b, ts, tb);
+            // the row-wise reads move on to tile T+1 between the two halves
+#pragma unroll
+            for (int t8 = 0; t8 < 8; ++t8) qofs[t8] += nbuf == 0 ? back : fwd;
+            rofs += nbuf == 0 ? rback : rfwd;
+            stage_dk(std::integral_constant<int, 1>{}, masked_tag, i0_cur, x0b, y0b, x0a, y0a, ts, 0u);
+        } else {
+            stage_dv(std::integral_constant<int, 0>{}, masked_tag, i0_cur, xa, xb, ts);
+            stage_dv(std::integral_constant<int, 1>{}, masked_tag, i0_cur, xb, xa, ts);
+#pragma unroll
+            for (int db = 0; db < 4; ++db) {                 // tile T -> T+1
+                tofs[db][0] += nbuf == 0 ? back : fwd;
+                tofs[db][1] += nbuf == 0 ? back : fwd;
+            }
+#pragma unroll
+            for (int t8 = 0; t8 < 8; ++t8) qofs[t8] += nnbuf == 0 ? back : fwd;   // tile T+1 -> T+2
+            rofs += nnbuf == 0 ? rback : rfwd;
+        }
+        first = false;
+        buf = nbuf;
+        i0_cur = i0_nx;
+        i0_nx = ts.i0;
     };
-    // Iteration u (sub-tile hb of streamed tile T, in LDS buffer buf; nbuf holds tile T+1).  On
-    // entry: s (dp) = scores of sub-tile u, qa (ga) = row-wise fragments of sub-tile u+1,
-    // ta = transposed fragments of sub-tile u-1, xf = P / dS of sub-tile u-1.
-    auto stage = [&](int T, int hb, int buf, int nbuf) __attribute__((always_inline)) {
-        // scores of sub-tile u move to ordinary registers (their accumulators are reused); the
-        // rare masked sub-tile is patched here, outside the main block
-        f32x16 x[2] = {s[0], s[1]};
-        f32x16 y[2];
-        if (IS_DK) { y[0] = dp[0]; y[1] = dp[1]; }
-        if (needs_mask(T, hb)) mask(x, T, hb);
+    for (int T = 0; T < nMain; ++T) tile_iter(std::false_type{});
+    for (int T = nMain; T < nT; ++T) tile_iter(std::true_type{});
+    {   // drain: the last sub-tile's contribution
         pin();
-        scores(hb ? nbuf : buf, hb ? 0 : 32);
-        // (dK: transposed fragments of sub-tile u-1 read here; the very first iteration has no
-        // predecessor and multiplies tile 0 by xf = 0)
-        if (!PREFETCH) load_tr((hb || T == 0) ? buf : (buf + NBUF - 1) % NBUF, hb ? 0 : 32);
+        if (IS_DK) {
+            // fragments 0-2 of the last sub-tile are in registers; the others come from the last
+            // tile's second half (the transposed-read addresses are on that tile)
+#pragma unroll
+            for (int p = 3; p < 8; ++p) ta[p] = ld_t(p, 1);
+        }
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
             for (int db = 0; db < 4; ++db) {
-                acc[db][0] = mma(ta[ks][db], xf[0][ks], acc[db][0]);
-                acc[db][1] = mma(ta[ks][db], xf[1][ks], acc[db][1]);
+                acc[db][0] = mma(ta[4 * ks + db], __builtin_bit_cast(bf16x8, xf[0][ks]), acc[db][0]);
+                acc[db][1] = mma(ta[4 * ks + db], __builtin_bit_cast(bf16x8, xf[1][ks]), acc[db][1]);
             }
-        // fragments for the next iteration: row-wise of sub-tile u+2, transposed of sub-tile u
-        if (PREFETCH) {
-            load_nat(nbuf, 32 * hb);
-            load_tr(buf, 32 * hb);
-        }
-        // per-row lse2 / delta of this sub-tile (rows 8 j + 4 g + (0..3)) are read from LDS four
-        // rows at a time, right where they are used
-        f32x16 w[2];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const f32x4 lr = *reinterpret_cast<const f32x4*>(&sm.l2[buf][32 * hb + 8 * j + 4 * lg]);
-            f32x4 dr = {0.f, 0.f, 0.f, 0.f};
-            if (IS_DK) dr = *reinterpret_cast<const f32x4*>(&sm.dl[buf][32 * hb + 8 * j + 4 * lg]);
-#pragma unroll
-            for (int kc = 0; kc < 2; ++kc)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int r = 4 * j + e;
-                    const float p = fast_exp2(fmaf(x[kc][r], c, -lr[e]));
-                    w[kc][r] = IS_DK ? p * (y[kc][r] - dr[e]) : p;
-                }
-        }
-#pragma unroll
-        for (int kc = 0; kc < 2; ++kc) {
-            xf[kc][0] = pack_frag(w[kc], 0);
-            xf[kc][1] = pack_frag(w[kc], 8);
-        }
-        // consumed only by the next iteration: anchored here so that their instructions stay in
-        // this block, next to the matrix-core work
-#pragma unroll
-        for (int kc = 0; kc < 2; ++kc) asm volatile("" : "+v"(xf[kc][0]), "+v"(xf[kc][1]));
-        if (PREFETCH) {
-#pragma unroll
-            for (int t8 = 0; t8 < 8; ++t8) asm volatile("" : "+v"(qa[t8]));
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-                for (int db = 0; db < 4; ++db) asm volatile("" : "+v"(ta[ks][db]));
-        }
-    };
-
-    issue(0, 0);
-    dma_wait();
-    __syncthreads();
-    issue(min(1, nT - 1), 1);
-    pin();
-    if (PREFETCH) load_nat(0, 0);
-    scores(0, 0);             // sub-tile 0
-    if (PREFETCH) {
-        load_nat(0, 32);      // row-wise fragments of sub-tile 1
-        load_tr(0, 0);        // placeholder for "sub-tile -1": multiplied by xf = 0
     }
-    // Streamed tile T lives in buffer T % NBUF.  The one barrier per tile opens the iteration of
-    // the tile's first sub-tile: it publishes tile T+1 and retires the buffer of the oldest tile
-    // no longer read (T-1 with prefetched fragments, T-2 without), which receives tile T+2.
-    int buf = 0;
-    for (int T = 0; T < nT; ++T) {
-        const int nbuf = (buf + 1) % NBUF;
-        dma_wait();
-        __syncthreads();
-        issue(min(T + 2, nT - 1), (buf + 2) % NBUF);
-        stage(T, 0, buf, nbuf);
-        stage(T, 1, buf, nbuf);
-        buf = nbuf;
-    }
-    if (!PREFETCH) load_tr((buf + NBUF - 1) % NBUF, 32);
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks)      // drain: the last sub-tile's contribution
-#pragma unroll
-        for (int db = 0; db < 4; ++db) {
-            acc[db][0] = mma(ta[ks][db], xf[0][ks], acc[db][0]);
-            acc[db][1] = mma(ta[ks][db], xf[1][ks], acc[db][1]);
-        }
     const float mul = IS_DK ? scale : 1.f;
 #pragma unroll
     for (int kc = 0; kc < 2; ++kc) {
