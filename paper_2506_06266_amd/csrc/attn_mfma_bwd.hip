@@ -81,20 +81,30 @@ __device__ __forceinline__ void store_rows_f32(const f32x16 (&acc)[4], float* ro
 // =================================================================================================
 // dQ: queries stationary
 // =================================================================================================
-// four buffers: the transposed K fragments of a tile's last sub-tile are fetched one iteration
-// after the tile's other reads, so a tile's buffer is retired one tile later than in the other
-// kernels
+// One workgroup = 256 consecutive queries of one (sequence, query head); each wavefront keeps its
+// 64 queries' Q (scaled by c = softmax_scale * log2(e)) and dO as B-operand fragments in
+// accumulation registers, next to the dQ^T accumulators.  Key tiles (K and V rows) stream through
+// LDS in the forward kernel's order: first the tiles every query sees entirely, through a loop
+// without masking code, then the ragged prefix tile and the diagonal tiles through a copy that
+// masks.  Per sub-tile of 32 keys:
+//   S^T = K Q^T, dP^T = V dO^T,  dS^T = 2^(S^T - lse2) (dP^T - delta),  dQ^T += K^T dS^T.
+// The iteration is laid out like the dK kernel's: 48 fenced groups; the scores / dP of query
+// block 1 live in one register set, those of block 0 in two used alternately; the transposed K
+// fragments of the previous sub-tile are fetched a few groups ahead, so a tile is read over
+// three tile iterations: four buffers.
 constexpr int DQ_NBUF = 4;
 struct DqSmem {
-    char k[DQ_NBUF][BWD_TILE_B];
-    char v[DQ_NBUF][BWD_TILE_B];
+    struct { char k[BWD_TILE_B]; char v[BWD_TILE_B]; } t[DQ_NBUF];
 };
 
 __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
     const bf16_t* __restrict__ zk, const bf16_t* __restrict__ zv, const bf16_t* __restrict__ d_o,
-    const float* __restrict__ lse2, const float* __restrict__ delta, bf16_t* __restrict__ dq, int B,
+    const float* __restrict__ nlse2, const float* __restrict__ ndelta, bf16_t* __restrict__ dq, int B,
     int S, int Hq, int Hkv, int P, float c, float scale) {
+    constexpr int NBUF = DQ_NBUF;
+    constexpr int BUF_B = 2 * BWD_TILE_B;
+    constexpr int V_OFF = BWD_TILE_B;
     __shared__ DqSmem sm;
     const int G = Hq / Hkv;
     const int nQt = (S + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
@@ -109,7 +119,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
     const int q0 = qt * BWD_WG_ROWS, wrow0 = q0 + 64 * wv;
 
     u32x4 qf[2][8], gf[2][8];     // B operands: column = query, k = head element
-    float l2[2], dl[2];     // -lse2, -delta of the lane's queries
+    float nl2[2], ndl[2];         // -lse2, -delta of the lane's queries
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb) {
         int qi = wrow0 + 32 * cb + lc;
@@ -117,36 +127,16 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
         const size_t row = (static_cast<size_t>(b) * S + qi) * Hq + h;
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
-            qf[cb][t] = *reinterpret_cast<const u32x4*>(q + row * HD + 8 * lg + 16 * t);
+            const u32x4 w = *reinterpret_cast<const u32x4*>(q + row * HD + 8 * lg + 16 * t);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                qf[cb][t][i] = pack_bf16x2(__uint_as_float(w[i] << 16) * c, __uint_as_float(w[i] & 0xffff0000u) * c);
             gf[cb][t] = *reinterpret_cast<const u32x4*>(d_o + row * HD + 8 * lg + 16 * t);
         }
         const size_t st = (static_cast<size_t>(b) * Hq + h) * S + qi;
-        l2[cb] = lse2[st];
-        dl[cb] = delta[st];
+        nl2[cb] = nlse2[st];
+        ndl[cb] = ndelta[st];
     }
-#define QF_(cb, t) __builtin_bit_cast(bf16x8, qf[cb][t])
-#define GF_(cb, t) __builtin_bit_cast(bf16x8, gf[cb][t])
-
-    const int nPt = (P + BWD_TILE - 1) / BWD_TILE;
-    const int own_end = min(S, q0 + BWD_WG_ROWS);
-    const int nT = nPt + (own_end + BWD_TILE - 1) / BWD_TILE;
-    const char* zk_b = reinterpret_cast<const char*>(zk) + static_cast<size_t>(hk) * P * ROW_B;
-    const char* zv_b = reinterpret_cast<const char*>(zv) + static_cast<size_t>(hk) * P * ROW_B;
-    const size_t own_pitch = static_cast<size_t>(Hkv) * ROW_B;
-    const char* k_b = reinterpret_cast<const char*>(k) + (static_cast<size_t>(b) * S * Hkv + hk) * ROW_B;
-    const char* v_b = reinterpret_cast<const char*>(v) + (static_cast<size_t>(b) * S * Hkv + hk) * ROW_B;
-
-    auto issue = [&](int t, int buf) __attribute__((always_inline)) {
-        const bool pre = t < nPt;
-        const int j0 = (pre ? t : t - nPt) * BWD_TILE;
-        const int last = (pre ? P : S) - 1;
-        const uint32_t pitch = pre ? static_cast<uint32_t>(ROW_B) : static_cast<uint32_t>(own_pitch);
-        const char* kb = pre ? zk_b : k_b;
-        const char* vb = pre ? zv_b : v_b;
-        tile_load_async<BWD_TILE>(sm.k[buf], kb, j0, last, pitch);
-        tile_load_async<BWD_TILE>(sm.v[buf], vb, j0, last, pitch);
-    };
-
     f32x16 acc[4][2];   // dQ^T: [head-element block][query block]
 #pragma unroll
     for (int db = 0; db < 4; ++db)
@@ -154,148 +144,207 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
         for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[db][cb][r] = 0.f;
-    f32x16 s[2], dp[2];
-    bf16x8 dsf[2][2];     // dS^T of sub-tile u-1 as B-operand fragments [query block][k-step]
-#pragma unroll
-    for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) dsf[cb][ks] = bf16x8{};
-
-    auto needs_mask = [&](int t, int hb) __attribute__((always_inline)) {
-        return t < nPt ? (t * BWD_TILE + 32 * hb + 32 > P) : ((t - nPt) * BWD_TILE + 32 * hb + 31 > wrow0);
-    };
-    auto mask = [&](f32x16 (&x)[2], int t, int hb) __attribute__((always_inline)) {
-        const bool own = t >= nPt;
-        const int j0 = (own ? t - nPt : t) * BWD_TILE + 32 * hb;
-#pragma unroll
-        for (int cb = 0; cb < 2; ++cb) {
-            const int thr = (own ? wrow0 + 32 * cb + lc : P - 1) - j0 - 4 * lg;
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-                if (8 * (r >> 2) + (r & 3) > thr) x[cb][r] = NEG_BIG;
-        }
-    };
-#ifndef CART_DQ_PIN_Q
-#define CART_DQ_PIN_Q 1
-#endif
-#ifndef CART_DQ_PREFETCH_V
-#define CART_DQ_PREFETCH_V 0
-#endif
     auto pin = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
             for (int t = 0; t < 8; ++t) {
-#if CART_DQ_PIN_Q
                 asm volatile("" : "+a"(qf[cb][t]));
-#endif
+                asm volatile("" : "+a"(gf[cb][t]));
             }
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
             for (int cb = 0; cb < 2; ++cb) asm volatile("" : "+a"(acc[db][cb]));
     };
-    // row-wise K (and V) fragments of sub-tile u+1 are fetched one iteration ahead (loop-carried)
-    bf16x8 ka[8], va[8];
-    auto load_nat = [&](int buf, int r0, bool with_v) __attribute__((always_inline)) {
-#pragma unroll
-        for (int t8 = 0; t8 < 8; ++t8) {
-            ka[t8] = lds_frag_n(sm.k[0] + buf * BWD_TILE_B, r0 + lc, 16 * t8 + 8 * lg);
-            if (with_v) va[t8] = lds_frag_n(sm.v[0] + buf * BWD_TILE_B, r0 + lc, 16 * t8 + 8 * lg);
-        }
+    pin();
+
+    // tile order: see the forward kernel
+    const int nPf = P / BWD_TILE;
+    const int rag = (P % BWD_TILE) ? 1 : 0;
+    const int nOf = q0 / BWD_TILE;
+    const int own_end = min(S, q0 + BWD_WG_ROWS);
+    const int nMain = nPf + nOf;
+    const int nT = nMain + rag + (own_end + BWD_TILE - 1) / BWD_TILE - nOf;
+    const char* zk_b = reinterpret_cast<const char*>(zk) + static_cast<size_t>(hk) * P * ROW_B;
+    const char* zv_b = reinterpret_cast<const char*>(zv) + static_cast<size_t>(hk) * P * ROW_B;
+    const uint32_t own_pitch = static_cast<uint32_t>(Hkv) * ROW_B;
+    const char* k_b = reinterpret_cast<const char*>(k) + (static_cast<size_t>(b) * S * Hkv + hk) * ROW_B;
+    const char* v_b = reinterpret_cast<const char*>(v) + (static_cast<size_t>(b) * S * Hkv + hk) * ROW_B;
+    auto tile_pre = [&](int t) __attribute__((always_inline)) { return t < nPf || (rag && t == nMain); };
+    auto tile_j0 = [&](int t) __attribute__((always_inline)) {
+        return (t < nPf ? t : t < nMain ? t - nPf : (rag && t == nMain) ? nPf : t - nPf - rag) * BWD_TILE;
     };
-    auto scores = [&](int vbuf, int vr0) __attribute__((always_inline)) {
+    const uint32_t dma_c0 = (lane & 15) ^ (((lane >> 4) & 3) << 2);
+    struct TileSrc { const char* kb; const char* vb; int lim; uint32_t pitch; uint32_t lds_k, lds_v; };
+    auto tile_src = [&](int t, int buf) __attribute__((always_inline)) {
+        const bool pre = tile_pre(t);
+        const int j0 = tile_j0(t);
+        TileSrc ts;
+        ts.pitch = pre ? static_cast<uint32_t>(ROW_B) : own_pitch;
+        ts.kb = (pre ? zk_b : k_b) + static_cast<size_t>(j0) * ts.pitch;
+        ts.vb = (pre ? zv_b : v_b) + static_cast<size_t>(j0) * ts.pitch;
+        ts.lim = (pre ? P : S) - 1 - j0;
+        ts.lds_k = lds_addr(sm.t[buf].k);
+        ts.lds_v = lds_addr(sm.t[buf].v);
+        return ts;
+    };
+    auto dma_piece = [&](const TileSrc& ts, int n) __attribute__((always_inline)) {
+        const int i = n & 3;
+        const int r0 = (4 * wv + i) * 4;
+        const uint32_t voff = __umul24(min(r0 + (lane >> 4), ts.lim), ts.pitch) + ((dma_c0 ^ i) << 4);
+        if (n < 4) dma16(ts.kb, voff, ts.lds_k + r0 * ROW_B);
+        else       dma16(ts.vb, voff, ts.lds_v + r0 * ROW_B);
+    };
+    // hidden entries of query block cb in the scores of the sub-tile whose first key is j0
+    auto mask1 = [&](f32x16& x, int cb, bool pre, int j0) __attribute__((always_inline)) {
+        const int thr = (pre ? P - 1 : wrow0 + 32 * cb + lc) - j0 - 4 * lg;
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            if (8 * (r >> 2) + (r & 3) > thr) x[r] = NEG_BIG;
+    };
+
+    // per-lane LDS addresses: row-wise K fragments (V: + V_OFF) of the tile of sub-tile u+1,
+    // transposed K fragments of the tile of sub-tile u-1 (they follow half a tile iteration later)
+    uint32_t kofs[8], tofs[4][2];
+    {
+        const uint32_t t0 = lds_addr(sm.t[0].k);
+#pragma unroll
+        for (int t8 = 0; t8 < 8; ++t8) kofs[t8] = t0 + frag_n_ofs(lane, t8);
+#pragma unroll
+        for (int db = 0; db < 4; ++db) {
+            frag_t_ofs(lane, db, tofs[db][0], tofs[db][1]);
+            tofs[db][0] += t0;
+            tofs[db][1] += t0;
+        }
+    }
+    auto ld_k = [&](int t8, int hb) __attribute__((always_inline)) { return lds_ld_frag(kofs[t8] + hb * 32 * ROW_B); };
+    auto ld_v = [&](int t8, int hb) __attribute__((always_inline)) { return lds_ld_frag(kofs[t8] + V_OFF + hb * 32 * ROW_B); };
+    auto ld_t = [&](int p, int hb) __attribute__((always_inline)) {
+        const int ks = p >> 2, db = p & 3;
+        return lds_ld_frag_t(tofs[db][0] + (32 * hb + 16 * ks) * ROW_B, tofs[db][1] + (32 * hb + 16 * ks) * ROW_B);
+    };
+
+    u32x4 dsf[2][2];      // dS^T of sub-tile u-1 as B-operand fragments [query block][k-step]
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) dsf[cb][ks] = u32x4{0u, 0u, 0u, 0u};
+    bf16x8 ka[8], va[8], ta[8];
+    f32x16 x1, y1, x0a, x0b, y0a, y0b;
+
+    // Iteration u (half hb of tile T).  Groups 0-15: dQ^T += K^T dS^T(u-1) on the matrix cores
+    // while the vector ALU turns query block 1 of sub-tile u into dS^T; groups 16-47: S^T(u+1),
+    // dP^T(u+1) (block 1's overwrite what was just consumed) while the vector ALU does block 0.
+    auto stage = [&](auto hb_tag, auto masked_tag, bool pre, int j0, f32x16& x0in, f32x16& y0in, f32x16& x0out,
+                     f32x16& y0out, const TileSrc& ts, uint32_t tbump) __attribute__((always_inline)) {
+        constexpr int hb = decltype(hb_tag)::value;
+        constexpr bool MASKED = decltype(masked_tag)::value;
+        if (MASKED) { mask1(x0in, 0, pre, j0 + 32 * hb); mask1(x1, 1, pre, j0 + 32 * hb); }
+        pin();
+        float w0[16], w1[16];
+        u32x4 dn[2][2];
+        static_for<48>([&](auto gc) __attribute__((always_inline)) {
+            constexpr int g = decltype(gc)::value;
+            if (g < 16) {
+                const int ks = g >> 3, db = (g >> 1) & 3, cb = g & 1;
+                acc[db][cb] = mma(ta[4 * ks + db], __builtin_bit_cast(bf16x8, dsf[cb][ks]), acc[db][cb]);
+            } else {
+                const int j = g - 16, t8 = j >> 2, which = j & 3;   // block 1 first: its results are read first
+                if (which == 0)      { if (t8 == 0) mma_vd_zero(x1, ka[0], qf[1][0]); else mma_vd(x1, ka[t8], qf[1][t8]); }
+                else if (which == 1) { if (t8 == 0) mma_vd_zero(y1, va[0], gf[1][0]); else mma_vd(y1, va[t8], gf[1][t8]); }
+                else if (which == 2) { if (t8 == 0) mma_vd_zero(x0out, ka[0], qf[0][0]); else mma_vd(x0out, ka[t8], qf[0][t8]); }
+                else                 { if (t8 == 0) mma_vd_zero(y0out, va[0], gf[0][0]); else mma_vd(y0out, va[t8], gf[0][t8]); }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (hb == 0 && g >= 16 && g < 24) dma_piece(ts, g - 16);
+            // transposed K fragments of sub-tile u-1 (groups 0-8) and, for the next iteration, u
+            if (g <= 8 && !(g & 1)) ta[3 + (g >> 1)] = ld_t(3 + (g >> 1), 1 - hb);
+            if (hb == 0 && g >= 9 && g < 13) {      // then the addresses move on to tile T
+                tofs[g - 9][0] += tbump;
+                tofs[g - 9][1] += tbump;
+            }
+            if (g >= 42 && !(g & 1)) ta[(g - 42) >> 1] = ld_t((g - 42) >> 1, hb);
+            // row-wise fragments of sub-tile u+1
+            if (g >= 10 && g <= 38 && ((g - 10) & 3) == 0) ka[(g - 10) >> 2] = ld_k((g - 10) >> 2, hb ? 0 : 1);
+            if (g >= 12 && g <= 40 && ((g - 12) & 3) == 0) va[(g - 12) >> 2] = ld_v((g - 12) >> 2, hb ? 0 : 1);
+            // vector ALU: block 1 element g (groups 0-15), block 0 element (g-16)/2 (even groups after)
+            if (g < 16) {
+                w1[g] = fast_exp2(x1[g] + nl2[1]) * (y1[g] + ndl[1]);
+                if (g >= 2 && !(g & 1)) dn[1][(g - 2) >> 3][((g - 2) & 7) >> 1] = pack_bf16x2(w1[g - 2], w1[g - 1]);
+            } else if (!(g & 1)) {
+                const int r = (g - 16) >> 1;
+                if (r == 0) dn[1][1][3] = pack_bf16x2(w1[14], w1[15]);
+                w0[r] = fast_exp2(x0in[r] + nl2[0]) * (y0in[r] + ndl[0]);
+                if (r >= 2 && !(r & 1)) dn[0][(r - 2) >> 3][((r - 2) & 7) >> 1] = pack_bf16x2(w0[r - 2], w0[r - 1]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        dn[0][1][3] = pack_bf16x2(w0[14], w0[15]);
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) { s[cb][r] = 0.f; dp[cb][r] = 0.f; }
-#pragma unroll
-        for (int t8 = 0; t8 < 8; ++t8) {
-            s[0] = mma(ka[t8], QF_(0, t8), s[0]);
-            s[1] = mma(ka[t8], QF_(1, t8), s[1]);
-#if CART_DQ_PREFETCH_V
-            const bf16x8 a2 = va[t8];
-#else
-            const bf16x8 a2 = lds_frag_n(sm.v[0] + vbuf * BWD_TILE_B, vr0 + lc, 16 * t8 + 8 * lg);
-#endif
-            dp[0] = mma(a2, GF_(0, t8), dp[0]);
-            dp[1] = mma(a2, GF_(1, t8), dp[1]);
-        }
+            for (int ks = 0; ks < 2; ++ks) dsf[cb][ks] = dn[cb][ks];
+        __builtin_amdgcn_sched_barrier(0);
     };
-    // Iteration u (sub-tile hb of tile t in buffer buf; nbuf holds tile t+1).  On entry: s, dp =
-    // scores of sub-tile u; ka (va) = row-wise fragments of sub-tile u+1; dsf = dS^T(u-1).
-    auto stage = [&](int t, int hb, int buf, int nbuf) __attribute__((always_inline)) {
-        f32x16 x[2] = {s[0], s[1]};
-        f32x16 y[2] = {dp[0], dp[1]};
-        if (needs_mask(t, hb)) mask(x, t, hb);
-        pin();
-        // matrix cores: scores of sub-tile u+1, dQ^T += K^T(u-1) dS^T(u-1)
-        scores(hb ? nbuf : buf, hb ? 0 : 32);
-        // (the very first iteration has no predecessor: it multiplies tile 0 by dS = 0)
-        const char* kt_prev = sm.k[0] + ((hb || t == 0) ? buf : ((buf + DQ_NBUF - 1) & (DQ_NBUF - 1))) * BWD_TILE_B;
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-            for (int db = 0; db < 4; ++db) {
-                const bf16x8 a = lds_frag_t(kt_prev, (hb ? 0 : 32) + 16 * ks, 32 * db, lane);
-                acc[db][0] = mma(a, dsf[0][ks], acc[db][0]);
-                acc[db][1] = mma(a, dsf[1][ks], acc[db][1]);
-            }
-        // row-wise fragments of sub-tile u+2
-        load_nat(nbuf, 32 * hb, CART_DQ_PREFETCH_V);
-        // vector ALU: dS^T of sub-tile u
-#pragma unroll
-        for (int cb = 0; cb < 2; ++cb) {
-            f32x16 w;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float p = fast_exp2(fmaf(x[cb][r], c, l2[cb]));
-                w[r] = p * (y[cb][r] + dl[cb]);
-            }
-            dsf[cb][0] = pack_frag(w, 0);
-            dsf[cb][1] = pack_frag(w, 8);
-        }
-#pragma unroll
-        for (int cb = 0; cb < 2; ++cb) asm volatile("" : "+v"(dsf[cb][0]), "+v"(dsf[cb][1]));
-#pragma unroll
-        for (int t8 = 0; t8 < 8; ++t8) {
-            asm volatile("" : "+v"(ka[t8]));
-#if CART_DQ_PREFETCH_V
-            asm volatile("" : "+v"(va[t8]));
-#endif
-        }
-    };
+    auto settle = [&]() __attribute__((always_inline)) { asm volatile("s_nop 15\n\ts_nop 7" ::: "memory"); };
 
-    issue(0, 0);
-    dma_wait();
-    __syncthreads();
-    issue(min(1, nT - 1), 1);
-    pin();
-    load_nat(0, 0, CART_DQ_PREFETCH_V);
-    scores(0, 0);                          // sub-tile 0
-    load_nat(0, 32, CART_DQ_PREFETCH_V);   // sub-tile 1
-    // Tile t lives in buffer t % 4.  The one barrier per tile opens the iteration of the tile's
-    // first sub-tile: it publishes tile t+1 and retires tile t-2's buffer (tile t-1's transposed
-    // K is still read in this iteration), which then receives tile t+2.
-    int buf = 0;
-    for (int t = 0; t < nT; ++t) {
-        const int nbuf = (buf + 1) & (DQ_NBUF - 1);
+    {   // prologue: tiles 0 and 1 on their way, scores of sub-tile 0
+        const TileSrc t0 = tile_src(0, 0);
+#pragma unroll
+        for (int n = 0; n < 8; ++n) dma_piece(t0, n);
         dma_wait();
         __syncthreads();
-        issue(min(t + 2, nT - 1), (buf + 2) & (DQ_NBUF - 1));
-        stage(t, 0, buf, nbuf);
-        stage(t, 1, buf, nbuf);
-        buf = nbuf;
+        const TileSrc t1 = tile_src(min(1, nT - 1), 1);
+#pragma unroll
+        for (int n = 0; n < 8; ++n) dma_piece(t1, n);
+#pragma unroll
+        for (int t8 = 0; t8 < 8; ++t8) { ka[t8] = ld_k(t8, 0); va[t8] = ld_v(t8, 0); }
+#pragma unroll
+        for (int t8 = 0; t8 < 8; ++t8) {
+            if (t8 == 0) { mma_vd_zero(x0a, ka[0], qf[0][0]); mma_vd_zero(x1, ka[0], qf[1][0]);
+                           mma_vd_zero(y0a, va[0], gf[0][0]); mma_vd_zero(y1, va[0], gf[1][0]); }
+            else         { mma_vd(x0a, ka[t8], qf[0][t8]); mma_vd(x1, ka[t8], qf[1][t8]);
+                           mma_vd(y0a, va[t8], gf[0][t8]); mma_vd(y1, va[t8], gf[1][t8]); }
+        }
+        settle();
+#pragma unroll
+        for (int p = 0; p < 3; ++p) ta[p] = ld_t(p, 0);     // placeholder: multiplied by dS = 0
     }
-    {   // drain: dQ^T += K^T dS^T of the last sub-tile
-        const char* kt_prev = sm.k[0] + ((buf + DQ_NBUF - 1) & (DQ_NBUF - 1)) * BWD_TILE_B;
+    int buf = 0;
+    bool first = true;
+    auto tile_iter = [&](int T, auto masked_tag) __attribute__((always_inline)) {
+        const int nbuf = buf + 1 == NBUF ? 0 : buf + 1;
+        const int nnbuf = nbuf + 1 == NBUF ? 0 : nbuf + 1;
+        const TileSrc ts = tile_src(min(T + 2, nT - 1), nnbuf);
+        const bool pre = tile_pre(T);
+        const int j0 = tile_j0(T);
+        const uint32_t fwd = static_cast<uint32_t>(BUF_B), back = static_cast<uint32_t>(-(NBUF - 1) * BUF_B);
+        dma_wait();
+        __syncthreads();
+        // the transposed reads still address tile T-1 when the iteration starts (the very first
+        // iteration has no predecessor: its placeholder is tile 0 itself)
+        const uint32_t tb = first ? 0u : (buf == 0 ? back : fwd);
+        stage(std::integral_constant<int, 0>{}, masked_tag, pre, j0, x0a, y0a, x0b, y0b, ts, tb);
+        // the row-wise reads move on to tile T+1 between the two halves
+#pragma unroll
+        for (int t8 = 0; t8 < 8; ++t8) kofs[t8] += nbuf == 0 ? back : fwd;
+        stage(std::integral_constant<int, 1>{}, masked_tag, pre, j0, x0b, y0b, x0a, y0a, ts, 0u);
+        first = false;
+        buf = nbuf;
+    };
+    for (int T = 0; T < nMain; ++T) tile_iter(T, std::false_type{});
+    for (int T = nMain; T < nT; ++T) tile_iter(T, std::true_type{});
+    {   // drain: dQ^T += K^T dS^T of the last sub-tile (fragments 0-2 are in registers)
+        pin();
+#pragma unroll
+        for (int p = 3; p < 8; ++p) ta[p] = ld_t(p, 1);
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
             for (int db = 0; db < 4; ++db) {
-                const bf16x8 a = lds_frag_t(kt_prev, 32 + 16 * ks, 32 * db, lane);
-                acc[db][0] = mma(a, dsf[0][ks], acc[db][0]);
-                acc[db][1] = mma(a, dsf[1][ks], acc[db][1]);
+                acc[db][0] = mma(ta[4 * ks + db], __builtin_bit_cast(bf16x8, dsf[0][ks]), acc[db][0]);
+                acc[db][1] = mma(ta[4 * ks + db], __builtin_bit_cast(bf16x8, dsf[1][ks]), acc[db][1]);
             }
     }
 #pragma unroll
