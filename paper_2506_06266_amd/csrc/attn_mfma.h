@@ -160,6 +160,9 @@ __device__ __forceinline__ void dma4(const char* base, uint32_t voff, uint32_t l
 }
 // every direct-to-LDS load of this wavefront has landed
 __device__ __forceinline__ void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// all but the wavefront's N most recent direct-to-LDS loads have landed
+template <int N>
+__device__ __forceinline__ void dma_wait_but() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory"); }
 
 // Tile of ROWS rows x 256 bytes -> LDS (row r at 256 r, 16-byte chunks swizzled), cooperatively
 // by the 4 wavefronts of a 256-thread workgroup.  One load instruction moves 64 chunks = 4 tile

@@ -90,7 +90,7 @@ __device__ __forceinline__ void store_rows_f32(const f32x16 (&acc)[4], float* ro
 //   S^T = K Q^T, dP^T = V dO^T,  dS^T = 2^(S^T - lse2) (dP^T - delta),  dQ^T += K^T dS^T.
 // The iteration is laid out like the dK kernel's: 48 fenced groups; the scores / dP of query
 // block 1 live in one register set, those of block 0 in two used alternately; the transposed K
-// fragments of the previous sub-tile are fetched a few groups ahead, so a tile is read over
+// fragments of the previous sub-tile are fetched about ten groups ahead, so a tile is read over
 // three tile iterations: four buffers.
 constexpr int DQ_NBUF = 4;
 struct DqSmem {
@@ -259,15 +259,15 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
             __builtin_amdgcn_sched_barrier(0);
             if (hb == 0 && g >= 16 && g < 24) dma_piece(ts, g - 16);
             // transposed K fragments of sub-tile u-1 (groups 0-8) and, for the next iteration, u
-            if (g <= 8 && !(g & 1)) ta[3 + (g >> 1)] = ld_t(3 + (g >> 1), 1 - hb);
-            if (hb == 0 && g >= 9 && g < 13) {      // then the addresses move on to tile T
-                tofs[g - 9][0] += tbump;
-                tofs[g - 9][1] += tbump;
+            if (g <= 4 && !(g & 1)) ta[5 + (g >> 1)] = ld_t(5 + (g >> 1), 1 - hb);
+            if (hb == 0 && g >= 5 && g < 9) {       // then the addresses move on to tile T
+                tofs[g - 5][0] += tbump;
+                tofs[g - 5][1] += tbump;
             }
-            if (g >= 42 && !(g & 1)) ta[(g - 42) >> 1] = ld_t((g - 42) >> 1, hb);
+            if (g >= 38 && !(g & 1)) ta[(g - 38) >> 1] = ld_t((g - 38) >> 1, hb);
             // row-wise fragments of sub-tile u+1
-            if (g >= 10 && g <= 38 && ((g - 10) & 3) == 0) ka[(g - 10) >> 2] = ld_k((g - 10) >> 2, hb ? 0 : 1);
-            if (g >= 12 && g <= 40 && ((g - 12) & 3) == 0) va[(g - 12) >> 2] = ld_v((g - 12) >> 2, hb ? 0 : 1);
+            if (g >= 6 && g <= 34 && ((g - 6) & 3) == 0) ka[(g - 6) >> 2] = ld_k((g - 6) >> 2, hb ? 0 : 1);
+            if (g >= 8 && g <= 36 && ((g - 8) & 3) == 0) va[(g - 8) >> 2] = ld_v((g - 8) >> 2, hb ? 0 : 1);
             // vector ALU: block 1 element g (groups 0-15), block 0 element (g-16)/2 (even groups after)
             if (g < 16) {
                 w1[g] = fast_exp2(x1[g] + nl2[1]) * (y1[g] + ndl[1]);
@@ -309,7 +309,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
         }
         settle();
 #pragma unroll
-        for (int p = 0; p < 3; ++p) ta[p] = ld_t(p, 0);     // placeholder: multiplied by dS = 0
+        for (int p = 0; p < 5; ++p) ta[p] = ld_t(p, 0);     // placeholder: multiplied by dS = 0
     }
     int buf = 0;
     bool first = true;
@@ -335,10 +335,10 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
     };
     for (int T = 0; T < nMain; ++T) tile_iter(T, std::false_type{});
     for (int T = nMain; T < nT; ++T) tile_iter(T, std::true_type{});
-    {   // drain: dQ^T += K^T dS^T of the last sub-tile (fragments 0-2 are in registers)
+    {   // drain: dQ^T += K^T dS^T of the last sub-tile (fragments 0-4 are in registers)
         pin();
 #pragma unroll
-        for (int p = 3; p < 8; ++p) ta[p] = ld_t(p, 1);
+        for (int p = 5; p < 8; ++p) ta[p] = ld_t(p, 1);
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
@@ -393,6 +393,8 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
     const int G = Hq / Hkv;
     const int nPb = (P + BWD_WG_ROWS - 1) / BWD_WG_ROWS, nOb = (S + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
     const int nKb = nPb + nOb;
+    // workgroup -> (sequence, key block, KV head): KV head fastest (one head per XCD with 8 KV
+    // heads); the key blocks of one sequence run together and share its Q / dO stream in L2
     int id = blockIdx.x;
     const int hk = id % Hkv; id /= Hkv;
     const int kb = id % nKb;
@@ -614,7 +616,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
     // 0's in two used alternately.  Groups 0-15: dK^T += Q^T dS(u-1) on the matrix cores while the
     // vector ALU turns block 1 of sub-tile u into dS; groups 16-47: S(u+1), dP(u+1) (block 1's
     // overwrite what was just consumed) while the vector ALU does block 0.  Fragments are fetched
-    // about six groups ahead of their use.
+    // about ten groups ahead of their use.
     // ---------------------------------------------------------------------------------------------
     auto stage_dk = [&](auto hb_tag, auto masked_tag, int i0, f32x16& x0in, f32x16& y0in, f32x16& x0out,
                         f32x16& y0out, const TileSrc& ts, uint32_t tbump) __attribute__((always_inline)) {
@@ -639,17 +641,17 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
             __builtin_amdgcn_sched_barrier(0);
             if (hb == 0 && g >= 16 && g < 25) dma_piece(ts, g - 16);
             // transposed Q fragments of sub-tile u-1 (groups 0-8) and, for the next iteration, u
-            if (g <= 8 && !(g & 1)) ta[3 + (g >> 1)] = ld_t(3 + (g >> 1), 1 - hb);
-            if (hb == 0 && g >= 9 && g < 13) {      // then the addresses move on to tile T
-                tofs[g - 9][0] += tbump;
-                tofs[g - 9][1] += tbump;
+            if (g <= 4 && !(g & 1)) ta[5 + (g >> 1)] = ld_t(5 + (g >> 1), 1 - hb);
+            if (hb == 0 && g >= 5 && g < 9) {       // then the addresses move on to tile T
+                tofs[g - 5][0] += tbump;
+                tofs[g - 5][1] += tbump;
             }
-            if (g >= 42 && !(g & 1)) ta[(g - 42) >> 1] = ld_t((g - 42) >> 1, hb);
+            if (g >= 38 && !(g & 1)) ta[(g - 38) >> 1] = ld_t((g - 38) >> 1, hb);
             // row-wise fragments and init values of sub-tile u+1
-            if (g == 6) ld_rows(nl, 0, hb ? 0 : 1);
-            if (g == 8) ld_rows(nd, R_OFF, hb ? 0 : 1);
-            if (g >= 10 && g <= 38 && ((g - 10) & 3) == 0) qa[(g - 10) >> 2] = ld_q((g - 10) >> 2, hb ? 0 : 1);
-            if (g >= 12 && g <= 40 && ((g - 12) & 3) == 0) ga[(g - 12) >> 2] = ld_g((g - 12) >> 2, hb ? 0 : 1);
+            if (g == 3) ld_rows(nl, 0, hb ? 0 : 1);
+            if (g == 5) ld_rows(nd, R_OFF, hb ? 0 : 1);
+            if (g >= 6 && g <= 34 && ((g - 6) & 3) == 0) qa[(g - 6) >> 2] = ld_q((g - 6) >> 2, hb ? 0 : 1);
+            if (g >= 8 && g <= 36 && ((g - 8) & 3) == 0) ga[(g - 8) >> 2] = ld_g((g - 8) >> 2, hb ? 0 : 1);
             // vector ALU: block 1 element g (groups 0-15), block 0 element (g-16)/2 (even groups after)
             if (g < 16) {
                 w1[g] = fast_exp2(x1[g]) * y1[g];
@@ -716,7 +718,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
             // steady state on entry of the first iteration: fragments of sub-tile u-1 for the
             // matrix cores (xf = 0: a placeholder tile), nothing else carried
 #pragma unroll
-            for (int p = 0; p < 3; ++p) ta[p] = ld_t(p, 0);
+            for (int p = 0; p < 5; ++p) ta[p] = ld_t(p, 0);
         } else {
 #pragma unroll
             for (int t8 = 0; t8 < 8; ++t8) qa[t8] = lds_ld_frag(qofs[t8] - BUF_B + 32 * ROW_B);   // sub-tile 1
@@ -774,10 +776,10 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
     {   // drain: the last sub-tile's contribution
         pin();
         if (IS_DK) {
-            // fragments 0-2 of the last sub-tile are in registers; the others come from the last
+            // fragments 0-4 of the last sub-tile are in registers; the others come from the last
             // tile's second half (the transposed-read addresses are on that tile)
 #pragma unroll
-            for (int p = 3; p < 8; ++p) ta[p] = ld_t(p, 1);
+            for (int p = 5; p < 8; ++p) ta[p] = ld_t(p, 1);
         }
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks)

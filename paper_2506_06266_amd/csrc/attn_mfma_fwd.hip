@@ -4,7 +4,7 @@
 // One 256-thread workgroup = 256 consecutive queries of one (sequence, query head); each of its
 // four wavefronts owns 64 of them, kept in registers as MFMA operand fragments.  Keys/values
 // stream through LDS in tiles of 64 (prefix tiles first, then own tiles up to the diagonal),
-// three buffers, one barrier per tile, consumed as sub-tiles of 32 keys.  Per sub-tile a
+// four buffers, one barrier per tile, consumed as sub-tiles of 32 keys.  Per sub-tile a
 // wavefront computes S^T = K Q^T (keys on the D rows, its queries on the D columns), turns it
 // into P = 2^(c S - m) per lane (a lane owns one query) and accumulates O^T += V^T P^T with V
 // read through the transposing LDS load.
@@ -26,7 +26,7 @@ using namespace mfma;
 
 constexpr int FWD_BM = 256;   // queries per workgroup
 constexpr int FWD_BN = 64;    // keys per LDS tile, consumed as two sub-tiles of 32
-constexpr int FWD_NBUF = 3;
+constexpr int FWD_NBUF = 4;     // tile t in buffer t % 4; loads run two tiles ahead of the barrier that publishes them
 constexpr int FWD_TILE_B = FWD_BN * ROW_B;
 
 struct FwdSmem {
@@ -263,11 +263,14 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_mfma_kernel(
         const TileSrc t0 = tile_src(0, 0);
 #pragma unroll
         for (int n = 0; n < 8; ++n) dma_piece(t0, n);
-        dma_wait();
-        __syncthreads();
         const TileSrc t1 = tile_src(min(1, nT - 1), 1);
 #pragma unroll
         for (int n = 0; n < 8; ++n) dma_piece(t1, n);
+        const TileSrc t2 = tile_src(min(2, nT - 1), 2);
+#pragma unroll
+        for (int n = 0; n < 8; ++n) dma_piece(t2, n);
+        dma_wait_but<16>();
+        __syncthreads();
 #pragma unroll
         for (int t8 = 0; t8 < 8; ++t8) ka[t8] = lds_frag_n(sm.k[0], lc, 16 * t8 + 8 * lg);
 #pragma unroll
@@ -293,24 +296,26 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_mfma_kernel(
 #pragma unroll
             for (int db = 0; db < 4; ++db) va[ks][db] = lds_frag_t(sm.v[0], 16 * ks, 32 * db, lane);
     }
-    // Three LDS buffers, tile t in buffer t % 3.  The one barrier per tile opens the iteration
-    // of the tile's first sub-tile: it publishes tile t+1 (read from this iteration on) and
-    // retires tile t-1's buffer (its last fragments were fetched in the previous iteration),
-    // which then receives tile t+2.
+    // Four LDS buffers, tile t in buffer t % 4.  The one barrier per tile opens the iteration of
+    // the tile's first sub-tile: it publishes tile t+1 (read from this iteration on; its loads
+    // went out two iterations ago, so their memory latency is covered twice over) and retires
+    // tile t-1's buffer (its last fragments were fetched in the previous iteration), which then
+    // receives tile t+3.
     int buf = 0;
     auto tile_iter = [&](int t, auto masked_tag) __attribute__((always_inline)) {
         const int nbuf = buf + 1 == FWD_NBUF ? 0 : buf + 1;
         const int nnbuf = nbuf + 1 == FWD_NBUF ? 0 : nbuf + 1;
-        const TileSrc ts = tile_src(min(t + 2, nT - 1), nnbuf);
+        const int n3buf = nnbuf + 1 == FWD_NBUF ? 0 : nnbuf + 1;
+        const TileSrc ts = tile_src(min(t + 3, nT - 1), n3buf);
         const bool pre = tile_pre(t);
         const int j0 = tile_j0(t);
-        dma_wait();
+        dma_wait_but<8>();      // tile t+1 has landed (t+2 may still be in flight)
         __syncthreads();
         stage(std::integral_constant<int, 0>{}, masked_tag, pre, j0, sa, sb, ts);
         stage(std::integral_constant<int, 1>{}, masked_tag, pre, j0, sb, sa, ts);
         // fragment addresses follow the buffers: K to tile t+2's, V to tile t+1's
-        const uint32_t dk = nnbuf == 0 ? static_cast<uint32_t>(-2 * FWD_TILE_B) : static_cast<uint32_t>(FWD_TILE_B);
-        const uint32_t dv = nbuf == 0 ? static_cast<uint32_t>(-2 * FWD_TILE_B) : static_cast<uint32_t>(FWD_TILE_B);
+        const uint32_t dk = nnbuf == 0 ? static_cast<uint32_t>(-(FWD_NBUF - 1) * FWD_TILE_B) : static_cast<uint32_t>(FWD_TILE_B);
+        const uint32_t dv = nbuf == 0 ? static_cast<uint32_t>(-(FWD_NBUF - 1) * FWD_TILE_B) : static_cast<uint32_t>(FWD_TILE_B);
 #pragma unroll
         for (int t8 = 0; t8 < 8; ++t8) kofs[t8] += dk;
 #pragma unroll
