@@ -18,6 +18,13 @@
 namespace cart {
 using namespace mfma;
 
+// 1: fold c = softmax_scale * log2(e) into the register-resident operand (one extra bf16
+// rounding) and -lse2 into the score product's init value.  0: scale in fp32,
+// P = 2^fma(score, c, -lse2): exact, one more vector-ALU instruction per element in dK / dV.
+#ifndef CART_PRESCALE
+#define CART_PRESCALE 0
+#endif
+
 constexpr int BWD_TILE = 64;                      // rows per LDS tile
 constexpr int BWD_TILE_B = BWD_TILE * ROW_B;
 constexpr int BWD_NBUF = 3;
@@ -128,9 +135,13 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
             const u32x4 w = *reinterpret_cast<const u32x4*>(q + row * HD + 8 * lg + 16 * t);
+#if CART_PRESCALE
 #pragma unroll
             for (int i = 0; i < 4; ++i)
                 qf[cb][t][i] = pack_bf16x2(__uint_as_float(w[i] << 16) * c, __uint_as_float(w[i] & 0xffff0000u) * c);
+#else
+            qf[cb][t] = w;
+#endif
             gf[cb][t] = *reinterpret_cast<const u32x4*>(d_o + row * HD + 8 * lg + 16 * t);
         }
         const size_t st = (static_cast<size_t>(b) * Hq + h) * S + qi;
@@ -270,12 +281,12 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
             if (g >= 8 && g <= 36 && ((g - 8) & 3) == 0) va[(g - 8) >> 2] = ld_v((g - 8) >> 2, hb ? 0 : 1);
             // vector ALU: block 1 element g (groups 0-15), block 0 element (g-16)/2 (even groups after)
             if (g < 16) {
-                w1[g] = fast_exp2(x1[g] + nl2[1]) * (y1[g] + ndl[1]);
+                w1[g] = fast_exp2(CART_PRESCALE ? x1[g] + nl2[1] : fmaf(x1[g], c, nl2[1])) * (y1[g] + ndl[1]);
                 if (g >= 2 && !(g & 1)) dn[1][(g - 2) >> 3][((g - 2) & 7) >> 1] = pack_bf16x2(w1[g - 2], w1[g - 1]);
             } else if (!(g & 1)) {
                 const int r = (g - 16) >> 1;
                 if (r == 0) dn[1][1][3] = pack_bf16x2(w1[14], w1[15]);
-                w0[r] = fast_exp2(x0in[r] + nl2[0]) * (y0in[r] + ndl[0]);
+                w0[r] = fast_exp2(CART_PRESCALE ? x0in[r] + nl2[0] : fmaf(x0in[r], c, nl2[0])) * (y0in[r] + ndl[0]);
                 if (r >= 2 && !(r & 1)) dn[0][(r - 2) >> 3][((r - 2) & 7) >> 1] = pack_bf16x2(w0[r - 2], w0[r - 1]);
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -418,9 +429,13 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
             const u32x4 w = *reinterpret_cast<const u32x4*>(kp + 16 * t);
+#if CART_PRESCALE
 #pragma unroll
             for (int i = 0; i < 4; ++i)
                 kf[kc][t][i] = pack_bf16x2(__uint_as_float(w[i] << 16) * c, __uint_as_float(w[i] & 0xffff0000u) * c);
+#else
+            kf[kc][t] = w;
+#endif
             if (IS_DK) vf[kc][t] = *reinterpret_cast<const u32x4*>(vp + 16 * t);
         }
     }
@@ -535,6 +550,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
         }
         rofs = lds_addr(&sm.nl2[IS_DK ? 0 : 1][4 * lg]);
     }
+    uint32_t rofs_c = lds_addr(&sm.nl2[0][4 * lg]);   // dV, exact mode: the same rows of tile T
     constexpr int R_OFF = NBUF * BWD_TILE * 4;     // -delta rows behind the -lse2 rows
     // fragment loads; hb = which 32-row half of the tile
     auto ld_q = [&](int t8, int hb) __attribute__((always_inline)) { return lds_ld_frag(qofs[t8] + hb * 32 * ROW_B); };
@@ -544,14 +560,15 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
         return lds_ld_frag_t(tofs[db][0] + (32 * hb + 16 * ks) * ROW_B, tofs[db][1] + (32 * hb + 16 * ks) * ROW_B);
     };
     // init values of the score (dP) products of a sub-tile: register r <-> row 8 (r/4) + 4 lg + r%4
-    auto ld_rows = [&](f32x16& d, int ofs, int hb) __attribute__((always_inline)) {
+    auto ld_rows_at = [&](f32x16& d, uint32_t base, int ofs, int hb) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const f32x4 w = lds_ld_f32x4(rofs + ofs + (32 * hb + 8 * j) * 4);
+            const f32x4 w = lds_ld_f32x4(base + ofs + (32 * hb + 8 * j) * 4);
 #pragma unroll
             for (int e = 0; e < 4; ++e) d[4 * j + e] = w[e];
         }
     };
+    auto ld_rows = [&](f32x16& d, int ofs, int hb) __attribute__((always_inline)) { ld_rows_at(d, rofs, ofs, hb); };
 
     u32x4 xf[2][2];       // P or dS of sub-tile u-1 as B-operand fragments [key block][k-step]
 #pragma unroll
@@ -559,7 +576,10 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) xf[kc][ks] = u32x4{0u, 0u, 0u, 0u};
     bf16x8 qa[8], ga[8], ta[8];   // row-wise Q, dO fragments; transposed fragments [2 ks + ... ]
-    f32x16 nl, nd;                // init values (-lse2, -delta rows) of the next score / dP products
+    // -lse2 / -delta of a sub-tile's rows: nd is the init value of the next dP products; nl is the
+    // init value of the next score products (pre-scaled mode) or the addend of the current
+    // sub-tile's exponents, with the next sub-tile's values arriving in nl_n (exact mode)
+    f32x16 nl, nd, nl_n;
     f32x16 xa[2], xb[2];          // dV: scores, two sets used alternately
     f32x16 x1, y1, x0a, x0b, y0a, y0b;   // dK: key block 1 single, key block 0 two sets
 
@@ -580,8 +600,9 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
             constexpr int g = decltype(gc)::value;
             if (g < 16) {
                 const int t8 = g >> 1, kc = g & 1;
-                if (t8 == 0) mma_vd_first(xout[kc], qa[0], kf[kc][0], nl);
-                else         mma_vd(xout[kc], qa[t8], kf[kc][t8]);
+                if (t8 == 0 && CART_PRESCALE) mma_vd_first(xout[kc], qa[0], kf[kc][0], nl);
+                else if (t8 == 0)             mma_vd_zero(xout[kc], qa[0], kf[kc][0]);
+                else                          mma_vd(xout[kc], qa[t8], kf[kc][t8]);
             } else {
                 const int i = g - 16, ks = i >> 3, db = (i >> 1) & 3, kc = i & 1;
                 acc[db][kc] = mma(ta[4 * ks + db], __builtin_bit_cast(bf16x8, xf[kc][ks]), acc[db][kc]);
@@ -589,12 +610,13 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
             __builtin_amdgcn_sched_barrier(0);   // the matrix-core instruction leads its group
             if (hb == 0 && g < 9) dma_piece(ts, g);
             // refill what the previous two groups used last: for sub-tile u+2 / of sub-tile u
-            if (g == 2) ld_rows(nl, 0, hb);
+            if (CART_PRESCALE && g == 2) ld_rows(nl, 0, hb);                 // of sub-tile u+2
+            if (!CART_PRESCALE && g == 20) ld_rows_at(nl_n, hb ? rofs : rofs_c, 0, 1 - hb);   // of sub-tile u+1
             if (g >= 2 && g <= 16 && !(g & 1)) qa[(g - 2) >> 1] = ld_q((g - 2) >> 1, hb);
             if (g >= 18 && !(g & 1)) ta[(g - 18) >> 1] = ld_t((g - 18) >> 1, hb);
             {
                 const int kc = g >> 4, r = g & 15;
-                pe[g] = fast_exp2(xin[kc][r]);
+                pe[g] = fast_exp2(CART_PRESCALE ? xin[kc][r] : fmaf(xin[kc][r], c, nl[r]));
                 if (g >= 2 && !(g & 1)) {
                     const int e = g - 2;
                     xn[e >> 4][(e & 15) >> 3][(e & 7) >> 1] = pack_bf16x2(pe[e], pe[e + 1]);
@@ -603,6 +625,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
             __builtin_amdgcn_sched_barrier(0);
         });
         ta[7] = ld_t(7, hb);
+        if (!CART_PRESCALE) nl = nl_n;
         xn[1][1][3] = pack_bf16x2(pe[30], pe[31]);
 #pragma unroll
         for (int kc = 0; kc < 2; ++kc)
@@ -633,9 +656,9 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
                 acc[db][kc] = mma(ta[4 * ks + db], __builtin_bit_cast(bf16x8, xf[kc][ks]), acc[db][kc]);
             } else {
                 const int j = g - 16, t8 = j >> 2, which = j & 3;   // block 1 first: its results are read first
-                if (which == 0)      { if (t8 == 0) mma_vd_first(x1, qa[0], kf[1][0], nl); else mma_vd(x1, qa[t8], kf[1][t8]); }
+                if (which == 0)      { if (t8 == 0 && CART_PRESCALE) mma_vd_first(x1, qa[0], kf[1][0], nl); else if (t8 == 0) mma_vd_zero(x1, qa[0], kf[1][0]); else mma_vd(x1, qa[t8], kf[1][t8]); }
                 else if (which == 1) { if (t8 == 0) mma_vd_first(y1, ga[0], vf[1][0], nd); else mma_vd(y1, ga[t8], vf[1][t8]); }
-                else if (which == 2) { if (t8 == 0) mma_vd_first(x0out, qa[0], kf[0][0], nl); else mma_vd(x0out, qa[t8], kf[0][t8]); }
+                else if (which == 2) { if (t8 == 0 && CART_PRESCALE) mma_vd_first(x0out, qa[0], kf[0][0], nl); else if (t8 == 0) mma_vd_zero(x0out, qa[0], kf[0][0]); else mma_vd(x0out, qa[t8], kf[0][t8]); }
                 else                 { if (t8 == 0) mma_vd_first(y0out, ga[0], vf[0][0], nd); else mma_vd(y0out, ga[t8], vf[0][t8]); }
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -648,23 +671,24 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
             }
             if (g >= 38 && !(g & 1)) ta[(g - 38) >> 1] = ld_t((g - 38) >> 1, hb);
             // row-wise fragments and init values of sub-tile u+1
-            if (g == 3) ld_rows(nl, 0, hb ? 0 : 1);
+            if (g == 3) ld_rows(CART_PRESCALE ? nl : nl_n, 0, hb ? 0 : 1);
             if (g == 5) ld_rows(nd, R_OFF, hb ? 0 : 1);
             if (g >= 6 && g <= 34 && ((g - 6) & 3) == 0) qa[(g - 6) >> 2] = ld_q((g - 6) >> 2, hb ? 0 : 1);
             if (g >= 8 && g <= 36 && ((g - 8) & 3) == 0) ga[(g - 8) >> 2] = ld_g((g - 8) >> 2, hb ? 0 : 1);
             // vector ALU: block 1 element g (groups 0-15), block 0 element (g-16)/2 (even groups after)
             if (g < 16) {
-                w1[g] = fast_exp2(x1[g]) * y1[g];
+                w1[g] = fast_exp2(CART_PRESCALE ? x1[g] : fmaf(x1[g], c, nl[g])) * y1[g];
                 if (g >= 2 && !(g & 1)) xn[1][(g - 2) >> 3][((g - 2) & 7) >> 1] = pack_bf16x2(w1[g - 2], w1[g - 1]);
             } else if (!(g & 1)) {
                 const int r = (g - 16) >> 1;
                 if (r == 0) xn[1][1][3] = pack_bf16x2(w1[14], w1[15]);
-                w0[r] = fast_exp2(x0in[r]) * y0in[r];
+                w0[r] = fast_exp2(CART_PRESCALE ? x0in[r] : fmaf(x0in[r], c, nl[r])) * y0in[r];
                 if (r >= 2 && !(r & 1)) xn[0][(r - 2) >> 3][((r - 2) & 7) >> 1] = pack_bf16x2(w0[r - 2], w0[r - 1]);
             }
             __builtin_amdgcn_sched_barrier(0);
         });
         xn[0][1][3] = pack_bf16x2(w0[14], w0[15]);
+        if (!CART_PRESCALE) nl = nl_n;
 #pragma unroll
         for (int kc = 0; kc < 2; ++kc)
 #pragma unroll
@@ -703,14 +727,14 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
         f32x16 (&s0)[2] = xa;
 #pragma unroll
         for (int t8 = 0; t8 < 8; ++t8) {
+            f32x16& sx0 = IS_DK ? x0a : s0[0];
+            f32x16& sx1 = IS_DK ? x1 : s0[1];
+            if (t8 == 0 && CART_PRESCALE) { mma_vd_first(sx0, qa[0], kf[0][0], nl); mma_vd_first(sx1, qa[0], kf[1][0], nl); }
+            else if (t8 == 0)             { mma_vd_zero(sx0, qa[0], kf[0][0]);      mma_vd_zero(sx1, qa[0], kf[1][0]); }
+            else                          { mma_vd(sx0, qa[t8], kf[0][t8]);         mma_vd(sx1, qa[t8], kf[1][t8]); }
             if (IS_DK) {
-                if (t8 == 0) { mma_vd_first(x0a, qa[0], kf[0][0], nl); mma_vd_first(x1, qa[0], kf[1][0], nl);
-                               mma_vd_first(y0a, ga[0], vf[0][0], nd); mma_vd_first(y1, ga[0], vf[1][0], nd); }
-                else         { mma_vd(x0a, qa[t8], kf[0][t8]); mma_vd(x1, qa[t8], kf[1][t8]);
-                               mma_vd(y0a, ga[t8], vf[0][t8]); mma_vd(y1, ga[t8], vf[1][t8]); }
-            } else {
-                if (t8 == 0) { mma_vd_first(s0[0], qa[0], kf[0][0], nl); mma_vd_first(s0[1], qa[0], kf[1][0], nl); }
-                else         { mma_vd(s0[0], qa[t8], kf[0][t8]);         mma_vd(s0[1], qa[t8], kf[1][t8]); }
+                if (t8 == 0) { mma_vd_first(y0a, ga[0], vf[0][0], nd); mma_vd_first(y1, ga[0], vf[1][0], nd); }
+                else         { mma_vd(y0a, ga[t8], vf[0][t8]);         mma_vd(y1, ga[t8], vf[1][t8]); }
             }
         }
         settle();
@@ -722,11 +746,13 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
         } else {
 #pragma unroll
             for (int t8 = 0; t8 < 8; ++t8) qa[t8] = lds_ld_frag(qofs[t8] - BUF_B + 32 * ROW_B);   // sub-tile 1
+            if (CART_PRESCALE) {     // init values of sub-tile 1 (exact mode keeps sub-tile 0's rows)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const f32x4 a = lds_ld_f32x4(rofs - BWD_TILE * 4 + (32 + 8 * j) * 4);
+                for (int j = 0; j < 4; ++j) {
+                    const f32x4 a = lds_ld_f32x4(rofs - BWD_TILE * 4 + (32 + 8 * j) * 4);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) nl[4 * j + e] = a[e];
+                    for (int e = 0; e < 4; ++e) nl[4 * j + e] = a[e];
+                }
             }
 #pragma unroll
             for (int p = 0; p < 8; ++p) ta[p] = ld_t(p, 0);     // placeholder: multiplied by P = 0
@@ -765,6 +791,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
 #pragma unroll
             for (int t8 = 0; t8 < 8; ++t8) qofs[t8] += nnbuf == 0 ? back : fwd;   // tile T+1 -> T+2
             rofs += nnbuf == 0 ? rback : rfwd;
+            rofs_c += nbuf == 0 ? rback : rfwd;
         }
         first = false;
         buf = nbuf;

@@ -34,6 +34,14 @@ struct FwdSmem {
     char v[FWD_NBUF][FWD_TILE_B];
 };
 
+// 1: fold the softmax scale into Q (one extra bf16 rounding of Q) and the softmax reference into
+// the score product's init value, so that an exponent costs no arithmetic of its own.  0: scores
+// are scaled in fp32, exponent = fma(score, c, -m): exact, one more vector-ALU instruction per
+// element.
+#ifndef CART_PRESCALE
+#define CART_PRESCALE 0
+#endif
+
 __global__ __launch_bounds__(256, 1) void attn_fwd_mfma_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
     const bf16_t* __restrict__ zk, const bf16_t* __restrict__ zv, bf16_t* __restrict__ o,
@@ -68,12 +76,16 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_mfma_kernel(
         const bf16_t* qp = q + ((static_cast<size_t>(b) * S + qi) * Hq + h) * HD + 8 * lg;
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
+            const u32x4 w = *reinterpret_cast<const u32x4*>(qp + 16 * t);
+#if CART_PRESCALE
             // Q enters every product scaled by c = softmax_scale * log2(e), rounded to bf16 once
             // here: the scores then come out of the matrix cores in log2 units
-            const u32x4 w = *reinterpret_cast<const u32x4*>(qp + 16 * t);
 #pragma unroll
             for (int i = 0; i < 4; ++i)
                 qraw[cb][t][i] = pack_bf16x2(__uint_as_float(w[i] << 16) * c, __uint_as_float(w[i] & 0xffff0000u) * c);
+#else
+            qraw[cb][t] = w;
+#endif
         }
     }
     f32x16 acc[4][2];   // O^T: [head-element block][query block]
@@ -187,7 +199,11 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_mfma_kernel(
 
     // -m (the softmax reference of the lane's query) in all 16 registers of a set: the first
     // product of every score chain starts from it, so S arrives as the exponent c s - m
+#if CART_PRESCALE
     f32x16 ninit[2];
+#else
+    float negm[2];
+#endif
     float l_run[2] = {0.f, 0.f};
     // Scores live in ordinary vector registers, in two sets used alternately: while the vector
     // ALU reads S(u) from one set the matrix cores write S(u+1) into the other, so no copy sits
@@ -220,7 +236,11 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_mfma_kernel(
         for (int g = 0; g < 32; ++g) {
             if (g < 16) {
                 const int t8 = g >> 1, cb = g & 1;
+#if CART_PRESCALE
                 if (t8 == 0) mma_vd_first(y[cb], ka[0], qraw[cb][0], ninit[cb]);
+#else
+                if (t8 == 0) mma_vd_zero(y[cb], ka[0], qraw[cb][0]);
+#endif
                 else         mma_vd(y[cb], ka[t8], qraw[cb][t8]);
             } else {
                 const int i = g - 16, ks = i >> 3, db = (i >> 1) & 3, cb = i & 1;
@@ -236,7 +256,11 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_mfma_kernel(
             }
             {   // softmax element g; the pair before it is rounded, packed and summed
                 const int cb = g >> 4, r = g & 15;
+#if CART_PRESCALE
                 pe[g] = fast_exp2(x[cb][r]);
+#else
+                pe[g] = fast_exp2(fmaf(x[cb][r], c, negm[cb]));
+#endif
                 if (g >= 2 && !(g & 1)) {
                     const int e = g - 2, cbe = e >> 4, re = e & 15;
                     pn[cbe][re >> 3][(re & 7) >> 1] = pack_bf16x2(pe[e], pe[e + 1]);
@@ -285,9 +309,13 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_mfma_kernel(
             float tm = sa[cb][0];
 #pragma unroll
             for (int r = 1; r < 16; ++r) tm = fmaxf(tm, sa[cb][r]);
+#if CART_PRESCALE
             const float nm = -partner_max(tm);
 #pragma unroll
             for (int r = 0; r < 16; ++r) { ninit[cb][r] = nm; sa[cb][r] += nm; }
+#else
+            negm[cb] = -partner_max(tm) * c;
+#endif
         }
 #pragma unroll
         for (int t8 = 0; t8 < 8; ++t8) ka[t8] = lds_frag_n(sm.k[0], 32 + lc, 16 * t8 + 8 * lg);   // sub-tile 1
@@ -334,7 +362,11 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_mfma_kernel(
                 acc[db][1] = mma(va[ks][db], __builtin_bit_cast(bf16x8, pf[1][ks]), acc[db][1]);
             }
     }
+#if CART_PRESCALE
     float m_ref[2] = {-ninit[0][0], -ninit[1][0]};
+#else
+    float m_ref[2] = {-negm[0], -negm[1]};
+#endif
 
     // normalise and store: lane holds, for its query, head elements 32db + 8(r/4) + 4g + r%4
     bool bad = false;

@@ -108,6 +108,51 @@ def test_attention_frozen_rows_and_accumulate():
     assert rel_err(to_np(out2[3])[:, 1:], g_ref[3][:, 1:]) <= 1e-4
 
 
+@pytest.mark.parametrize("gap_nats", [60.0, 200.0])
+def test_attention_score_far_above_first_keys(gap_nats):
+    """One own key whose score exceeds everything the first keys hold by `gap_nats`.
+
+    The MFMA forward kernel fixes the softmax reference of a query on its first 32 keys; 60 nats
+    stays inside the range of exp2 / fp32 around that reference, 200 nats overflows it and has to
+    come out of the flagged recomputation.  Either way: the oracle's forward numbers, and its dV
+    / dZ_v.  The other gradients are only required to be finite here: a saturated row has
+    dS = P (dP - delta) with dP - delta cancelling to ~0, delta is formed from the bf16-rounded O
+    the forward pass returned (2^-9 relative), and the planted key is 500 times longer than the
+    others, so that rounding alone moves dQ / dK by more than their whole scale -- a property of
+    the inputs' precision, not of the kernels.
+    """
+    B, S, Hq, Hkv, D, P, hot = 2, 320, 4, 2, 128, 96, 150
+    g = torch.Generator().manual_seed(int(gap_nats))
+    u = torch.randn(D, generator=g)
+    u /= u.norm()
+    amp = math.sqrt(gap_nats * math.sqrt(D))           # amp^2 |u|^2 / sqrt(D) = gap
+    t = {
+        "q": (amp * u + 0.05 * torch.randn(B, S, Hq, D, generator=g)).to(torch.bfloat16),
+        "k_own": 0.05 * torch.randn(B, S, Hkv, D, generator=g),
+        "v_own": torch.randn(B, S, Hkv, D, generator=g).to(torch.bfloat16),
+        "z_k": (0.05 * torch.randn(Hkv, P, D, generator=g)).to(torch.bfloat16),
+        "z_v": torch.randn(Hkv, P, D, generator=g).to(torch.bfloat16),
+        "d_o": torch.randn(B, S, Hq, D, generator=g).to(torch.bfloat16),
+    }
+    t["k_own"][:, hot] += amp * u
+    t["k_own"] = t["k_own"].to(torch.bfloat16)
+    n = {k: to_np(v) for k, v in t.items()}
+    o_ref, lse_ref = orc.attn_fwd(n["q"], n["k_own"], n["v_own"], n["z_k"], n["z_v"])
+    g_ref = orc.attn_bwd(n["q"], n["k_own"], n["v_own"], n["z_k"], n["z_v"], n["d_o"])
+    # the construction does what it says: queries from `hot` on put (almost) all mass on that key
+    assert np.abs(o_ref[:, hot + 1:] - n["v_own"][:, hot:hot + 1].repeat(Hq // Hkv, axis=2)).max() < 1e-6
+    d = dev(t)
+    o, lse = cb.cart_attn_fwd(d["q"], d["k_own"], d["v_own"], d["z_k"], d["z_v"], impl=cb.IMPL_MFMA)
+    grads = cb.cart_attn_bwd(d["q"], d["k_own"], d["v_own"], d["z_k"], d["z_v"], o, lse, d["d_o"], impl=cb.IMPL_MFMA)
+    torch.cuda.synchronize()
+    errs = {"o": rel_err(to_np(o), o_ref), "lse": rel_err(to_np(lse), lse_ref)}
+    for nm, x, r in zip(["d_q", "d_k_own", "d_v_own", "d_z_k", "d_z_v"], grads, g_ref):
+        errs[nm] = rel_err(to_np(x), r)
+    print("gap", gap_nats, errs, flush=True)
+    for k in ("o", "lse", "d_v_own", "d_z_v"):
+        assert errs[k] <= TOL["bf16"], (gap_nats, k, errs[k])
+
+
 # ------------------------------------------------------------------------------------------------
 # distillation loss
 # ------------------------------------------------------------------------------------------------
