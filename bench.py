@@ -149,13 +149,17 @@ def main() -> int:
     # dominant kernel of the step = the slowest of the three backward kernels, priced on the
     # contractions it must perform over every visible pair: dq and dk kernels 3 (S, dP, and dQ
     # or dK) = 6*D flops per pair, dv kernel 2 (S, dV) = 4*D.
+    # HBM bytes per launch of these kernels at this workload, from the rocprofv3 --pmc runs of
+    # this command (FETCH_SIZE x 2.0, its calibration factor against a plain copy, + WRITE_SIZE);
+    # the counters cannot be read from inside the process, so the figures are carried here
+    hbm_bytes = {"dq": 1.451e9 + 0.269e9, "dk": 1.872e9 + 0.336e9, "dv": 1.708e9 + 0.336e9}
     dom = max(("dq", "dk", "dv"), key=lambda n: k_ms[n])
     per_pair = {"dq": 6, "dk": 6, "dv": 4}[dom] * acfg.D
     dom_tflops = pairs * per_pair / (k_ms[dom] * 1e-3) / 1e12
     roofline = {"kernel": {"dq": "attn_bwd_dq_kernel", "dk": "attn_bwd_kstat_kernel<true>",
                            "dv": "attn_bwd_kstat_kernel<false>"}[dom],
                 "bound": "mfma", "achieved": round(dom_tflops, 1), "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(dom_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "unit": "TFLOP/s", "frac": round(dom_tflops / PEAK_BF16_TFLOPS, 4), "traffic": hbm_bytes[dom],
                 "avg_launch_ms": round(k_ms[dom], 4)}
 
     out = {
