@@ -345,7 +345,9 @@ __global__ __launch_bounds__(256, 2) void decode_own_kernel(
 }
 
 // o[b,h,:] = sum_i w_i part_o[i] / sum_i w_i, w_i = exp(lse_i - max lse), over the n_ps prefix
-// splits and the request's ceil(len/chunk) own chunks.  One wavefront per (b, h), 2 elements/lane.
+// splits and the request's ceil(len/chunk) own chunks.  One wavefront per (b, h): lane i holds
+// partial i's lse and weight (n <= 64, else a serial loop), then every lane accumulates its two
+// head elements over the partials with the loads of four partials in flight.
 __global__ __launch_bounds__(256) void decode_merge_kernel(const float* __restrict__ part_o,
                                                            const float* __restrict__ part_l,
                                                            const int32_t* __restrict__ cu,
@@ -359,15 +361,41 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(const float* __restri
     const int len = cu[b + 1] - cu[b];
     const int n = n_ps + (len + chunk - 1) / chunk;
     const size_t stride = static_cast<size_t>(B) * Hq;
-    float m = -3.0e38f;
-    for (int i = 0; i < n; ++i) m = fmaxf(m, part_l[i * stride + row]);
-    float wsum = 0.f, a0 = 0.f, a1 = 0.f;
-    for (int i = 0; i < n; ++i) {
-        const float w = __expf(part_l[i * stride + row] - m);
-        const float2 x = *reinterpret_cast<const float2*>(part_o + (i * stride + row) * HD + 2 * lane);
-        wsum += w;
-        a0 = fmaf(w, x.x, a0);
-        a1 = fmaf(w, x.y, a1);
+    float wsum = 0.f, a0 = 0.f, a1 = 0.f, m;
+    if (n <= 64) {
+        const float li = lane < n ? part_l[lane * stride + row] : -3.0e38f;
+        m = wave_max(li);
+        const float wi = lane < n ? __expf(li - m) : 0.f;
+        wsum = wave_sum(wi);
+        int i = 0;
+        for (; i + 4 <= n; i += 4) {
+            float2 x[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                x[j] = *reinterpret_cast<const float2*>(part_o + ((i + j) * stride + row) * HD + 2 * lane);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float w = __shfl(wi, i + j);
+                a0 = fmaf(w, x[j].x, a0);
+                a1 = fmaf(w, x[j].y, a1);
+            }
+        }
+        for (; i < n; ++i) {
+            const float w = __shfl(wi, i);
+            const float2 x = *reinterpret_cast<const float2*>(part_o + (i * stride + row) * HD + 2 * lane);
+            a0 = fmaf(w, x.x, a0);
+            a1 = fmaf(w, x.y, a1);
+        }
+    } else {
+        m = -3.0e38f;
+        for (int i = 0; i < n; ++i) m = fmaxf(m, part_l[i * stride + row]);
+        for (int i = 0; i < n; ++i) {
+            const float w = __expf(part_l[i * stride + row] - m);
+            const float2 x = *reinterpret_cast<const float2*>(part_o + (i * stride + row) * HD + 2 * lane);
+            wsum += w;
+            a0 = fmaf(w, x.x, a0);
+            a1 = fmaf(w, x.y, a1);
+        }
     }
     const float inv = 1.f / wsum;
     *reinterpret_cast<uint32_t*>(o + row * HD + 2 * lane) = pack_bf16x2(a0 * inv, a1 * inv);
@@ -383,6 +411,25 @@ size_t decode_mfma_workspace(const cart_decode_desc& d) {
     return p.part_o_bytes + p.part_l_bytes;
 }
 
+// A second stream per device, on which the prefix kernel runs beside the own-KV kernel (the two
+// are independent until the merge); default priority; created on first use and kept.
+struct DecodeSide {
+    hipStream_t stream = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
+};
+static DecodeSide* decode_side() {
+    static DecodeSide side[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    DecodeSide& s = side[dev];
+    if (!s.stream) {
+        if (hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) != hipSuccess) { s.stream = nullptr; return nullptr; }
+        if (hipEventCreateWithFlags(&s.fork, hipEventDisableTiming) != hipSuccess ||
+            hipEventCreateWithFlags(&s.join, hipEventDisableTiming) != hipSuccess) return nullptr;
+    }
+    return &s;
+}
+
 int launch_decode_mfma(const cart_decode_desc& d, float scale, const void* q, const void* zk,
                        const void* zv, const void* k, const void* v, const int32_t* cu, void* o,
                        float* lse, void* ws, hipStream_t st) {
@@ -390,20 +437,29 @@ int launch_decode_mfma(const cart_decode_desc& d, float scale, const void* q, co
     float* part_o = static_cast<float*>(ws);
     float* part_l = reinterpret_cast<float*>(static_cast<char*>(ws) + p.part_o_bytes);
     const float c = scale * CART_LOG2E;
-    trace_begin(st);   // kernel order: prefix, own, merge
+    trace_begin(st);   // kernel order on the caller's stream: own (prefix beside it), merge
+    DecodeSide* side = p.n_ps > 0 ? decode_side() : nullptr;
+    bool forked = false;
     if (p.n_ps > 0) {
+        hipStream_t ps = st;
+        if (side && hipEventRecord(side->fork, st) == hipSuccess &&
+            hipStreamWaitEvent(side->stream, side->fork, 0) == hipSuccess) {
+            ps = side->stream;
+            forked = true;
+        }
         const unsigned grid = static_cast<unsigned>(d.Hkv) * p.n_rb * p.n_ps;
-        hipLaunchKernelGGL(decode_prefix_kernel, dim3(grid), dim3(256), 0, st,
+        hipLaunchKernelGGL(decode_prefix_kernel, dim3(grid), dim3(256), 0, ps,
                            static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(zk),
                            static_cast<const bf16_t*>(zv), part_o, part_l, d.B, d.Hq, d.Hkv, d.P, c, p.n_rb,
                            p.tiles_per_split);
+        if (forked && hipEventRecord(side->join, ps) != hipSuccess) return static_cast<int>(hipGetLastError());
     }
-    trace_mark(st);
     const long items = static_cast<long>(d.B) * d.Hkv * p.n_oc;
     hipLaunchKernelGGL(decode_own_kernel, dim3(static_cast<unsigned>((items + 3) / 4)), dim3(256), 0, st,
                        static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(k),
                        static_cast<const bf16_t*>(v), cu, part_o, part_l, d.B, d.Hq, d.Hkv, c, p.chunk, p.n_oc,
                        p.n_ps);
+    if (forked && hipStreamWaitEvent(st, side->join, 0) != hipSuccess) return static_cast<int>(hipGetLastError());
     trace_mark(st);
     const long rows = static_cast<long>(d.B) * d.Hq;
     hipLaunchKernelGGL(decode_merge_kernel, dim3(static_cast<unsigned>((rows + 3) / 4)), dim3(256), 0, st, part_o,

@@ -86,6 +86,64 @@ def test_attention_p0_and_odd_shapes_vector():
             assert rel_err(to_np(x), r) <= 1e-4
 
 
+# shapes that walk the MFMA kernels' special paths: no prefix, a prefix shorter than one tile, one
+# token, sequences ending inside a sub-tile / a tile / a workgroup's block, prefix one past a tile,
+# one query head per KV head, eight query heads per KV head, no unmasked tile at all, several
+# 256-row blocks with a ragged last one
+MFMA_EDGE_SHAPES = [
+    # B, S, Hq, Hkv, P
+    (2, 1, 2, 1, 0), (1, 1, 4, 2, 1), (2, 31, 2, 2, 0), (1, 64, 4, 1, 64), (2, 65, 4, 2, 63),
+    (1, 97, 8, 1, 65), (2, 256, 2, 1, 0), (1, 257, 4, 2, 128), (1, 600, 4, 4, 200), (3, 129, 6, 3, 31),
+]
+
+
+@pytest.mark.parametrize("shape", MFMA_EDGE_SHAPES, ids=lambda t: "B%d_S%d_Hq%d_Hkv%d_P%d" % t)
+def test_attention_mfma_edge_shapes(shape):
+    B, S, Hq, Hkv, P = shape
+    D = 128
+    print("case", shape, flush=True)
+    g = torch.Generator().manual_seed(1000 * S + P)
+    rn = lambda *sz, std=1.0: (std * torch.randn(*sz, generator=g)).to(torch.bfloat16)
+    q, k, v = rn(B, S, Hq, D, std=0.5), rn(B, S, Hkv, D, std=0.5), rn(B, S, Hkv, D)
+    zk, zv, do = rn(Hkv, P, D, std=0.5), rn(Hkv, P, D), rn(B, S, Hq, D)
+    f = lambda t: to_np(t)
+    o_ref, lse_ref = orc.attn_fwd(f(q), f(k), f(v), f(zk), f(zv))
+    g_ref = orc.attn_bwd(f(q), f(k), f(v), f(zk), f(zv), f(do))
+    a = [x.to(DEV) for x in (q, k, v, zk, zv)]
+    zargs = a[3:] if P > 0 else [None, None]
+    o, lse = cb.cart_attn_fwd(a[0], a[1], a[2], *zargs, impl=cb.IMPL_MFMA)
+    grads = cb.cart_attn_bwd(a[0], a[1], a[2], *zargs, o, lse, do.to(DEV), impl=cb.IMPL_MFMA)
+    torch.cuda.synchronize()
+    errs = {"o": rel_err(to_np(o), o_ref), "lse": rel_err(to_np(lse), lse_ref)}
+    for nm, x, r in list(zip(["d_q", "d_k_own", "d_v_own", "d_z_k", "d_z_v"], grads, g_ref))[: 3 if P == 0 else 5]:
+        if np.abs(r).max() < 1e-12:     # a softmax over one key: the exact gradient is 0
+            assert np.abs(to_np(x)).max() < 1e-2, (shape, nm)
+            continue
+        errs[nm] = rel_err(to_np(x), r)
+    print(shape, errs, flush=True)
+    for kk, e in errs.items():
+        assert e <= TOL["bf16"], (shape, kk, e)
+
+
+def test_attention_mfma_frozen_rows_and_accumulate():
+    """n_frozen / dz_accumulate through the MFMA backward (fp32 partials + fixed-order reduce)."""
+    cfg = synth.ATTN_CONFIGS["ragged"]
+    t = synth.attn_inputs(cfg)
+    n = {k: to_np(v) for k, v in t.items()}
+    g_ref = orc.attn_bwd(n["q"], n["k_own"], n["v_own"], n["z_k"], n["z_v"], n["d_o"])
+    g = dev(t)
+    o, lse = cb.cart_attn_fwd(g["q"], g["k_own"], g["v_own"], g["z_k"], g["z_v"], impl=cb.IMPL_MFMA)
+    base_k = torch.full(g["z_k"].shape, 0.5, dtype=torch.float32, device=DEV)
+    base_v = torch.full(g["z_v"].shape, -0.25, dtype=torch.float32, device=DEV)
+    out = cb.cart_attn_bwd(g["q"], g["k_own"], g["v_own"], g["z_k"], g["z_v"], o, lse, g["d_o"],
+                           n_frozen=5, d_z_k=base_k, d_z_v=base_v, dz_accumulate=True, impl=cb.IMPL_MFMA)
+    torch.cuda.synchronize()
+    exp_k = g_ref[3].copy(); exp_k[:, :5] = 0; exp_k += 0.5
+    exp_v = g_ref[4].copy(); exp_v[:, :5] = 0; exp_v -= 0.25
+    assert rel_err(to_np(out[3]), exp_k) <= TOL["bf16"] and rel_err(to_np(out[4]), exp_v) <= TOL["bf16"]
+    assert (to_np(out[3])[:, :5] == 0.5).all() and (to_np(out[4])[:, :5] == -0.25).all()
+
+
 def test_attention_frozen_rows_and_accumulate():
     cfg = synth.ATTN_CONFIGS["cfg1_attn"]
     t = synth.attn_inputs(cfg)
