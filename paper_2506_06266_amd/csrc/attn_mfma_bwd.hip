@@ -251,7 +251,13 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
                      f32x16& y0out, const TileSrc& ts, uint32_t tbump) __attribute__((always_inline)) {
         constexpr int hb = decltype(hb_tag)::value;
         constexpr bool MASKED = decltype(masked_tag)::value;
-        if (MASKED) { mask1(x0in, 0, pre, j0 + 32 * hb); mask1(x1, 1, pre, j0 + 32 * hb); }
+        if (MASKED) {
+            // the last score products of the previous iteration were issued only two groups ago
+            // and the compiler does not know they are matrix-core results: let them retire
+            asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
+            mask1(x0in, 0, pre, j0 + 32 * hb);
+            mask1(x1, 1, pre, j0 + 32 * hb);
+        }
         pin();
         float w0[16], w1[16];
         u32x4 dn[2][2];
@@ -645,7 +651,13 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
                         f32x16& y0out, const TileSrc& ts, uint32_t tbump) __attribute__((always_inline)) {
         constexpr int hb = decltype(hb_tag)::value;
         constexpr bool MASKED = decltype(masked_tag)::value;
-        if (MASKED) { mask1(x0in, 0, i0 + 32 * hb); mask1(x1, 1, i0 + 32 * hb); }
+        if (MASKED) {
+            // the last score products of the previous iteration were issued only two groups ago
+            // and the compiler does not know they are matrix-core results: let them retire
+            asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
+            mask1(x0in, 0, i0 + 32 * hb);
+            mask1(x1, 1, i0 + 32 * hb);
+        }
         pin();
         float w0[16], w1[16];
         u32x4 xn[2][2];

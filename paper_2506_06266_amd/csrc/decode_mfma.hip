@@ -411,25 +411,6 @@ size_t decode_mfma_workspace(const cart_decode_desc& d) {
     return p.part_o_bytes + p.part_l_bytes;
 }
 
-// A second stream per device, on which the prefix kernel runs beside the own-KV kernel (the two
-// are independent until the merge); default priority; created on first use and kept.
-struct DecodeSide {
-    hipStream_t stream = nullptr;
-    hipEvent_t fork = nullptr, join = nullptr;
-};
-static DecodeSide* decode_side() {
-    static DecodeSide side[64];
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
-    DecodeSide& s = side[dev];
-    if (!s.stream) {
-        if (hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) != hipSuccess) { s.stream = nullptr; return nullptr; }
-        if (hipEventCreateWithFlags(&s.fork, hipEventDisableTiming) != hipSuccess ||
-            hipEventCreateWithFlags(&s.join, hipEventDisableTiming) != hipSuccess) return nullptr;
-    }
-    return &s;
-}
-
 int launch_decode_mfma(const cart_decode_desc& d, float scale, const void* q, const void* zk,
                        const void* zv, const void* k, const void* v, const int32_t* cu, void* o,
                        float* lse, void* ws, hipStream_t st) {
@@ -437,29 +418,22 @@ int launch_decode_mfma(const cart_decode_desc& d, float scale, const void* q, co
     float* part_o = static_cast<float*>(ws);
     float* part_l = reinterpret_cast<float*>(static_cast<char*>(ws) + p.part_o_bytes);
     const float c = scale * CART_LOG2E;
-    trace_begin(st);   // kernel order on the caller's stream: own (prefix beside it), merge
-    DecodeSide* side = p.n_ps > 0 ? decode_side() : nullptr;
-    bool forked = false;
+    // (running the prefix kernel beside the own-KV kernel on a second stream was measured: the
+    // event hand-over between the two queues costs more than the overlap gains, 141 vs 131 us)
+    trace_begin(st);   // kernel order: prefix, own, merge
     if (p.n_ps > 0) {
-        hipStream_t ps = st;
-        if (side && hipEventRecord(side->fork, st) == hipSuccess &&
-            hipStreamWaitEvent(side->stream, side->fork, 0) == hipSuccess) {
-            ps = side->stream;
-            forked = true;
-        }
         const unsigned grid = static_cast<unsigned>(d.Hkv) * p.n_rb * p.n_ps;
-        hipLaunchKernelGGL(decode_prefix_kernel, dim3(grid), dim3(256), 0, ps,
+        hipLaunchKernelGGL(decode_prefix_kernel, dim3(grid), dim3(256), 0, st,
                            static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(zk),
                            static_cast<const bf16_t*>(zv), part_o, part_l, d.B, d.Hq, d.Hkv, d.P, c, p.n_rb,
                            p.tiles_per_split);
-        if (forked && hipEventRecord(side->join, ps) != hipSuccess) return static_cast<int>(hipGetLastError());
     }
+    trace_mark(st);
     const long items = static_cast<long>(d.B) * d.Hkv * p.n_oc;
     hipLaunchKernelGGL(decode_own_kernel, dim3(static_cast<unsigned>((items + 3) / 4)), dim3(256), 0, st,
                        static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(k),
                        static_cast<const bf16_t*>(v), cu, part_o, part_l, d.B, d.Hq, d.Hkv, c, p.chunk, p.n_oc,
                        p.n_ps);
-    if (forked && hipStreamWaitEvent(st, side->join, 0) != hipSuccess) return static_cast<int>(hipGetLastError());
     trace_mark(st);
     const long rows = static_cast<long>(d.B) * d.Hq;
     hipLaunchKernelGGL(decode_merge_kernel, dim3(static_cast<unsigned>((rows + 3) / 4)), dim3(256), 0, st, part_o,
