@@ -18,6 +18,11 @@ What each function follows (arxiv 2506.06266):
   student's next-token distribution, restricted to the teacher entries that
   were recorded (App. A.2 "Training Objective": top output probabilities are
   collected at data-generation time).
+* distill_kl_rest_bucket -- the same divergence with the unrecorded vocabulary
+  kept as one extra outcome on both sides (a proper KL of (k+1)-outcome
+  distributions); ntp_cross_entropy -- the next-token objective Sec. 4.2
+  compares context distillation with (ablated in Sec. 5.3), with an ignore
+  label.
 * decode -- Sec. 2.3 (decode: one new query over the whole cache) with the
   cache of Sec. 3.3 (a cartridge is served as a cached prefix of length p).
 
@@ -36,7 +41,7 @@ from typing import Optional, Tuple
 
 import numpy as np
 
-__all__ = ["attn_fwd", "attn_bwd", "distill_kl", "decode"]
+__all__ = ["attn_fwd", "attn_bwd", "distill_kl", "distill_kl_rest_bucket", "ntp_cross_entropy", "decode"]
 
 
 def _f64(x) -> np.ndarray:
@@ -159,6 +164,71 @@ def distill_kl(logits, teacher_idx, teacher_logp, scale: float = 1.0):
             M += t
         d_logits[n] += M * s[n]
     return scale * row_kl.sum(), scale * d_logits, row_kl
+
+
+def distill_kl_rest_bucket(logits, teacher_idx, teacher_logp, scale: float = 1.0):
+    """The same loss with the unrecorded vocabulary kept as one extra outcome.
+
+    Eq. 3 is a KL divergence between full distributions while App. A.2 records only the teacher's
+    top entries.  Here the k recorded tokens and "every other token" form a (k+1)-outcome
+    distribution on both sides: teacher (t_1..t_k, 1 - M), student (s_idx_1..s_idx_k, 1 - S_K)
+    with M = sum_j t_j and S_K = sum_j s_idx_j, and the row value is their KL divergence
+    KL_n = sum_j t_j (log t_j - log s_idx_j) + (1 - M) (log(1 - M) - log(1 - S_K))  (>= 0).
+    d KL_n / d logits[v] = s_v - t_v on the recorded tokens and s_v (M - S_K) / (1 - S_K) elsewhere.
+    Entries with a negative index are ignored.  Returns (loss, d_logits [N,V], row_kl [N])."""
+    z = _f64(logits)
+    idx = np.asarray(teacher_idx, dtype=np.int64)
+    lp = _f64(teacher_logp)
+    N, V = z.shape
+    m = z.max(axis=1, keepdims=True)
+    lse = m + np.log(np.exp(z - m).sum(axis=1, keepdims=True))
+    log_s = z - lse
+    s = np.exp(log_s)
+    row_kl = np.zeros(N)
+    d_logits = np.zeros((N, V))
+    for n in range(N):
+        on = np.zeros(V, dtype=bool)
+        M = 0.0
+        S_K = 0.0
+        for j in range(idx.shape[1]):
+            v = idx[n, j]
+            if v < 0:
+                continue
+            t = math.exp(lp[n, j])
+            row_kl[n] += t * (lp[n, j] - log_s[n, v])
+            d_logits[n, v] = s[n, v] - t
+            on[v] = True
+            M += t
+            S_K += s[n, v]
+        rest_t = 1.0 - M
+        rest_s = s[n, ~on].sum()            # 1 - S_K without the cancellation
+        if rest_t > 1e-12:                  # below that the teacher's mass is 1 up to rounding
+            row_kl[n] += rest_t * (math.log(rest_t) - math.log(rest_s)) if rest_s > 0.0 else math.inf
+        if rest_s > 0.0:
+            d_logits[n, ~on] = s[n, ~on] * (M - S_K) / rest_s
+    return scale * row_kl.sum(), scale * d_logits, row_kl
+
+
+def ntp_cross_entropy(logits, labels, scale: float = 1.0):
+    """Next-token cross-entropy (the objective Sec. 4.2 compares context distillation with).
+
+    logits [N,V]; labels [N] integer, rows with a negative label are ignored (no loss, zero
+    gradient).  row_n = -log softmax(logits_n)[label_n]; loss = scale * sum_n row_n;
+    d loss / d logits = scale * (softmax - onehot).  Returns (loss, d_logits [N,V], row [N])."""
+    z = _f64(logits)
+    lab = np.asarray(labels, dtype=np.int64)
+    N, V = z.shape
+    row = np.zeros(N)
+    d_logits = np.zeros((N, V))
+    for n in range(N):
+        if lab[n] < 0:
+            continue
+        zn = z[n] - z[n].max()
+        log_s = zn - math.log(np.exp(zn).sum())
+        row[n] = -log_s[lab[n]]
+        d_logits[n] = np.exp(log_s)
+        d_logits[n, lab[n]] -= 1.0
+    return scale * row.sum(), scale * d_logits, row
 
 
 def decode(q, z_k, z_v, k_own, v_own, cu_lens, scale: Optional[float] = None):
