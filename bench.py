@@ -136,6 +136,24 @@ def main() -> int:
             k_ms[n] += v / args.steps
         tr.close()
 
+    # ---- rows past the step (not part of ms_per_step): the loss kernel's other two modes on the
+    # same cfg4 buffers -- rest-bucket KL, and next-token cross-entropy (K = 1, no teacher_logp)
+    def timed(f, n=5):
+        f()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            f()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+    labels = kl["teacher_idx"][:, :1].contiguous()
+    rest_ms = timed(lambda: cb.cart_distill_kl_fwd_bwd(kl["logits"], kl["teacher_idx"], kl["teacher_logp"],
+                                                       kcfg.scale, mode=cb.KL_REST, d_logits=dlogits, loss=loss,
+                                                       workspace=ws_kl))
+    ntp_ms = timed(lambda: cb.cart_distill_kl_fwd_bwd(kl["logits"], labels, None, kcfg.scale, d_logits=dlogits,
+                                                      loss=loss, workspace=ws_kl))
+
     pairs = attn_pairs(acfg) * acfg.B * acfg.Hq
     fwd_flop, bwd_flop = pairs * 4 * acfg.D, pairs * 10 * acfg.D
     attn_ms = part_ms["attn_fwd"] + part_ms["attn_bwd"]
@@ -179,6 +197,10 @@ def main() -> int:
                   "decode_ms": round(part_ms["decode"], 4), "decode_gbs": round(dec_gbs, 1),
                   "decode_hbm_frac": round(dec_gbs / PEAK_HBM_GBS, 4)},
         "roofline": roofline,
+        "next_rows": {"kl_rest_bucket_ms": round(rest_ms, 4),
+                      "kl_rest_bucket_gbs": round((2 * kcfg.N * kcfg.V * 2 + kcfg.N * kcfg.K * 8) / rest_ms / 1e6, 1),
+                      "ntp_cross_entropy_ms": round(ntp_ms, 4),
+                      "ntp_cross_entropy_gbs": round((2 * kcfg.N * kcfg.V * 2 + kcfg.N * 4) / ntp_ms / 1e6, 1)},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(a, acfg)

@@ -58,6 +58,12 @@ typedef struct {
     cart_impl impl;
 } cart_attn_desc;
 
+/* What Eq. 3 becomes when only the teacher's top entries were recorded (App. A.2):
+ *   CART_KL_TOPK  the terms of the recorded tokens only (the unrecorded tail is dropped);
+ *   CART_KL_REST  the recorded tokens plus one extra outcome "every other token" on both sides,
+ *                 i.e. the KL divergence of the two (K+1)-outcome distributions. */
+typedef enum { CART_KL_TOPK = 0, CART_KL_REST = 1 } cart_kl_mode;
+
 /* Context-distillation loss over N positions (Eq. 3, Sec. 4.2). */
 typedef struct {
     int32_t N;              /* positions (rows), >= 1 */
@@ -65,6 +71,7 @@ typedef struct {
     int32_t K;              /* recorded teacher entries per position, 1..V and <= 1024 */
     cart_dtype logits_dtype;
     float scale;            /* loss = scale * sum_n KL_n (1/N gives the mean) */
+    cart_kl_mode mode;      /* which divergence over the recorded entries; 0 = CART_KL_TOPK */
 } cart_kl_desc;
 
 /* Serve-time decode step over a shared cartridge (Sec. 3.3). */
@@ -123,8 +130,14 @@ cart_status cart_attn_bwd(const cart_attn_desc *desc, const void *q, const void 
  *   KL_n = sum_j t_j (teacher_logp[n,j] - log s[teacher_idx[n,j]])
  *   loss = scale * sum_n KL_n
  *   d_logits[n,v] = scale * (M_n s[v] - t_v),  t_v = t_j where v = teacher_idx[n,j], else 0.
+ * With mode CART_KL_REST, S_n = sum_j s[teacher_idx[n,j]]:
+ *   KL_n = (the sum above) + (1 - M_n) (log(1 - M_n) - log(1 - S_n))
+ *   d_logits[n,v] = scale * (s[v] - t_v) on recorded tokens, scale * s[v] (M_n - S_n) / (1 - S_n)
+ *   elsewhere (1 - M_n and 1 - S_n are floored at 0 / 2^-24: fp32 cannot resolve less).
+ * Next-token cross-entropy (the objective Sec. 4.2 compares with) is the case K = 1,
+ * teacher_idx = the label (negative = ignore the position), teacher_logp = NULL.
  *   logits [N,V] in;  teacher_idx [N,K] int32 in (distinct within a row, each < V; an entry < 0
- *   is ignored);  teacher_logp [N,K] fp32 in
+ *   is ignored);  teacher_logp [N,K] fp32 in, NULL = all zero (every recorded t_j is 1)
  *   loss   [1] fp32 out (device);  d_logits [N,V] out, dtype of logits, MAY alias logits;
  *   row_kl [N] fp32 out, may be NULL.
  */

@@ -33,7 +33,7 @@ class AttnDesc(C.Structure):
 
 class KlDesc(C.Structure):
     _fields_ = [("N", C.c_int32), ("V", C.c_int32), ("K", C.c_int32), ("logits_dtype", C.c_int),
-                ("scale", C.c_float)]
+                ("scale", C.c_float), ("mode", C.c_int)]
 
 
 class DecodeDesc(C.Structure):
@@ -172,13 +172,17 @@ def cart_attn_bwd(q, k_own, v_own, z_k, z_v, o, lse, d_o, *, scale: float = 0.0,
     return d_q, d_k_own, d_v_own, d_z_k, d_z_v
 
 
-def cart_distill_kl_fwd_bwd(logits, teacher_idx, teacher_logp, scale: float, *, d_logits=None,
-                            loss=None, row_kl=None, workspace=None, stream=None):
-    """logits [N,V]; teacher_idx [N,K] int32; teacher_logp [N,K] fp32 ->
+KL_TOPK, KL_REST = 0, 1
+
+
+def cart_distill_kl_fwd_bwd(logits, teacher_idx, teacher_logp, scale: float, *, mode: int = KL_TOPK,
+                            d_logits=None, loss=None, row_kl=None, workspace=None, stream=None):
+    """logits [N,V]; teacher_idx [N,K] int32; teacher_logp [N,K] fp32 or None (all zero: with
+    K = 1 that is next-token cross-entropy on the labels teacher_idx[:,0]) ->
     (loss [1] fp32 device tensor, d_logits [N,V]).  Pass d_logits=logits to work in place."""
     lib = load()
     N, V = logits.shape
-    d = KlDesc(N, V, teacher_idx.shape[1], _dtype_code(logits), scale)
+    d = KlDesc(N, V, teacher_idx.shape[1], _dtype_code(logits), scale, mode)
     d_logits = torch.empty_like(logits) if d_logits is None else d_logits
     loss = torch.empty(1, dtype=torch.float32, device=logits.device) if loss is None else loss
     need = lib.cart_kl_workspace(C.byref(d))

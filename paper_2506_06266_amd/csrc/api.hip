@@ -44,6 +44,7 @@ cart_status check_kl(const cart_kl_desc* d) {
     if (d->K > 1024) return CART_ERR_UNSUPPORTED;
     if (d->logits_dtype != CART_F32 && d->logits_dtype != CART_BF16) return CART_ERR_UNSUPPORTED;
     if (isnan(d->scale) || isinf(d->scale)) return CART_ERR_SHAPE;
+    if (d->mode != CART_KL_TOPK && d->mode != CART_KL_REST) return CART_ERR_UNSUPPORTED;
     return CART_OK;
 }
 
@@ -143,7 +144,7 @@ cart_status cart_distill_kl_fwd_bwd(const cart_kl_desc* d, const void* logits,
                                     size_t workspace_bytes, void* stream) {
     cart_status s = check_kl(d);
     if (s != CART_OK) return s;
-    REQUIRE(logits); REQUIRE(teacher_idx); REQUIRE(teacher_logp); REQUIRE(loss); REQUIRE(d_logits);
+    REQUIRE(logits); REQUIRE(teacher_idx); REQUIRE(loss); REQUIRE(d_logits);   // teacher_logp NULL = zeros
     ALIGNED(logits); ALIGNED(teacher_idx); ALIGNED(teacher_logp); ALIGNED(d_logits); ALIGNED(workspace);
     if (!row_kl && (!workspace || workspace_bytes < cart_kl_workspace(d))) return CART_ERR_WORKSPACE;
     int e = cart::launch_kl(*d, logits, teacher_idx, teacher_logp, loss, d_logits, row_kl, workspace,

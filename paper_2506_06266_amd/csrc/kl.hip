@@ -1,5 +1,8 @@
 // Context-distillation loss (Eq. 3, Sec. 4.2, over the teacher's recorded top entries of
-// App. A.2) fused with its gradient: one streaming pass over the student's logits.
+// App. A.2) fused with its gradient: one streaming pass over the student's logits.  Two
+// readings of the truncated teacher (recorded terms only / plus a rest bucket) share the pass:
+// they differ in one per-row coefficient and in the k fix-ups; next-token cross-entropy is the
+// case of one recorded token of probability 1.
 //
 // kl_row_resident: one 1024-thread workgroup per position holds the whole bf16 row
 // (<= 131072 logits) in registers, so HBM sees each logit read once and each gradient written
@@ -25,7 +28,7 @@ __device__ __forceinline__ float kl_stage_teacher(KlTeacher& tc, const T* logits
     float m_part = 0.f;
     for (int j = threadIdx.x; j < K; j += THREADS) {
         int id = idx[j];
-        float lp = logp[j];
+        float lp = logp ? logp[j] : 0.f;
         bool ok = id >= 0 && id < V;
         float t = ok ? __expf(lp) : 0.f;
         tc.idx[j] = ok ? id : -1;
@@ -37,13 +40,32 @@ __device__ __forceinline__ float kl_stage_teacher(KlTeacher& tc, const T* logits
     return m_part;
 }
 
-// KL_n = sum_j t_j (logp_j - x_j + lse), evaluated by the first wavefront
-__device__ __forceinline__ void kl_row_value(const KlTeacher& tc, int K, float lse, float* out) {
+// KL_n = sum_j t_j (logp_j - x_j + lse) (+ extra, the rest-bucket term), by the first wavefront
+__device__ __forceinline__ void kl_row_value(const KlTeacher& tc, int K, float lse, float extra, float* out) {
     if (threadIdx.x < CART_WAVE) {
         float a = 0.f;
         for (int j = threadIdx.x; j < K; j += CART_WAVE) a += tc.t[j] * (tc.lp[j] - tc.x[j] + lse);
         a = wave_sum(a);
-        if (threadIdx.x == 0) *out = a;
+        if (threadIdx.x == 0) *out = a + extra;
+    }
+}
+
+// Rest-bucket mode, once the row's log2-sum-exp is known.  The first wavefront sums the student's
+// mass on the recorded tokens, S = sum_j 2^(x_j log2e - lse2), and leaves in LDS the coefficient
+// of the off-support gradient, (M - S) / (1 - S), and the row's extra term
+// (1 - M)(log(1 - M) - log(1 - S)); the caller synchronises before reading them.  1 - M is
+// floored at 0 and 1 - S at 2^-24, below which fp32 cannot resolve them.
+__device__ __forceinline__ void kl_rest_terms(const KlTeacher& tc, int K, float lse2, float M, float* out2) {
+    if (threadIdx.x < CART_WAVE) {
+        float a = 0.f;
+        for (int j = threadIdx.x; j < K; j += CART_WAVE)
+            if (tc.idx[j] >= 0) a += fast_exp2(fmaf(tc.x[j], CART_LOG2E, -lse2));
+        a = wave_sum(a);
+        if (threadIdx.x == 0) {
+            const float rs = fmaxf(1.f - a, 5.9604645e-8f), rt = fmaxf(1.f - M, 0.f);
+            out2[0] = (M - a) / rs;
+            out2[1] = rt > 0.f ? rt * (__logf(rt) - __logf(rs)) : 0.f;
+        }
     }
 }
 
@@ -63,10 +85,11 @@ __device__ __forceinline__ float max3_raw(float a, uint32_t b, uint32_t c) {
 template <int NV>
 __global__ __launch_bounds__(1024) void kl_row_resident(const bf16_t* logits, const int32_t* idx,
                                                         const float* logp, bf16_t* dlogits,
-                                                        float* row_kl, int V, int K, float scale) {
+                                                        float* row_kl, int V, int K, float scale,
+                                                        int rest) {
     constexpr int THREADS = 1024, NW = THREADS / CART_WAVE;
     __shared__ KlTeacher tc;
-    __shared__ float red_max[NW], red_m[NW], red_sum[NW];
+    __shared__ float red_max[NW], red_m[NW], red_sum[NW], rest_terms[2];
     const int n = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const size_t row = static_cast<size_t>(n) * V;
     const u32x4* src = reinterpret_cast<const u32x4*>(logits + row);
@@ -81,7 +104,7 @@ __global__ __launch_bounds__(1024) void kl_row_resident(const bf16_t* logits, co
         if (v < nvec) x[i] = __builtin_nontemporal_load(src + v);
     }
     float m_part = kl_stage_teacher<bf16_t, THREADS>(tc, logits + row, idx + static_cast<size_t>(n) * K,
-                                                    logp + static_cast<size_t>(n) * K, V, K);
+                                                    logp ? logp + static_cast<size_t>(n) * K : nullptr, V, K);
 
     // sweep 1: a reference value within one bf16 ulp of the row maximum.  The packed word read
     // as fp32 is the high element plus a sub-ulp perturbation, which is good enough here: any
@@ -126,8 +149,16 @@ __global__ __launch_bounds__(1024) void kl_row_resident(const bf16_t* logits, co
     for (int w = 0; w < NW; ++w) sum += red_sum[w];
     const float lse2 = fast_log2(sum) - c0;          // log2 of the softmax denominator
 
-    // sweep 3: g = scale * M * exp(x - lse); the positive factor rides in the exponent
-    const float c = scale * M;
+    // sweep 3: g = c * exp(x - lse) with c = scale * M (rest-bucket mode: the off-support
+    // coefficient scale * (M - S) / (1 - S)); |c| rides in the exponent
+    float coef = M, extra = 0.f;
+    if (rest) {
+        kl_rest_terms(tc, K, lse2, M, rest_terms);
+        __syncthreads();
+        coef = rest_terms[0];
+        extra = rest_terms[1];
+    }
+    const float c = scale * coef;
     const float off = -(lse2 - fast_log2(fabsf(c)));  // c == 0 gives -inf, hence g == 0
     const uint32_t sgn = c < 0.f ? 0x80008000u : 0u;
     u32x4* dst = reinterpret_cast<u32x4*>(dlogits + row);
@@ -151,25 +182,25 @@ __global__ __launch_bounds__(1024) void kl_row_resident(const bf16_t* logits, co
         int id = tc.idx[j];
         if (id >= 0 && ((id >> 3) & (THREADS - 1)) == tid) {
             float s = fast_exp2(fmaf(tc.x[j], CART_LOG2E, -lse2));
-            dlogits[row + id] = f32_to_bf16(scale * (M * s - tc.t[j]));
+            dlogits[row + id] = f32_to_bf16(scale * ((rest ? 1.f : M) * s - tc.t[j]));
         }
     }
-    kl_row_value(tc, K, lse2 * CART_LN2, row_kl + n);
+    kl_row_value(tc, K, lse2 * CART_LN2, extra, row_kl + n);
 }
 
 template <typename T>
 __global__ __launch_bounds__(256) void kl_row_stream(const T* logits, const int32_t* idx,
                                                      const float* logp, T* dlogits, float* row_kl,
-                                                     int V, int K, float scale) {
+                                                     int V, int K, float scale, int rest) {
     constexpr int THREADS = 256, NW = THREADS / CART_WAVE;
     __shared__ KlTeacher tc;
-    __shared__ float red_max[NW], red_m[NW], red_sum[NW];
+    __shared__ float red_max[NW], red_m[NW], red_sum[NW], rest_terms[2];
     const int n = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const size_t row = static_cast<size_t>(n) * V;
     const T* src = logits + row;
 
     float m_part = kl_stage_teacher<T, THREADS>(tc, src, idx + static_cast<size_t>(n) * K,
-                                               logp + static_cast<size_t>(n) * K, V, K);
+                                               logp ? logp + static_cast<size_t>(n) * K : nullptr, V, K);
     // pass 1: running (max, sum) per thread in base 2
     float mx = -3.0e38f, sum = 0.f;
     for (int v = tid; v < V; v += THREADS) {
@@ -192,7 +223,14 @@ __global__ __launch_bounds__(256) void kl_row_stream(const T* logits, const int3
     const float lse2 = gmx + fast_log2(sum);
 
     // pass 2: gradient; each thread rewrites the recorded tokens it owns after its own stores
-    const float c = scale * M;
+    float coef = M, extra = 0.f;
+    if (rest) {
+        kl_rest_terms(tc, K, lse2, M, rest_terms);
+        __syncthreads();
+        coef = rest_terms[0];
+        extra = rest_terms[1];
+    }
+    const float c = scale * coef;
     T* dst = dlogits + row;
     for (int v = tid; v < V; v += THREADS) {
         float y = elem<T>::load(src + v);
@@ -202,10 +240,10 @@ __global__ __launch_bounds__(256) void kl_row_stream(const T* logits, const int3
         int id = tc.idx[j];
         if (id >= 0 && (id & (THREADS - 1)) == tid) {
             float s = fast_exp2(fmaf(tc.x[j], CART_LOG2E, -lse2));
-            elem<T>::store(dst + id, scale * (M * s - tc.t[j]));
+            elem<T>::store(dst + id, scale * ((rest ? 1.f : M) * s - tc.t[j]));
         }
     }
-    kl_row_value(tc, K, lse2 * CART_LN2, row_kl + n);
+    kl_row_value(tc, K, lse2 * CART_LN2, extra, row_kl + n);
 }
 
 // loss = scale * sum_n row_kl[n]: one workgroup, fixed summation order, fp64 accumulation
@@ -226,6 +264,7 @@ __global__ __launch_bounds__(1024) void kl_reduce_rows(const float* row_kl, int 
 int launch_kl(const cart_kl_desc& d, const void* logits, const int32_t* idx, const float* logp,
               float* loss, void* d_logits, float* row_kl, void* ws, hipStream_t st) {
     float* rows = row_kl ? row_kl : static_cast<float*>(ws);
+    const int rest = d.mode == CART_KL_REST ? 1 : 0;
     trace_begin(st);   // kernel order: row kernel, loss reduce
     const bool resident = d.logits_dtype == CART_BF16 && (d.V % 8) == 0 && d.V <= 1024 * 16 * 8;
     if (resident) {
@@ -233,19 +272,19 @@ int launch_kl(const cart_kl_desc& d, const void* logits, const int32_t* idx, con
         bf16_t* g = static_cast<bf16_t*>(d_logits);
         const int nvec = d.V / 8;
         if (nvec <= 1024 * 4)
-            hipLaunchKernelGGL(kl_row_resident<4>, dim3(d.N), dim3(1024), 0, st, x, idx, logp, g, rows, d.V, d.K, d.scale);
+            hipLaunchKernelGGL(kl_row_resident<4>, dim3(d.N), dim3(1024), 0, st, x, idx, logp, g, rows, d.V, d.K, d.scale, rest);
         else if (nvec <= 1024 * 8)
-            hipLaunchKernelGGL(kl_row_resident<8>, dim3(d.N), dim3(1024), 0, st, x, idx, logp, g, rows, d.V, d.K, d.scale);
+            hipLaunchKernelGGL(kl_row_resident<8>, dim3(d.N), dim3(1024), 0, st, x, idx, logp, g, rows, d.V, d.K, d.scale, rest);
         else
-            hipLaunchKernelGGL(kl_row_resident<16>, dim3(d.N), dim3(1024), 0, st, x, idx, logp, g, rows, d.V, d.K, d.scale);
+            hipLaunchKernelGGL(kl_row_resident<16>, dim3(d.N), dim3(1024), 0, st, x, idx, logp, g, rows, d.V, d.K, d.scale, rest);
     } else if (d.logits_dtype == CART_BF16) {
         hipLaunchKernelGGL(kl_row_stream<bf16_t>, dim3(d.N), dim3(256), 0, st,
                            static_cast<const bf16_t*>(logits), idx, logp,
-                           static_cast<bf16_t*>(d_logits), rows, d.V, d.K, d.scale);
+                           static_cast<bf16_t*>(d_logits), rows, d.V, d.K, d.scale, rest);
     } else {
         hipLaunchKernelGGL(kl_row_stream<float>, dim3(d.N), dim3(256), 0, st,
                            static_cast<const float*>(logits), idx, logp,
-                           static_cast<float*>(d_logits), rows, d.V, d.K, d.scale);
+                           static_cast<float*>(d_logits), rows, d.V, d.K, d.scale, rest);
     }
     trace_mark(st);
     hipLaunchKernelGGL(kl_reduce_rows, dim3(1), dim3(1024), 0, st, rows, d.N, d.scale, loss);

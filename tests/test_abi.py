@@ -87,6 +87,8 @@ def test_kl_and_decode_argument_validation(lib):
     assert lib.cart_distill_kl_fwd_bwd(C.byref(k), *([0x1000] * 7), 1 << 20, None) == 3   # K > 1024
     k = binding.KlDesc(4, 100, 5, binding.CART_F32, float("nan"))
     assert lib.cart_distill_kl_fwd_bwd(C.byref(k), *([0x1000] * 7), 1 << 20, None) == 2
+    k = binding.KlDesc(4, 100, 5, binding.CART_F32, 1.0, 7)
+    assert lib.cart_distill_kl_fwd_bwd(C.byref(k), *([0x1000] * 7), 1 << 20, None) == 3   # unknown mode
     k = binding.KlDesc(4, 100, 5, binding.CART_F32, 1.0)
     args = [0x1000] * 7
     args[3] = None                                       # loss

@@ -60,19 +60,21 @@ def test_attention_full_shape_one_kv_group(name, hk):
         assert torch.equal(a, b)
 
 
-def test_distill_kl_full_size_sampled_rows():
+@pytest.mark.parametrize("mode", [cb.KL_TOPK, cb.KL_REST], ids=["topk", "rest"])
+def test_distill_kl_full_size_sampled_rows(mode):
     cfg = synth.KL_CONFIGS["cfg4"]
-    print("case cfg4", flush=True)
+    print("case cfg4 mode", mode, flush=True)
     g = synth.kl_inputs(cfg, DEV)
     row_kl = torch.empty(cfg.N, dtype=torch.float32, device=DEV)
-    loss, dl = cb.cart_distill_kl_fwd_bwd(g["logits"], g["teacher_idx"], g["teacher_logp"], cfg.scale, row_kl=row_kl)
+    loss, dl = cb.cart_distill_kl_fwd_bwd(g["logits"], g["teacher_idx"], g["teacher_logp"], cfg.scale, mode=mode,
+                                          row_kl=row_kl)
     torch.cuda.synchronize()
     rows = torch.tensor(sorted({0, 1, 777, 4095, 4096, 8191, 12345, 16383} |
                                set(np.random.default_rng(7).integers(0, cfg.N, 40).tolist())), device=DEV)
     z = f64(g["logits"][rows])
     idx = g["teacher_idx"][rows].cpu().numpy()
     lp = f64(g["teacher_logp"][rows])
-    _, dl_ref, row_ref = orc.distill_kl(z, idx, lp, cfg.scale)
+    _, dl_ref, row_ref = (orc.distill_kl if mode == cb.KL_TOPK else orc.distill_kl_rest_bucket)(z, idx, lp, cfg.scale)
     e_dl = rel_err(f64(dl[rows]), dl_ref)
     e_row = rel_err(f64(row_kl[rows]), row_ref)
     print("cfg4", {"dl": e_dl, "row_kl": e_row}, flush=True)
@@ -85,7 +87,7 @@ def test_distill_kl_full_size_sampled_rows():
     assert abs(loss.item() - expect) <= 1e-6 * abs(expect)
     # in place (d_logits aliases logits): same bits
     buf = g["logits"].clone()
-    loss2, dl2 = cb.cart_distill_kl_fwd_bwd(buf, g["teacher_idx"], g["teacher_logp"], cfg.scale, d_logits=buf)
+    loss2, dl2 = cb.cart_distill_kl_fwd_bwd(buf, g["teacher_idx"], g["teacher_logp"], cfg.scale, mode=mode, d_logits=buf)
     torch.cuda.synchronize()
     assert torch.equal(dl2[rows], dl[rows]) and torch.equal(dl2[::97], dl[::97]) and loss2.item() == loss.item()
 

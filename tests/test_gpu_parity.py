@@ -247,6 +247,62 @@ def test_distill_kl_matches_oracle(name):
     assert torch.equal(dl2, dl) and loss2.item() == loss.item()
 
 
+@pytest.mark.parametrize("name", ["cfg1_loss", "kl_small", "kl_ragged"])
+def test_distill_kl_rest_bucket_matches_oracle(name):
+    """The second reading of the truncated teacher: recorded tokens + one rest outcome."""
+    cfg = synth.KL_CONFIGS[name]
+    print("case rest", name, flush=True)
+    t = synth.kl_inputs(cfg)
+    loss_ref, dl_ref, row_ref = orc.distill_kl_rest_bucket(to_np(t["logits"]), t["teacher_idx"].numpy(),
+                                                           to_np(t["teacher_logp"]), cfg.scale)
+    g = dev(t)
+    row_kl = torch.empty(cfg.N, dtype=torch.float32, device=DEV)
+    loss, dl = cb.cart_distill_kl_fwd_bwd(g["logits"], g["teacher_idx"], g["teacher_logp"], cfg.scale,
+                                          mode=cb.KL_REST, row_kl=row_kl)
+    torch.cuda.synchronize()
+    tol = TOL[cfg.dtype]
+    e = {"loss": abs(loss.item() - loss_ref) / abs(loss_ref), "dl": rel_err(to_np(dl), dl_ref),
+         "row": rel_err(to_np(row_kl), row_ref)}
+    print(name, e, flush=True)
+    assert e["loss"] <= min(tol, 1e-4) and e["row"] <= min(tol, 1e-4) and e["dl"] <= tol
+    assert (to_np(row_kl) >= -1e-6).all()                     # a KL divergence
+    idx = t["teacher_idx"].long()
+    at_idx = torch.gather(dl.cpu().double(), 1, idx).numpy()
+    ref_at = np.take_along_axis(dl_ref, idx.numpy(), axis=1)
+    assert np.abs(at_idx - ref_at).max() <= tol * np.abs(ref_at).max()
+    buf = g["logits"].clone()
+    loss2, dl2 = cb.cart_distill_kl_fwd_bwd(buf, g["teacher_idx"], g["teacher_logp"], cfg.scale,
+                                            mode=cb.KL_REST, d_logits=buf)
+    torch.cuda.synchronize()
+    assert torch.equal(dl2, dl) and loss2.item() == loss.item()
+
+
+@pytest.mark.parametrize("dtype,V", [(torch.float32, 1000), (torch.bfloat16, 4096), (torch.bfloat16, 50264)])
+def test_ntp_cross_entropy_matches_oracle(dtype, V):
+    """K = 1, teacher_logp = NULL: next-token cross-entropy on the labels; negative = ignored."""
+    N = 96
+    g = torch.Generator().manual_seed(V)
+    logits = (2.0 * torch.randn(N, V, generator=g)).to(dtype)
+    labels = torch.randint(0, V, (N,), generator=g, dtype=torch.int64)
+    labels[::7] = -100
+    labels[5] = V - 1
+    labels[6] = 0
+    loss_ref, dl_ref, row_ref = orc.ntp_cross_entropy(to_np(logits), labels.numpy(), 1.0 / N)
+    row = torch.empty(N, dtype=torch.float32, device=DEV)
+    idx = labels.to(torch.int32).view(N, 1).to(DEV)
+    for mode in (cb.KL_TOPK, cb.KL_REST):
+        loss, dl = cb.cart_distill_kl_fwd_bwd(logits.to(DEV), idx, None, 1.0 / N, mode=mode, row_kl=row)
+        torch.cuda.synchronize()
+        tol = 1e-4 if dtype == torch.float32 else 2e-2
+        assert abs(loss.item() - loss_ref) <= 1e-4 * abs(loss_ref)
+        assert rel_err(to_np(row), row_ref) <= 1e-4
+        assert rel_err(to_np(dl), dl_ref) <= tol
+        ign = (labels < 0)
+        assert not dl[ign.to(DEV)].any() and not row[ign.to(DEV)].any()   # exactly zero
+        lab_grad = torch.gather(dl.cpu().double()[~ign], 1, labels[~ign].view(-1, 1))
+        assert (lab_grad < 0).all()
+
+
 def test_distill_kl_special_cases():
     rng = np.random.default_rng(0)
     N, V = 9, 1000
