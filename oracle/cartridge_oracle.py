@@ -25,6 +25,9 @@ What each function follows (arxiv 2506.06266):
   label.
 * decode -- Sec. 2.3 (decode: one new query over the whole cache) with the
   cache of Sec. 3.3 (a cartridge is served as a cached prefix of length p).
+  decode_composed -- the same over several cartridges concatenated (Sec. 5.4,
+  composition without retraining) and / or a different cartridge per request
+  (the serving protocol of App. B's throughput measurement).
 
 Readings where the paper is silent (listed in the design notes as well):
 scale is 1/sqrt(head_dim) per head unless given; query head h reads KV head
@@ -41,7 +44,7 @@ from typing import Optional, Tuple
 
 import numpy as np
 
-__all__ = ["attn_fwd", "attn_bwd", "distill_kl", "distill_kl_rest_bucket", "ntp_cross_entropy", "decode"]
+__all__ = ["attn_fwd", "attn_bwd", "distill_kl", "distill_kl_rest_bucket", "ntp_cross_entropy", "decode", "decode_composed"]
 
 
 def _f64(x) -> np.ndarray:
@@ -251,6 +254,45 @@ def decode(q, z_k, z_v, k_own, v_own, cu_lens, scale: Optional[float] = None):
             hk = h // G
             keys = np.concatenate([z_k[hk], k_own[cu[b]:cu[b + 1], hk]], axis=0)
             vals = np.concatenate([z_v[hk], v_own[cu[b]:cu[b + 1], hk]], axis=0)
+            s = scale * (keys @ q[b, h])
+            m = s.max()
+            e = np.exp(s - m)
+            l = e.sum()
+            o[b, h] = (e / l) @ vals
+            lse[b, h] = m + math.log(l)
+    return o, lse
+
+
+def decode_composed(q, shared, pool_k, pool_v, cart_id, k_own, v_own, cu_lens, scale: Optional[float] = None):
+    """Decode step over composed cartridges (Sec. 5.4: independently trained cartridges are
+    concatenated without retraining; App. B's throughput protocol serves a different cartridge
+    per request).
+
+    Request b attends over, in cache order: every shared segment (z_k, z_v) of `shared`, each
+    [Hkv,p_s,d]; then its private cartridge pool_k[cart_id[b]], pool_v[cart_id[b]] ([Hkv,p_c,d];
+    none when cart_id[b] < 0 or the pool is None); then its own rows of k_own / v_own.  All
+    visible.  Returns o [B,Hq,d] and lse [B,Hq]."""
+    q, k_own, v_own = map(_f64, (q, k_own, v_own))
+    shared = [(_f64(a), _f64(b_)) for a, b_ in shared]
+    cu = np.asarray(cu_lens, dtype=np.int64)
+    B, Hq, d = q.shape
+    Hkv = k_own.shape[1]
+    G = Hq // Hkv
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    o = np.zeros((B, Hq, d))
+    lse = np.zeros((B, Hq))
+    for b in range(B):
+        for h in range(Hq):
+            hk = h // G
+            ks = [zk[hk] for zk, _ in shared]
+            vs = [zv[hk] for _, zv in shared]
+            if pool_k is not None and cart_id is not None and int(cart_id[b]) >= 0:
+                ks.append(_f64(pool_k[int(cart_id[b]), hk]))
+                vs.append(_f64(pool_v[int(cart_id[b]), hk]))
+            ks.append(k_own[cu[b]:cu[b + 1], hk])
+            vs.append(v_own[cu[b]:cu[b + 1], hk])
+            keys, vals = np.concatenate(ks, axis=0), np.concatenate(vs, axis=0)
             s = scale * (keys @ q[b, h])
             m = s.max()
             e = np.exp(s - m)
