@@ -154,6 +154,23 @@ def main() -> int:
     ntp_ms = timed(lambda: cb.cart_distill_kl_fwd_bwd(kl["logits"], labels, None, kcfg.scale, d_logits=dlogits,
                                                       loss=loss, workspace=ws_kl))
 
+    # decode with the cartridge in pieces: cfg5's 8192 slots as four shared segments, and the
+    # paper's serving protocol of one cartridge per request (128 requests x 2048 slots)
+    quarter = dcfg.P // 4
+    segs = [(dc["z_k"][:, i * quarter:(i + 1) * quarter].contiguous(), dc["z_v"][:, i * quarter:(i + 1) * quarter].contiguous())
+            for i in range(4)]
+    seg_ms = timed(lambda: cb.cart_decode_composed(dc["q"], segs, None, None, None, dc["k_own"], dc["v_own"],
+                                                   dc["cu_lens"], dcfg.max_len, o=dec_o, lse=dec_lse))
+    gen = torch.Generator(device=dev).manual_seed(77)
+    pool_p = 2048
+    pool_k = (0.02 * torch.randn(dcfg.B, dcfg.Hkv, pool_p, dcfg.D, generator=gen, device=dev)).to(torch.bfloat16)
+    pool_v = (0.02 * torch.randn(dcfg.B, dcfg.Hkv, pool_p, dcfg.D, generator=gen, device=dev)).to(torch.bfloat16)
+    cart_id = torch.arange(dcfg.B, dtype=torch.int32, device=dev)
+    pool_ms = timed(lambda: cb.cart_decode_composed(dc["q"], [], pool_k, pool_v, cart_id, dc["k_own"], dc["v_own"],
+                                                    dc["cu_lens"], dcfg.max_len, o=dec_o, lse=dec_lse))
+    pool_bytes = 2 * pool_k.numel() * 2 + 2 * own_tokens * dcfg.Hkv * dcfg.D * 2 + 2 * dcfg.B * dcfg.Hq * dcfg.D * 2
+    del pool_k, pool_v
+
     pairs = attn_pairs(acfg) * acfg.B * acfg.Hq
     fwd_flop, bwd_flop = pairs * 4 * acfg.D, pairs * 10 * acfg.D
     attn_ms = part_ms["attn_fwd"] + part_ms["attn_bwd"]
@@ -200,7 +217,10 @@ def main() -> int:
         "next_rows": {"kl_rest_bucket_ms": round(rest_ms, 4),
                       "kl_rest_bucket_gbs": round((2 * kcfg.N * kcfg.V * 2 + kcfg.N * kcfg.K * 8) / rest_ms / 1e6, 1),
                       "ntp_cross_entropy_ms": round(ntp_ms, 4),
-                      "ntp_cross_entropy_gbs": round((2 * kcfg.N * kcfg.V * 2 + kcfg.N * 4) / ntp_ms / 1e6, 1)},
+                      "ntp_cross_entropy_gbs": round((2 * kcfg.N * kcfg.V * 2 + kcfg.N * 4) / ntp_ms / 1e6, 1),
+                      "decode_4_shared_segments_ms": round(seg_ms, 4),
+                      "decode_cartridge_per_request_ms": round(pool_ms, 4),
+                      "decode_cartridge_per_request_gbs": round(pool_bytes / pool_ms / 1e6, 1)},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(a, acfg)

@@ -85,11 +85,34 @@ typedef struct {
     cart_impl impl;
 } cart_decode_desc;
 
+/* One trained cartridge (or a piece of one): key and value vectors [Hkv,p,D], device memory. */
+typedef struct {
+    const void *z_k;
+    const void *z_v;
+    int32_t p;              /* slots, >= 0 (an empty segment adds nothing) */
+} cart_segment;
+#define CART_MAX_SEGMENTS 8
+
+/* Decode step over composed cartridges (Sec. 5.4) and / or one cartridge per request (the
+ * serving protocol of App. B's throughput measurement). */
+typedef struct {
+    int32_t B;                  /* requests, >= 1 */
+    int32_t Hq, Hkv, D;         /* as in cart_attn_desc */
+    int32_t n_shared;           /* 0..CART_MAX_SEGMENTS segments every request attends over */
+    int32_t n_pool;             /* cartridges in the per-request pool, 0 = no pool */
+    int32_t pool_p;             /* slots of each pooled cartridge (all the same size), >= 1 with a pool */
+    int32_t total_own_tokens;   /* T = cu_lens[B] */
+    int32_t max_own_len;        /* upper bound on any request's own length */
+    cart_dtype dtype;           /* CART_BF16 with D = 128 and Hq/Hkv <= 32 (else CART_ERR_UNSUPPORTED) */
+    float softmax_scale;        /* 0 selects 1/sqrt(D) */
+} cart_decode_composed_desc;
+
 /* Bytes of workspace each entry point needs for the given descriptor (0 on an invalid one). */
 size_t cart_attn_fwd_workspace(const cart_attn_desc *desc);
 size_t cart_attn_bwd_workspace(const cart_attn_desc *desc);
 size_t cart_kl_workspace(const cart_kl_desc *desc);
 size_t cart_decode_workspace(const cart_decode_desc *desc);
+size_t cart_decode_composed_workspace(const cart_decode_composed_desc *desc, const cart_segment *shared);
 
 /*
  * cart_attn_fwd -- Eq. 1 (Sec. 2.3) over the cartridge cache of Sec. 3.2.
@@ -159,6 +182,23 @@ cart_status cart_decode(const cart_decode_desc *desc, const void *q, const void 
                         const void *z_v, const void *k_own, const void *v_own,
                         const int32_t *cu_lens, void *o, float *lse, void *workspace,
                         size_t workspace_bytes, void *stream);
+
+/*
+ * cart_decode_composed -- cart_decode with the prefix given in pieces.  Request b attends over,
+ * in cache order: the n_shared segments of `shared` (Sec. 5.4: cartridges trained independently
+ * are composed by concatenating them; no segment is copied), then, when cart_id[b] >= 0, its own
+ * cartridge pool_k / pool_v[cart_id[b]], then its own rows; all visible.  With one shared
+ * segment and no pool this is cart_decode.
+ *   q [B,Hq,D] in;  shared: host array of n_shared segments (device pointers inside), read
+ *   during the call only;  pool_k, pool_v [n_pool,Hkv,pool_p,D] in, cart_id [B] int32 in
+ *   (device; an entry < 0: no private cartridge; every entry < n_pool) -- all three NULL when
+ *   n_pool == 0;  k_own, v_own, cu_lens, o, lse as in cart_decode.
+ */
+cart_status cart_decode_composed(const cart_decode_composed_desc *desc, const void *q,
+                                 const cart_segment *shared, const void *pool_k, const void *pool_v,
+                                 const int32_t *cart_id, const void *k_own, const void *v_own,
+                                 const int32_t *cu_lens, void *o, float *lse, void *workspace,
+                                 size_t workspace_bytes, void *stream);
 
 /*
  * cart_trace_events -- optional per-kernel timing hook for benchmarks (not part of the paper).

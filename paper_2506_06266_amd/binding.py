@@ -22,7 +22,8 @@ STATUS_NAMES = ["CART_OK", "CART_ERR_NULL", "CART_ERR_SHAPE", "CART_ERR_UNSUPPOR
 
 EXPORTS = ["cart_attn_fwd_workspace", "cart_attn_bwd_workspace", "cart_kl_workspace",
            "cart_decode_workspace", "cart_attn_fwd", "cart_attn_bwd", "cart_distill_kl_fwd_bwd",
-           "cart_decode", "cart_trace_events", "cart_status_str", "cart_version"]
+           "cart_decode", "cart_decode_composed_workspace", "cart_decode_composed", "cart_trace_events",
+           "cart_status_str", "cart_version"]
 
 
 class AttnDesc(C.Structure):
@@ -34,6 +35,17 @@ class AttnDesc(C.Structure):
 class KlDesc(C.Structure):
     _fields_ = [("N", C.c_int32), ("V", C.c_int32), ("K", C.c_int32), ("logits_dtype", C.c_int),
                 ("scale", C.c_float), ("mode", C.c_int)]
+
+
+class Segment(C.Structure):
+    _fields_ = [("z_k", C.c_void_p), ("z_v", C.c_void_p), ("p", C.c_int32)]
+
+
+class DecodeComposedDesc(C.Structure):
+    _fields_ = [("B", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("D", C.c_int32),
+                ("n_shared", C.c_int32), ("n_pool", C.c_int32), ("pool_p", C.c_int32),
+                ("total_own_tokens", C.c_int32), ("max_own_len", C.c_int32), ("dtype", C.c_int),
+                ("softmax_scale", C.c_float)]
 
 
 class DecodeDesc(C.Structure):
@@ -74,6 +86,10 @@ def load() -> C.CDLL:
     lib.cart_distill_kl_fwd_bwd.argtypes = [C.POINTER(KlDesc)] + [vp] * 7 + [sz, vp]
     lib.cart_decode.restype = C.c_int
     lib.cart_decode.argtypes = [C.POINTER(DecodeDesc)] + [vp] * 9 + [sz, vp]
+    lib.cart_decode_composed_workspace.restype = sz
+    lib.cart_decode_composed_workspace.argtypes = [C.POINTER(DecodeComposedDesc), C.POINTER(Segment)]
+    lib.cart_decode_composed.restype = C.c_int
+    lib.cart_decode_composed.argtypes = [C.POINTER(DecodeComposedDesc), vp, C.POINTER(Segment)] + [vp] * 9 + [sz, vp]
     lib.cart_trace_events.restype = C.c_int
     lib.cart_trace_events.argtypes = [C.POINTER(C.c_void_p), C.c_int32]
     lib.cart_status_str.restype, lib.cart_status_str.argtypes = C.c_char_p, [C.c_int]
@@ -210,6 +226,30 @@ def cart_decode(q, z_k, z_v, k_own, v_own, cu_lens, max_own_len: int, *, scale: 
                          _ptr(cu_lens), _ptr(o), _ptr(lse), _ptr(ws),
                          0 if ws is None else ws.numel(), _stream(stream))
     _check(st, "cart_decode")
+    return o, lse
+
+
+def cart_decode_composed(q, shared, pool_k, pool_v, cart_id, k_own, v_own, cu_lens, max_own_len: int, *,
+                         scale: float = 0.0, o=None, lse=None, workspace=None, stream=None):
+    """q [B,Hq,D]; shared: list of (z_k, z_v) tensors [Hkv,p_s,D] every request attends over;
+    pool_k, pool_v [n_pool,Hkv,p_c,D] and cart_id [B] int32 (device; < 0 = none), or None;
+    k_own, v_own [T,Hkv,D]; cu_lens [B+1] int32 (device) -> (o [B,Hq,D], lse [B,Hq])."""
+    lib = load()
+    B, Hq, D = q.shape
+    segs = (Segment * max(len(shared), 1))()
+    for i, (zk, zv) in enumerate(shared):
+        segs[i] = Segment(_ptr(zk), _ptr(zv), zk.shape[1])
+    n_pool, pool_p = (0, 0) if pool_k is None else (pool_k.shape[0], pool_k.shape[2])
+    d = DecodeComposedDesc(B, Hq, k_own.shape[1], D, len(shared), n_pool, pool_p, k_own.shape[0], max_own_len,
+                           _dtype_code(q), scale)
+    o = torch.empty_like(q) if o is None else o
+    lse = torch.empty(B, Hq, dtype=torch.float32, device=q.device) if lse is None else lse
+    need = lib.cart_decode_composed_workspace(C.byref(d), segs)
+    ws = _workspace(need, workspace, q.device)
+    st = lib.cart_decode_composed(C.byref(d), _ptr(q), segs, _ptr(pool_k), _ptr(pool_v), _ptr(cart_id),
+                                  _ptr(k_own), _ptr(v_own), _ptr(cu_lens), _ptr(o), _ptr(lse), _ptr(ws),
+                                  0 if ws is None else ws.numel(), _stream(stream))
+    _check(st, "cart_decode_composed")
     return o, lse
 
 

@@ -89,6 +89,46 @@ size_t cart_kl_workspace(const cart_kl_desc* d) {
     return round256(static_cast<size_t>(d->N) * sizeof(float));
 }
 
+static cart_status check_decode_composed(const cart_decode_composed_desc* d, const cart_segment* shared) {
+    if (!d) return CART_ERR_NULL;
+    if (d->B < 1 || d->Hq < 1 || d->Hkv < 1 || d->D < 1) return CART_ERR_SHAPE;
+    if (d->Hq % d->Hkv) return CART_ERR_SHAPE;
+    if (d->n_shared < 0 || d->n_shared > CART_MAX_SEGMENTS) return CART_ERR_SHAPE;
+    if (d->n_pool < 0 || (d->n_pool > 0 && d->pool_p < 1)) return CART_ERR_SHAPE;
+    if (d->total_own_tokens < d->B || d->max_own_len < 1 || d->max_own_len > d->total_own_tokens) return CART_ERR_SHAPE;
+    if (isnan(d->softmax_scale) || isinf(d->softmax_scale) || d->softmax_scale < 0.f) return CART_ERR_SHAPE;
+    if (d->n_shared > 0 && !shared) return CART_ERR_NULL;
+    for (int s = 0; s < d->n_shared; ++s) {
+        if (shared[s].p < 0) return CART_ERR_SHAPE;
+        if (shared[s].p > 0 && (!shared[s].z_k || !shared[s].z_v)) return CART_ERR_NULL;
+        if ((reinterpret_cast<uintptr_t>(shared[s].z_k) | reinterpret_cast<uintptr_t>(shared[s].z_v)) & 15) return CART_ERR_ALIGN;
+    }
+    if (!cart::decode_composed_supported(*d)) return CART_ERR_UNSUPPORTED;
+    return CART_OK;
+}
+
+size_t cart_decode_composed_workspace(const cart_decode_composed_desc* d, const cart_segment* shared) {
+    if (check_decode_composed(d, shared) != CART_OK) return 0;
+    return cart::decode_composed_workspace(*d, shared);
+}
+
+cart_status cart_decode_composed(const cart_decode_composed_desc* d, const void* q, const cart_segment* shared,
+                                 const void* pool_k, const void* pool_v, const int32_t* cart_id,
+                                 const void* k_own, const void* v_own, const int32_t* cu_lens, void* o,
+                                 float* lse, void* workspace, size_t workspace_bytes, void* stream) {
+    cart_status s = check_decode_composed(d, shared);
+    if (s != CART_OK) return s;
+    REQUIRE(q); REQUIRE(k_own); REQUIRE(v_own); REQUIRE(cu_lens); REQUIRE(o);
+    if (d->n_pool > 0) { REQUIRE(pool_k); REQUIRE(pool_v); REQUIRE(cart_id); }
+    ALIGNED(q); ALIGNED(k_own); ALIGNED(v_own); ALIGNED(o); ALIGNED(pool_k); ALIGNED(pool_v); ALIGNED(workspace);
+    const size_t need = cart::decode_composed_workspace(*d, shared);
+    if (!workspace || workspace_bytes < need) return CART_ERR_WORKSPACE;
+    const float scale = attn_scale(d->softmax_scale, d->D);
+    int e = cart::launch_decode_composed(*d, scale, q, shared, pool_k, pool_v, cart_id, k_own, v_own, cu_lens, o,
+                                         lse, workspace, static_cast<hipStream_t>(stream));
+    return e == 0 ? CART_OK : CART_ERR_LAUNCH;
+}
+
 size_t cart_decode_workspace(const cart_decode_desc* d) {
     if (check_decode(d) != CART_OK) return 0;
     return use_mfma(*d) ? cart::decode_mfma_workspace(*d) : 0;

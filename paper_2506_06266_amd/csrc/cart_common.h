@@ -106,6 +106,12 @@ int launch_attn_bwd_mfma(const cart_attn_desc& d, float scale, const void* q, co
                          const void* v, const void* zk, const void* zv, const void* o,
                          const float* lse, const void* d_o, void* dq, void* dk, void* dv,
                          float* dzk, float* dzv, void* ws, hipStream_t st);
+bool decode_composed_supported(const cart_decode_composed_desc& d);
+size_t decode_composed_workspace(const cart_decode_composed_desc& d, const cart_segment* shared);
+int launch_decode_composed(const cart_decode_composed_desc& d, float scale, const void* q,
+                           const cart_segment* shared, const void* pool_k, const void* pool_v,
+                           const int32_t* cart_id, const void* k, const void* v, const int32_t* cu, void* o,
+                           float* lse, void* ws, hipStream_t st);
 bool decode_mfma_supported(const cart_decode_desc& d);
 size_t decode_mfma_workspace(const cart_decode_desc& d);
 int launch_decode_mfma(const cart_decode_desc& d, float scale, const void* q, const void* zk,

@@ -9,6 +9,11 @@
 // keys) streams its chunk through a private LDS slot with the G query rows padded into one
 // 32-column MFMA block (decode_own_kernel).  Every split writes a normalised partial (O, lse);
 // decode_merge_kernel combines them by their log-sum-exps.
+//
+// Composition (Sec. 5.4: cartridges trained apart are concatenated without retraining) and the
+// per-request cartridges of App. B's serving protocol use the same three kernels: the shared
+// prefix is a list of segments, each split and run like a single cartridge (a segment is never
+// copied next to another), and a request's private cartridge is streamed like its own KV.
 #include "attn_mfma.h"
 
 namespace cart {
@@ -21,30 +26,56 @@ constexpr int DEC_TILE_B = DEC_BN * ROW_B;
 constexpr int DEC_SUB = 32;            // own keys per wavefront step
 constexpr int DEC_SUB_B = DEC_SUB * ROW_B;
 
+constexpr int DEC_MAX_SEG = CART_MAX_SEGMENTS;
+
+// The shared prefix as a list of segments (one for a single cartridge), by value in the kernel
+// arguments.  Segment s is split along its slots into n_ps[s] parts of tiles_per_split[s] tiles;
+// its workgroups are blockIdx [blk0[s], blk0[s+1]) and its partial results slots slot0[s] + part.
+struct PrefixTable {
+    const bf16_t* zk[DEC_MAX_SEG];
+    const bf16_t* zv[DEC_MAX_SEG];
+    int p[DEC_MAX_SEG], tiles_per_split[DEC_MAX_SEG], n_ps[DEC_MAX_SEG], slot0[DEC_MAX_SEG];
+    int blk0[DEC_MAX_SEG + 1];
+    int n_seg;
+};
+
 struct DecodePlan {
-    int G, n_rb, tiles_per_split, n_ps;   // prefix: row blocks, tiles per split, splits
-    int chunk, n_oc;                      // own: keys per chunk, chunks per request (worst case)
+    PrefixTable tab;
+    int G, n_rb, n_ps;                    // prefix: row blocks, partial slots of all segments
+    int chunk, n_cc, n_oc;                // keys per chunk; chunks of a private cartridge / own KV (worst case)
     size_t part_o_bytes, part_l_bytes;
 };
 
-static DecodePlan make_plan(const cart_decode_desc& d) {
+// seg_p[n_seg]: slots per shared segment; pool_p: slots of a private cartridge (0 = none)
+static DecodePlan make_plan(int B, int Hq, int Hkv, int max_own_len, const int* seg_p, int n_seg, int pool_p) {
     DecodePlan p;
-    p.G = d.Hq / d.Hkv;
-    const int rows = d.B * p.G;
+    p.G = Hq / Hkv;
+    const int rows = B * p.G;
     p.n_rb = (rows + DEC_BM - 1) / DEC_BM;
-    const int nPt = (d.P + DEC_BN - 1) / DEC_BN;
-    if (nPt == 0) {
-        p.tiles_per_split = 0;
-        p.n_ps = 0;
-    } else {
-        int want = (256 + d.Hkv * p.n_rb - 1) / (d.Hkv * p.n_rb);   // splits to reach ~256 workgroups
-        want = want < 1 ? 1 : (want > nPt ? nPt : want);
-        p.tiles_per_split = (nPt + want - 1) / want;
-        p.n_ps = (nPt + p.tiles_per_split - 1) / p.tiles_per_split;
+    int total_tiles = 0;
+    for (int s = 0; s < n_seg; ++s) total_tiles += (seg_p[s] + DEC_BN - 1) / DEC_BN;
+    int want = (256 + Hkv * p.n_rb - 1) / (Hkv * p.n_rb);           // parts to reach ~256 workgroups
+    want = want < 1 ? 1 : (want > total_tiles ? total_tiles : want);
+    const int tps = total_tiles ? (total_tiles + want - 1) / want : 0;
+    p.tab.n_seg = 0;
+    p.tab.blk0[0] = 0;
+    p.n_ps = 0;
+    for (int s = 0; s < n_seg; ++s) {
+        const int nPt = (seg_p[s] + DEC_BN - 1) / DEC_BN;
+        if (nPt == 0) continue;                                     // an empty segment adds nothing
+        const int k = p.tab.n_seg++;
+        p.tab.p[k] = seg_p[s];
+        p.tab.tiles_per_split[k] = tps;
+        p.tab.n_ps[k] = (nPt + tps - 1) / tps;
+        p.tab.slot0[k] = p.n_ps;
+        p.n_ps += p.tab.n_ps[k];
+        p.tab.blk0[k + 1] = p.tab.blk0[k] + Hkv * p.n_rb * p.tab.n_ps[k];
+        p.tab.zk[k] = p.tab.zv[k] = nullptr;                        // filled by the launcher
     }
-    p.chunk = d.max_own_len > 4096 ? 1024 : 256;
-    p.n_oc = (d.max_own_len + p.chunk - 1) / p.chunk;
-    const size_t slots = static_cast<size_t>(p.n_ps + p.n_oc) * d.B * d.Hq;
+    p.chunk = (max_own_len > 4096 || pool_p > 4096) ? 1024 : 256;
+    p.n_cc = (pool_p + p.chunk - 1) / p.chunk;
+    p.n_oc = (max_own_len + p.chunk - 1) / p.chunk;
+    const size_t slots = static_cast<size_t>(p.n_ps + p.n_cc + p.n_oc) * B * Hq;
     p.part_o_bytes = (slots * HD * sizeof(float) + 255) & ~static_cast<size_t>(255);
     p.part_l_bytes = (slots * sizeof(float) + 255) & ~static_cast<size_t>(255);
     return p;
@@ -65,17 +96,22 @@ __device__ __forceinline__ void dec_acc_scale(float& x, float alpha) {
         : "v"(alpha));
 }
 
-// part_o [split][B][Hq][128] fp32 (normalised), part_l [split][B][Hq] (natural-log lse)
+// part_o [slot][B][Hq][128] fp32 (normalised), part_l [slot][B][Hq] (natural-log lse)
 __global__ __launch_bounds__(256, 1) void decode_prefix_kernel(
-    const bf16_t* __restrict__ q, const bf16_t* __restrict__ zk, const bf16_t* __restrict__ zv,
-    float* __restrict__ part_o, float* __restrict__ part_l, int B, int Hq, int Hkv, int P, float c,
-    int n_rb, int tiles_per_split) {
+    const bf16_t* __restrict__ q, const PrefixTable tab, float* __restrict__ part_o,
+    float* __restrict__ part_l, int B, int Hq, int Hkv, float c, int n_rb) {
     __shared__ DecSmem sm;
     const int G = Hq / Hkv;
-    int id = blockIdx.x;
+    int seg = 0;
+    while (seg + 1 < tab.n_seg && static_cast<int>(blockIdx.x) >= tab.blk0[seg + 1]) ++seg;
+    int id = blockIdx.x - tab.blk0[seg];
     const int hk = id % Hkv; id /= Hkv;
     const int rb = id % n_rb;
     const int sp = id / n_rb;
+    const bf16_t* zk = tab.zk[seg];
+    const bf16_t* zv = tab.zv[seg];
+    const int P = tab.p[seg], tiles_per_split = tab.tiles_per_split[seg];
+    const int slot_base = tab.slot0[seg];
     const int lane = threadIdx.x & 63, lg = lane >> 5, lc = lane & 31;
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int rows = B * G;
@@ -211,7 +247,7 @@ __global__ __launch_bounds__(256, 1) void decode_prefix_kernel(
         const float l_tot = l_run[cb] + partner(l_run[cb]);
         const float inv = 1.f / l_tot;
         if (rho < rows) {
-            const size_t slot = (static_cast<size_t>(sp) * B + rho / G) * Hq + hk * G + rho % G;
+            const size_t slot = (static_cast<size_t>(slot_base + sp) * B + rho / G) * Hq + hk * G + rho % G;
             float* op = part_o + slot * HD;
 #pragma unroll
             for (int db = 0; db < 4; ++db)
@@ -227,23 +263,46 @@ __global__ __launch_bounds__(256, 1) void decode_prefix_kernel(
     }
 }
 
-// One wavefront per (request, KV head, chunk of own keys); 32 keys per step through a private
-// 16 KB LDS slot.  The G query rows of the group occupy columns 0..G-1 of one MFMA block.
+// One wavefront per (request, KV head, chunk of keys): chunks 0 .. n_cc-1 cover the request's
+// private cartridge pool[cart_id[b]] ([Hkv,pool_p,128]; none when cart_id is null or negative),
+// chunks n_cc .. n_cc+n_oc-1 its own KV rows.  32 keys per step through a private 16 KB LDS
+// slot; the G query rows of the group occupy columns 0..G-1 of one MFMA block.
 __global__ __launch_bounds__(256, 2) void decode_own_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
-    const int32_t* __restrict__ cu, float* __restrict__ part_o, float* __restrict__ part_l, int B,
-    int Hq, int Hkv, float c, int chunk, int n_oc, int n_ps) {
+    const int32_t* __restrict__ cu, const bf16_t* __restrict__ pool_k, const bf16_t* __restrict__ pool_v,
+    const int32_t* __restrict__ cart_id, int pool_p, float* __restrict__ part_o,
+    float* __restrict__ part_l, int B, int Hq, int Hkv, float c, int chunk, int n_cc, int n_oc, int n_ps) {
     __shared__ char sm[4][2][DEC_SUB_B];   // [wavefront][K, V]
     const int G = Hq / Hkv;
     const int lane = threadIdx.x & 63, lg = lane >> 5, lc = lane & 31;
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     long item = static_cast<long>(blockIdx.x) * 4 + wv;
     const int hk = item % Hkv; item /= Hkv;
-    const int cc = item % n_oc;
-    const int b = static_cast<int>(item / n_oc);
+    const int cc = item % (n_cc + n_oc);
+    const int b = static_cast<int>(item / (n_cc + n_oc));
     if (b >= B) return;
-    const int t0 = cu[b], len = cu[b + 1] - t0;
-    const int k0 = cc * chunk;
+    const bool priv = cc < n_cc;
+    int len, k0;
+    uint32_t pitch;
+    const char *k_b, *v_b;
+    if (priv) {
+        const int cid = cart_id ? cart_id[b] : -1;
+        if (cid < 0) return;
+        len = pool_p;
+        k0 = cc * chunk;
+        pitch = ROW_B;
+        const size_t row0 = (static_cast<size_t>(cid) * Hkv + hk) * pool_p + k0;
+        k_b = reinterpret_cast<const char*>(pool_k) + row0 * ROW_B;
+        v_b = reinterpret_cast<const char*>(pool_v) + row0 * ROW_B;
+    } else {
+        const int t0 = cu[b];
+        len = cu[b + 1] - t0;
+        k0 = (cc - n_cc) * chunk;
+        pitch = static_cast<uint32_t>(Hkv) * ROW_B;
+        const size_t row0 = static_cast<size_t>(t0 + k0) * Hkv + hk;
+        k_b = reinterpret_cast<const char*>(k) + row0 * ROW_B;
+        v_b = reinterpret_cast<const char*>(v) + row0 * ROW_B;
+    }
     if (k0 >= len) return;
     const int nk = min(chunk, len - k0);
 
@@ -255,9 +314,6 @@ __global__ __launch_bounds__(256, 2) void decode_own_kernel(
     }
     char* kt = sm[wv][0];
     char* vt = sm[wv][1];
-    const uint32_t pitch = static_cast<uint32_t>(Hkv) * ROW_B;
-    const char* k_b = reinterpret_cast<const char*>(k) + (static_cast<size_t>(t0 + k0) * Hkv + hk) * ROW_B;
-    const char* v_b = reinterpret_cast<const char*>(v) + (static_cast<size_t>(t0 + k0) * Hkv + hk) * ROW_B;
     // 32 rows x 256 B = 8 direct-to-LDS loads of 4 rows each, per tensor, by this wavefront alone
     auto issue = [&](int j0) __attribute__((always_inline)) {
         const size_t step = static_cast<size_t>(j0) * pitch;
@@ -344,35 +400,42 @@ __global__ __launch_bounds__(256, 2) void decode_own_kernel(
     }
 }
 
-// o[b,h,:] = sum_i w_i part_o[i] / sum_i w_i, w_i = exp(lse_i - max lse), over the n_ps prefix
-// splits and the request's ceil(len/chunk) own chunks.  One wavefront per (b, h): lane i holds
-// partial i's lse and weight (n <= 64, else a serial loop), then every lane accumulates its two
-// head elements over the partials with the loads of four partials in flight.
+// o[b,h,:] = sum_i w_i part_o[i] / sum_i w_i, w_i = exp(lse_i - max lse), over the partial slots
+// that exist for the request: the n_ps prefix parts, the chunks of its private cartridge (when it
+// has one), the ceil(len/chunk) chunks of its own rows.  One wavefront per (b, h): lane i holds
+// slot i's lse and weight (up to 64 slots, else a serial loop), then every lane accumulates its
+// two head elements over the slots with the loads of four slots in flight.
 __global__ __launch_bounds__(256) void decode_merge_kernel(const float* __restrict__ part_o,
                                                            const float* __restrict__ part_l,
                                                            const int32_t* __restrict__ cu,
+                                                           const int32_t* __restrict__ cart_id, int pool_p,
                                                            bf16_t* __restrict__ o,
                                                            float* __restrict__ lse, int B, int Hq,
-                                                           int n_ps, int chunk) {
+                                                           int n_ps, int n_cc, int n_oc, int chunk) {
     const int lane = threadIdx.x & 63;
     const long row = static_cast<long>(blockIdx.x) * 4 + (threadIdx.x >> 6);
     if (row >= static_cast<long>(B) * Hq) return;
     const int b = row / Hq;
     const int len = cu[b + 1] - cu[b];
-    const int n = n_ps + (len + chunk - 1) / chunk;
+    const int priv = (n_cc > 0 && cart_id && cart_id[b] >= 0) ? (pool_p + chunk - 1) / chunk : 0;
+    const int own = (len + chunk - 1) / chunk;
+    const int n = n_ps + n_cc + n_oc;
+    auto valid = [&](int i) { return i < n_ps || (i < n_ps + n_cc ? i - n_ps < priv : i - n_ps - n_cc < own); };
     const size_t stride = static_cast<size_t>(B) * Hq;
     float wsum = 0.f, a0 = 0.f, a1 = 0.f, m;
     if (n <= 64) {
-        const float li = lane < n ? part_l[lane * stride + row] : -3.0e38f;
+        const float li = (lane < n && valid(lane)) ? part_l[lane * stride + row] : -3.0e38f;
         m = wave_max(li);
-        const float wi = lane < n ? __expf(li - m) : 0.f;
+        const float wi = (lane < n && valid(lane)) ? __expf(li - m) : 0.f;
         wsum = wave_sum(wi);
         int i = 0;
         for (; i + 4 <= n; i += 4) {
             float2 x[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                x[j] = *reinterpret_cast<const float2*>(part_o + ((i + j) * stride + row) * HD + 2 * lane);
+            for (int j = 0; j < 4; ++j) {
+                x[j] = float2{0.f, 0.f};
+                if (valid(i + j)) x[j] = *reinterpret_cast<const float2*>(part_o + ((i + j) * stride + row) * HD + 2 * lane);
+            }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const float w = __shfl(wi, i + j);
@@ -381,6 +444,7 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(const float* __restri
             }
         }
         for (; i < n; ++i) {
+            if (!valid(i)) continue;
             const float w = __shfl(wi, i);
             const float2 x = *reinterpret_cast<const float2*>(part_o + (i * stride + row) * HD + 2 * lane);
             a0 = fmaf(w, x.x, a0);
@@ -388,8 +452,10 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(const float* __restri
         }
     } else {
         m = -3.0e38f;
-        for (int i = 0; i < n; ++i) m = fmaxf(m, part_l[i * stride + row]);
+        for (int i = 0; i < n; ++i)
+            if (valid(i)) m = fmaxf(m, part_l[i * stride + row]);
         for (int i = 0; i < n; ++i) {
+            if (!valid(i)) continue;
             const float w = __expf(part_l[i * stride + row] - m);
             const float2 x = *reinterpret_cast<const float2*>(part_o + (i * stride + row) * HD + 2 * lane);
             wsum += w;
@@ -407,39 +473,80 @@ bool decode_mfma_supported(const cart_decode_desc& d) {
 }
 
 size_t decode_mfma_workspace(const cart_decode_desc& d) {
-    const DecodePlan p = make_plan(d);
+    const DecodePlan p = make_plan(d.B, d.Hq, d.Hkv, d.max_own_len, &d.P, d.P > 0 ? 1 : 0, 0);
     return p.part_o_bytes + p.part_l_bytes;
 }
 
-int launch_decode_mfma(const cart_decode_desc& d, float scale, const void* q, const void* zk,
-                       const void* zv, const void* k, const void* v, const int32_t* cu, void* o,
-                       float* lse, void* ws, hipStream_t st) {
-    const DecodePlan p = make_plan(d);
+bool decode_composed_supported(const cart_decode_composed_desc& d) {
+    return d.dtype == CART_BF16 && d.D == 128 && d.Hq / d.Hkv <= 32;
+}
+
+static DecodePlan composed_plan(const cart_decode_composed_desc& d, const cart_segment* shared) {
+    int seg_p[DEC_MAX_SEG];
+    for (int s = 0; s < d.n_shared; ++s) seg_p[s] = shared[s].p;
+    return make_plan(d.B, d.Hq, d.Hkv, d.max_own_len, seg_p, d.n_shared, d.n_pool > 0 ? d.pool_p : 0);
+}
+
+size_t decode_composed_workspace(const cart_decode_composed_desc& d, const cart_segment* shared) {
+    const DecodePlan p = composed_plan(d, shared);
+    return p.part_o_bytes + p.part_l_bytes;
+}
+
+// prefix parts, then private-cartridge and own chunks, then the merge
+static int run_decode(const DecodePlan& p, int B, int Hq, int Hkv, float scale, const void* q, const void* pool_k,
+                      const void* pool_v, const int32_t* cart_id, int pool_p, const void* k, const void* v,
+                      const int32_t* cu, void* o, float* lse, void* ws, hipStream_t st) {
     float* part_o = static_cast<float*>(ws);
     float* part_l = reinterpret_cast<float*>(static_cast<char*>(ws) + p.part_o_bytes);
     const float c = scale * CART_LOG2E;
     // (running the prefix kernel beside the own-KV kernel on a second stream was measured: the
     // event hand-over between the two queues costs more than the overlap gains, 141 vs 131 us)
     trace_begin(st);   // kernel order: prefix, own, merge
-    if (p.n_ps > 0) {
-        const unsigned grid = static_cast<unsigned>(d.Hkv) * p.n_rb * p.n_ps;
-        hipLaunchKernelGGL(decode_prefix_kernel, dim3(grid), dim3(256), 0, st,
-                           static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(zk),
-                           static_cast<const bf16_t*>(zv), part_o, part_l, d.B, d.Hq, d.Hkv, d.P, c, p.n_rb,
-                           p.tiles_per_split);
-    }
+    if (p.n_ps > 0)
+        hipLaunchKernelGGL(decode_prefix_kernel, dim3(static_cast<unsigned>(p.tab.blk0[p.tab.n_seg])), dim3(256), 0, st,
+                           static_cast<const bf16_t*>(q), p.tab, part_o, part_l, B, Hq, Hkv, c, p.n_rb);
     trace_mark(st);
-    const long items = static_cast<long>(d.B) * d.Hkv * p.n_oc;
+    const long items = static_cast<long>(B) * Hkv * (p.n_cc + p.n_oc);
     hipLaunchKernelGGL(decode_own_kernel, dim3(static_cast<unsigned>((items + 3) / 4)), dim3(256), 0, st,
                        static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(k),
-                       static_cast<const bf16_t*>(v), cu, part_o, part_l, d.B, d.Hq, d.Hkv, c, p.chunk, p.n_oc,
-                       p.n_ps);
+                       static_cast<const bf16_t*>(v), cu, static_cast<const bf16_t*>(pool_k),
+                       static_cast<const bf16_t*>(pool_v), cart_id, pool_p, part_o, part_l, B, Hq, Hkv, c, p.chunk,
+                       p.n_cc, p.n_oc, p.n_ps);
     trace_mark(st);
-    const long rows = static_cast<long>(d.B) * d.Hq;
+    const long rows = static_cast<long>(B) * Hq;
     hipLaunchKernelGGL(decode_merge_kernel, dim3(static_cast<unsigned>((rows + 3) / 4)), dim3(256), 0, st, part_o,
-                       part_l, cu, static_cast<bf16_t*>(o), lse, d.B, d.Hq, p.n_ps, p.chunk);
+                       part_l, cu, cart_id, pool_p, static_cast<bf16_t*>(o), lse, B, Hq, p.n_ps, p.n_cc, p.n_oc,
+                       p.chunk);
     trace_mark(st);
     return static_cast<int>(hipGetLastError());
+}
+
+int launch_decode_mfma(const cart_decode_desc& d, float scale, const void* q, const void* zk,
+                       const void* zv, const void* k, const void* v, const int32_t* cu, void* o,
+                       float* lse, void* ws, hipStream_t st) {
+    DecodePlan p = make_plan(d.B, d.Hq, d.Hkv, d.max_own_len, &d.P, d.P > 0 ? 1 : 0, 0);
+    if (p.tab.n_seg > 0) {
+        p.tab.zk[0] = static_cast<const bf16_t*>(zk);
+        p.tab.zv[0] = static_cast<const bf16_t*>(zv);
+    }
+    return run_decode(p, d.B, d.Hq, d.Hkv, scale, q, nullptr, nullptr, nullptr, 0, k, v, cu, o, lse, ws, st);
+}
+
+int launch_decode_composed(const cart_decode_composed_desc& d, float scale, const void* q,
+                           const cart_segment* shared, const void* pool_k, const void* pool_v,
+                           const int32_t* cart_id, const void* k, const void* v, const int32_t* cu, void* o,
+                           float* lse, void* ws, hipStream_t st) {
+    DecodePlan p = composed_plan(d, shared);
+    int kseg = 0;
+    for (int s = 0; s < d.n_shared; ++s) {
+        if (shared[s].p <= 0) continue;
+        p.tab.zk[kseg] = static_cast<const bf16_t*>(shared[s].z_k);
+        p.tab.zv[kseg] = static_cast<const bf16_t*>(shared[s].z_v);
+        ++kseg;
+    }
+    const bool pool = d.n_pool > 0 && d.pool_p > 0;
+    return run_decode(p, d.B, d.Hq, d.Hkv, scale, q, pool ? pool_k : nullptr, pool ? pool_v : nullptr,
+                      pool ? cart_id : nullptr, pool ? d.pool_p : 0, k, v, cu, o, lse, ws, st);
 }
 
 }  // namespace cart

@@ -111,3 +111,34 @@ def test_decode_full_size_sampled_requests(name, reqs):
     print(name, "worst", worst, flush=True)
     assert worst <= TOL
     assert torch.isfinite(o.float()).all() and torch.isfinite(lse).all()
+
+
+def test_decode_composed_full_size_sampled_requests():
+    """cfg5's shape with the cartridge in three unequal shared segments plus a 2048-slot cartridge
+    of its own for every other request."""
+    cfg = synth.DECODE_CONFIGS["cfg5"]
+    print("case cfg5 composed", flush=True)
+    g = synth.decode_inputs(cfg, DEV)
+    cuts = [0, 3000, 3064, cfg.P]
+    shared = [(g["z_k"][:, a:b].contiguous(), g["z_v"][:, a:b].contiguous()) for a, b in zip(cuts[:-1], cuts[1:])]
+    gen = torch.Generator(device=DEV).manual_seed(5)
+    n_pool, pool_p = 16, 2048
+    pool_k = (0.02 * torch.randn(n_pool, cfg.Hkv, pool_p, cfg.D, generator=gen, device=DEV)).to(torch.bfloat16)
+    pool_v = (0.5 * torch.randn(n_pool, cfg.Hkv, pool_p, cfg.D, generator=gen, device=DEV)).to(torch.bfloat16)
+    cart_id = (torch.arange(cfg.B, device=DEV) % (2 * n_pool)).to(torch.int32)
+    cart_id[cart_id >= n_pool] = -1
+    o, lse = cb.cart_decode_composed(g["q"], shared, pool_k, pool_v, cart_id, g["k_own"], g["v_own"], g["cu_lens"],
+                                     cfg.max_len)
+    torch.cuda.synchronize()
+    cu = g["cu_lens"].cpu().numpy()
+    ids = cart_id.cpu().numpy()
+    worst = 0.0
+    for b in [0, 1, 15, 16, 17, 63, 127]:
+        lo, hi = int(cu[b]), int(cu[b + 1])
+        o_ref, l_ref = orc.decode_composed(f64(g["q"][b:b + 1]), [(f64(a), f64(c)) for a, c in shared], f64(pool_k),
+                                           f64(pool_v), ids[b:b + 1], f64(g["k_own"][lo:hi]), f64(g["v_own"][lo:hi]),
+                                           np.array([0, hi - lo]))
+        worst = max(worst, rel_err(f64(o[b:b + 1]), o_ref), rel_err(f64(lse[b:b + 1]), l_ref))
+    print("cfg5 composed worst", worst, flush=True)
+    assert worst <= TOL
+    assert torch.isfinite(o.float()).all() and torch.isfinite(lse).all()

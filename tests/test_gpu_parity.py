@@ -352,3 +352,66 @@ def test_decode_matches_oracle(name, impl):
     e = {"o": rel_err(to_np(o), o_ref), "lse": rel_err(to_np(lse), lse_ref)}
     print(name, e, flush=True)
     assert e["o"] <= tol and e["lse"] <= tol
+
+
+# ------------------------------------------------------------------------------------------------
+# decode over composed cartridges / one cartridge per request
+# ------------------------------------------------------------------------------------------------
+def _composed_case(seed, B, Hq, Hkv, seg_ps, n_pool, pool_p, max_len):
+    g = torch.Generator().manual_seed(seed)
+    D = 128
+    rn = lambda *sz, std=1.0: (std * torch.randn(*sz, generator=g)).to(torch.bfloat16)
+    lens = torch.randint(1, max_len + 1, (B,), generator=g)
+    lens[0] = max_len
+    cu = torch.zeros(B + 1, dtype=torch.int32)
+    cu[1:] = torch.cumsum(lens, 0)
+    T = int(cu[-1])
+    c = {"q": rn(B, Hq, D, std=0.3), "k_own": rn(T, Hkv, D, std=0.3), "v_own": rn(T, Hkv, D), "cu": cu,
+         "shared": [(rn(Hkv, p, D, std=0.3), rn(Hkv, p, D)) for p in seg_ps], "max_len": max_len}
+    if n_pool:
+        c["pool_k"], c["pool_v"] = rn(n_pool, Hkv, pool_p, D, std=0.3), rn(n_pool, Hkv, pool_p, D)
+        ids = torch.randint(-1, n_pool, (B,), generator=g)
+        ids[0], ids[-1] = n_pool - 1, -1
+        c["cart_id"] = ids.to(torch.int32)
+    else:
+        c["pool_k"] = c["pool_v"] = c["cart_id"] = None
+    return c
+
+
+def _run_composed(c):
+    f = to_np
+    o_ref, lse_ref = orc.decode_composed(
+        f(c["q"]), [(f(a), f(b)) for a, b in c["shared"]], None if c["pool_k"] is None else f(c["pool_k"]),
+        None if c["pool_v"] is None else f(c["pool_v"]), None if c["cart_id"] is None else c["cart_id"].numpy(),
+        f(c["k_own"]), f(c["v_own"]), c["cu"].numpy())
+    d = lambda t: None if t is None else t.to(DEV)
+    o, lse = cb.cart_decode_composed(d(c["q"]), [(d(a), d(b)) for a, b in c["shared"]], d(c["pool_k"]), d(c["pool_v"]),
+                                     d(c["cart_id"]), d(c["k_own"]), d(c["v_own"]), d(c["cu"]), c["max_len"])
+    torch.cuda.synchronize()
+    return {"o": rel_err(to_np(o), o_ref), "lse": rel_err(to_np(lse), lse_ref)}, o, lse
+
+
+@pytest.mark.parametrize("case", [
+    dict(seed=1, B=6, Hq=8, Hkv=2, seg_ps=(70, 64, 200), n_pool=0, pool_p=0, max_len=50),     # three shared segments
+    dict(seed=2, B=9, Hq=8, Hkv=2, seg_ps=(), n_pool=4, pool_p=300, max_len=40),              # one cartridge per request
+    dict(seed=3, B=5, Hq=4, Hkv=4, seg_ps=(1, 0, 129), n_pool=3, pool_p=33, max_len=300),     # both, an empty segment
+    dict(seed=4, B=70, Hq=32, Hkv=8, seg_ps=(512, 1024, 256, 64, 64, 64, 64, 64), n_pool=0, pool_p=0, max_len=20),
+    dict(seed=5, B=3, Hq=2, Hkv=1, seg_ps=(), n_pool=0, pool_p=0, max_len=17),                # nothing but own rows
+], ids=["shared3", "pool", "both", "eight_segments", "own_only"])
+def test_decode_composed_matches_oracle(case):
+    print("case composed", case, flush=True)
+    c = _composed_case(**case)
+    e, _, _ = _run_composed(c)
+    print(e, flush=True)
+    assert e["o"] <= TOL["bf16"] and e["lse"] <= TOL["bf16"]
+
+
+def test_decode_composed_single_segment_is_cart_decode():
+    """One shared segment and no pool: the same kernels, the same bits as cart_decode."""
+    cfg = synth.DECODE_CONFIGS["decode_small"]
+    g = dev(synth.decode_inputs(cfg))
+    o1, l1 = cb.cart_decode(g["q"], g["z_k"], g["z_v"], g["k_own"], g["v_own"], g["cu_lens"], cfg.max_len)
+    o2, l2 = cb.cart_decode_composed(g["q"], [(g["z_k"], g["z_v"])], None, None, None, g["k_own"], g["v_own"],
+                                     g["cu_lens"], cfg.max_len)
+    torch.cuda.synchronize()
+    assert torch.equal(o1, o2) and torch.equal(l1, l2)
