@@ -23,6 +23,8 @@ What each function follows (arxiv 2506.06266):
   distributions); ntp_cross_entropy -- the next-token objective Sec. 4.2
   compares context distillation with (ablated in Sec. 5.3), with an ignore
   label.
+* teacher_topk -- App. A.2: the teacher's top output probabilities, recorded
+  at data-generation time (what distill_kl consumes).
 * decode -- Sec. 2.3 (decode: one new query over the whole cache) with the
   cache of Sec. 3.3 (a cartridge is served as a cached prefix of length p).
   decode_composed -- the same over several cartridges concatenated (Sec. 5.4,
@@ -44,7 +46,7 @@ from typing import Optional, Tuple
 
 import numpy as np
 
-__all__ = ["attn_fwd", "attn_bwd", "distill_kl", "distill_kl_rest_bucket", "ntp_cross_entropy", "decode", "decode_composed"]
+__all__ = ["attn_fwd", "attn_bwd", "distill_kl", "distill_kl_rest_bucket", "ntp_cross_entropy", "decode", "decode_composed", "teacher_topk"]
 
 
 def _f64(x) -> np.ndarray:
@@ -300,3 +302,22 @@ def decode_composed(q, shared, pool_k, pool_v, cart_id, k_own, v_own, cu_lens, s
             o[b, h] = (e / l) @ vals
             lse[b, h] = m + math.log(l)
     return o, lse
+
+
+def teacher_topk(logits, k: int):
+    """The records App. A.2 says are collected while the teacher generates: at every position the
+    k most probable next tokens and their log-probabilities.
+
+    logits [N,V] -> idx [N,k] int64, logp [N,k], each row by descending probability; among equal
+    logits the lower token index comes first (so the result is unique)."""
+    z = _f64(logits)
+    N, V = z.shape
+    idx = np.zeros((N, k), dtype=np.int64)
+    logp = np.zeros((N, k))
+    for n in range(N):
+        m = z[n].max()
+        lse = m + math.log(np.exp(z[n] - m).sum())
+        order = sorted(range(V), key=lambda v: (-z[n, v], v))[:k]
+        idx[n] = order
+        logp[n] = z[n, order] - lse
+    return idx, logp
