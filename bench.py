@@ -154,6 +154,11 @@ def main() -> int:
     ntp_ms = timed(lambda: cb.cart_distill_kl_fwd_bwd(kl["logits"], labels, None, kcfg.scale, d_logits=dlogits,
                                                       loss=loss, workspace=ws_kl))
 
+    # teacher records: top-20 tokens and log-probabilities of every cfg4 row
+    tk_idx = torch.empty(kcfg.N, kcfg.K, dtype=torch.int32, device=dev)
+    tk_lp = torch.empty(kcfg.N, kcfg.K, dtype=torch.float32, device=dev)
+    topk_ms = timed(lambda: cb.cart_teacher_topk(kl["logits"], kcfg.K, teacher_idx=tk_idx, teacher_logp=tk_lp))
+
     # decode with the cartridge in pieces: cfg5's 8192 slots as four shared segments, and the
     # paper's serving protocol of one cartridge per request (128 requests x 2048 slots)
     quarter = dcfg.P // 4
@@ -218,6 +223,8 @@ def main() -> int:
                       "kl_rest_bucket_gbs": round((2 * kcfg.N * kcfg.V * 2 + kcfg.N * kcfg.K * 8) / rest_ms / 1e6, 1),
                       "ntp_cross_entropy_ms": round(ntp_ms, 4),
                       "ntp_cross_entropy_gbs": round((2 * kcfg.N * kcfg.V * 2 + kcfg.N * 4) / ntp_ms / 1e6, 1),
+                      "teacher_topk_ms": round(topk_ms, 4),
+                      "teacher_topk_gbs": round(kcfg.N * kcfg.V * 2 / topk_ms / 1e6, 1),
                       "decode_4_shared_segments_ms": round(seg_ms, 4),
                       "decode_cartridge_per_request_ms": round(pool_ms, 4),
                       "decode_cartridge_per_request_gbs": round(pool_bytes / pool_ms / 1e6, 1)},

@@ -85,6 +85,14 @@ typedef struct {
     cart_impl impl;
 } cart_decode_desc;
 
+/* Teacher records over N positions (App. A.2): the K most probable tokens of each. */
+typedef struct {
+    int32_t N;              /* positions (rows), >= 1 */
+    int32_t V;              /* vocabulary size, >= 1 */
+    int32_t K;              /* records per position, 1..min(V, 1024) */
+    cart_dtype logits_dtype;
+} cart_topk_desc;
+
 /* One trained cartridge (or a piece of one): key and value vectors [Hkv,p,D], device memory. */
 typedef struct {
     const void *z_k;
@@ -182,6 +190,19 @@ cart_status cart_decode(const cart_decode_desc *desc, const void *q, const void 
                         const void *z_v, const void *k_own, const void *v_own,
                         const int32_t *cu_lens, void *o, float *lse, void *workspace,
                         size_t workspace_bytes, void *stream);
+
+/*
+ * cart_teacher_topk -- the producer of cart_distill_kl_fwd_bwd's teacher inputs (App. A.2: the
+ * teacher's top output probabilities are collected while it generates).  Per position n:
+ *   teacher_idx[n,0..K)  the K tokens with the largest logits, by descending logit, the lower
+ *                        token index first among equal logits (so the result is unique);
+ *   teacher_logp[n,j]  = logits[n, teacher_idx[n,j]] - log sum_v exp(logits[n,v]).
+ *   logits [N,V] in (bf16 or fp32);  teacher_idx [N,K] int32 out;  teacher_logp [N,K] fp32 out.
+ * No workspace.  Indices are exact (comparisons on the stored values); log-probabilities carry
+ * the rounding of an fp32 log-sum-exp.
+ */
+cart_status cart_teacher_topk(const cart_topk_desc *desc, const void *logits, int32_t *teacher_idx,
+                              float *teacher_logp, void *stream);
 
 /*
  * cart_decode_composed -- cart_decode with the prefix given in pieces.  Request b attends over,

@@ -22,7 +22,7 @@ STATUS_NAMES = ["CART_OK", "CART_ERR_NULL", "CART_ERR_SHAPE", "CART_ERR_UNSUPPOR
 
 EXPORTS = ["cart_attn_fwd_workspace", "cart_attn_bwd_workspace", "cart_kl_workspace",
            "cart_decode_workspace", "cart_attn_fwd", "cart_attn_bwd", "cart_distill_kl_fwd_bwd",
-           "cart_decode", "cart_decode_composed_workspace", "cart_decode_composed", "cart_trace_events",
+           "cart_decode", "cart_decode_composed_workspace", "cart_decode_composed", "cart_teacher_topk", "cart_trace_events",
            "cart_status_str", "cart_version"]
 
 
@@ -35,6 +35,10 @@ class AttnDesc(C.Structure):
 class KlDesc(C.Structure):
     _fields_ = [("N", C.c_int32), ("V", C.c_int32), ("K", C.c_int32), ("logits_dtype", C.c_int),
                 ("scale", C.c_float), ("mode", C.c_int)]
+
+
+class TopkDesc(C.Structure):
+    _fields_ = [("N", C.c_int32), ("V", C.c_int32), ("K", C.c_int32), ("logits_dtype", C.c_int)]
 
 
 class Segment(C.Structure):
@@ -86,6 +90,8 @@ def load() -> C.CDLL:
     lib.cart_distill_kl_fwd_bwd.argtypes = [C.POINTER(KlDesc)] + [vp] * 7 + [sz, vp]
     lib.cart_decode.restype = C.c_int
     lib.cart_decode.argtypes = [C.POINTER(DecodeDesc)] + [vp] * 9 + [sz, vp]
+    lib.cart_teacher_topk.restype = C.c_int
+    lib.cart_teacher_topk.argtypes = [C.POINTER(TopkDesc), vp, vp, vp, vp]
     lib.cart_decode_composed_workspace.restype = sz
     lib.cart_decode_composed_workspace.argtypes = [C.POINTER(DecodeComposedDesc), C.POINTER(Segment)]
     lib.cart_decode_composed.restype = C.c_int
@@ -227,6 +233,18 @@ def cart_decode(q, z_k, z_v, k_own, v_own, cu_lens, max_own_len: int, *, scale: 
                          0 if ws is None else ws.numel(), _stream(stream))
     _check(st, "cart_decode")
     return o, lse
+
+
+def cart_teacher_topk(logits, k: int, *, teacher_idx=None, teacher_logp=None, stream=None):
+    """logits [N,V] -> (teacher_idx [N,k] int32, teacher_logp [N,k] fp32), by descending probability."""
+    lib = load()
+    N, V = logits.shape
+    d = TopkDesc(N, V, k, _dtype_code(logits))
+    idx = torch.empty(N, k, dtype=torch.int32, device=logits.device) if teacher_idx is None else teacher_idx
+    lp = torch.empty(N, k, dtype=torch.float32, device=logits.device) if teacher_logp is None else teacher_logp
+    st = lib.cart_teacher_topk(C.byref(d), _ptr(logits), _ptr(idx), _ptr(lp), _stream(stream))
+    _check(st, "cart_teacher_topk")
+    return idx, lp
 
 
 def cart_decode_composed(q, shared, pool_k, pool_v, cart_id, k_own, v_own, cu_lens, max_own_len: int, *,

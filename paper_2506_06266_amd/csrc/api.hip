@@ -89,6 +89,18 @@ size_t cart_kl_workspace(const cart_kl_desc* d) {
     return round256(static_cast<size_t>(d->N) * sizeof(float));
 }
 
+cart_status cart_teacher_topk(const cart_topk_desc* d, const void* logits, int32_t* teacher_idx,
+                              float* teacher_logp, void* stream) {
+    if (!d) return CART_ERR_NULL;
+    if (d->N < 1 || d->V < 1 || d->K < 1 || d->K > d->V) return CART_ERR_SHAPE;
+    if (d->K > 1024) return CART_ERR_UNSUPPORTED;
+    if (d->logits_dtype != CART_F32 && d->logits_dtype != CART_BF16) return CART_ERR_UNSUPPORTED;
+    REQUIRE(logits); REQUIRE(teacher_idx); REQUIRE(teacher_logp);
+    ALIGNED(logits);
+    int e = cart::launch_topk(*d, logits, teacher_idx, teacher_logp, static_cast<hipStream_t>(stream));
+    return e == 0 ? CART_OK : CART_ERR_LAUNCH;
+}
+
 static cart_status check_decode_composed(const cart_decode_composed_desc* d, const cart_segment* shared) {
     if (!d) return CART_ERR_NULL;
     if (d->B < 1 || d->Hq < 1 || d->Hkv < 1 || d->D < 1) return CART_ERR_SHAPE;

@@ -106,6 +106,7 @@ int launch_attn_bwd_mfma(const cart_attn_desc& d, float scale, const void* q, co
                          const void* v, const void* zk, const void* zv, const void* o,
                          const float* lse, const void* d_o, void* dq, void* dk, void* dv,
                          float* dzk, float* dzv, void* ws, hipStream_t st);
+int launch_topk(const cart_topk_desc& d, const void* logits, int32_t* idx, float* logp, hipStream_t st);
 bool decode_composed_supported(const cart_decode_composed_desc& d);
 size_t decode_composed_workspace(const cart_decode_composed_desc& d, const cart_segment* shared);
 int launch_decode_composed(const cart_decode_composed_desc& d, float scale, const void* q,

@@ -106,16 +106,14 @@ __global__ __launch_bounds__(1024) void kl_row_resident(const bf16_t* logits, co
     float m_part = kl_stage_teacher<bf16_t, THREADS>(tc, logits + row, idx + static_cast<size_t>(n) * K,
                                                     logp ? logp + static_cast<size_t>(n) * K : nullptr, V, K);
 
-    // sweep 1: a reference value within one bf16 ulp of the row maximum.  The packed word read
-    // as fp32 is the high element plus a sub-ulp perturbation, which is good enough here: any
-    // reference close to the maximum keeps the exponentials in range, and the log-sum-exp below
-    // is exact for whatever reference was used.
+    // sweep 1: the row maximum; both elements of a packed word widened to fp32 (a word of two
+    // -inf logits read whole would be a NaN) and a three-way maximum
     float mx = -3.0e38f;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
         const uint32_t w[4] = {x[i].x, x[i].y, x[i].z, x[i].w};
 #pragma unroll
-        for (int e = 0; e < 4; ++e) mx = max3_raw(mx, w[e], w[e] << 16);
+        for (int e = 0; e < 4; ++e) mx = max3_raw(mx, w[e] & 0xffff0000u, w[e] << 16);
     }
     KL_FORGET(x);
     mx = wave_max(mx);

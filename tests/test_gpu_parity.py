@@ -303,6 +303,28 @@ def test_ntp_cross_entropy_matches_oracle(dtype, V):
         assert (lab_grad < 0).all()
 
 
+def test_distill_kl_with_masked_vocabulary():
+    """Logits of -inf (tokens the student may not emit), in adjacent pairs and whole vectors: zero
+    probability, zero gradient there, everything else as the oracle says."""
+    N, V, K = 8, 32768, 20
+    g = torch.Generator().manual_seed(21)
+    z = (2.0 * torch.randn(N, V, generator=g))
+    z[:, 1000:3000] = float("-inf")
+    z[:, 20000:20002] = float("-inf")
+    z[3, :16384] = float("-inf")
+    z = z.to(torch.bfloat16)
+    idx = torch.stack([torch.randperm(V - 16384, generator=g)[:K] + 16384 for _ in range(N)]).to(torch.int32)
+    lp = torch.log_softmax(torch.randn(N, K, generator=g), dim=1) + math.log(0.9)
+    for mode, ref in ((cb.KL_TOPK, orc.distill_kl), (cb.KL_REST, orc.distill_kl_rest_bucket)):
+        loss_ref, dl_ref, row_ref = ref(to_np(z), idx.numpy(), to_np(lp), 0.125)
+        row = torch.empty(N, dtype=torch.float32, device=DEV)
+        loss, dl = cb.cart_distill_kl_fwd_bwd(z.to(DEV), idx.to(DEV), lp.to(DEV), 0.125, mode=mode, row_kl=row)
+        torch.cuda.synchronize()
+        assert abs(loss.item() - loss_ref) <= 1e-4 * abs(loss_ref)
+        assert rel_err(to_np(row), row_ref) <= 1e-4 and rel_err(to_np(dl), dl_ref) <= TOL["bf16"]
+        assert not dl[:, 1000:3000].any()
+
+
 def test_distill_kl_special_cases():
     rng = np.random.default_rng(0)
     N, V = 9, 1000
@@ -415,3 +437,63 @@ def test_decode_composed_single_segment_is_cart_decode():
                                      g["cu_lens"], cfg.max_len)
     torch.cuda.synchronize()
     assert torch.equal(o1, o2) and torch.equal(l1, l2)
+
+
+# ------------------------------------------------------------------------------------------------
+# teacher top-k records
+# ------------------------------------------------------------------------------------------------
+def _check_topk(logits, k):
+    idx_ref, lp_ref = orc.teacher_topk(to_np(logits), k)
+    idx, lp = cb.cart_teacher_topk(logits.to(DEV), k)
+    torch.cuda.synchronize()
+    assert idx.dtype == torch.int32 and lp.dtype == torch.float32
+    assert np.array_equal(idx.cpu().numpy().astype(np.int64), idx_ref), "indices must match bit for bit"
+    assert np.abs(lp.cpu().numpy().astype(np.float64) - lp_ref).max() <= 1e-4 * max(1.0, np.abs(lp_ref).max())
+
+
+@pytest.mark.parametrize("dtype,N,V,k", [
+    (torch.bfloat16, 24, 128256, 20),      # the register-resident path at the paper's vocabulary
+    (torch.bfloat16, 16, 32768, 64),
+    (torch.bfloat16, 16, 1000, 20),        # most threads without data
+    (torch.bfloat16, 8, 50257, 20),        # not a multiple of 8: streaming path
+    (torch.float32, 32, 1000, 20),
+    (torch.float32, 4, 40000, 1),
+    (torch.bfloat16, 4, 4096, 1024),       # the largest k
+], ids=lambda v: str(v).replace("torch.", ""))
+def test_teacher_topk_matches_oracle(dtype, N, V, k):
+    print("case topk", dtype, N, V, k, flush=True)
+    g = torch.Generator().manual_seed(V + k)
+    _check_topk((2.5 * torch.randn(N, V, generator=g)).to(dtype), k)
+
+
+def test_teacher_topk_ties():
+    """bf16 logits tie all the time; the order among equals is by token index.  Coarse grids put
+    thousands of ties at the top (the list overflows: the slower exact path), an all-equal row and a
+    row of -inf but for a few entries are the extremes."""
+    g = torch.Generator().manual_seed(9)
+    V = 128256
+    x = torch.randn(6, V, generator=g)
+    rows = [x[0] * 3, torch.round(x[1] * 2) / 2, torch.round(x[2]), torch.zeros(V), torch.clamp(x[4], max=0.5),
+            torch.full((V,), float("-inf"))]
+    rows[5][torch.tensor([7, 100000, 5, 90000, 128255])] = torch.tensor([1.0, 1.0, 0.5, 2.0, 1.0])
+    rows[5][torch.arange(1000, 1040)] = -3.0
+    # +0 and -0 are the same logit: a row whose top is a mix of the two
+    zeros = torch.full((V,), -1.0)
+    zeros[torch.arange(50, 90)] = 0.0
+    zeros[torch.arange(50, 90, 2)] = -0.0
+    rows.append(zeros)
+    _check_topk(torch.stack(rows).to(torch.bfloat16), 20)
+    # the same through the streaming kernels
+    _check_topk(torch.stack([r[:5003] for r in rows[:5]]).to(torch.bfloat16), 20)
+    _check_topk(torch.stack([r[:3000] for r in rows[:5]]).to(torch.float32), 33)
+
+
+def test_teacher_topk_feeds_the_loss():
+    """Records produced on the GPU, consumed by the loss on the GPU: a student equal to the teacher
+    has zero rest-bucket loss and zero gradient."""
+    g = torch.Generator().manual_seed(3)
+    z = (2.0 * torch.randn(32, 8192, generator=g)).to(torch.bfloat16).to(DEV)
+    idx, lp = cb.cart_teacher_topk(z, 20)
+    loss, dl = cb.cart_distill_kl_fwd_bwd(z, idx, lp, 1.0, mode=cb.KL_REST)
+    torch.cuda.synchronize()
+    assert abs(loss.item()) < 1e-4 and dl.float().abs().max().item() < 1e-4
