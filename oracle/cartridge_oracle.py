@@ -14,6 +14,8 @@ What each function follows (arxiv 2506.06266):
   The backward pass is the analytic gradient of that definition; Sec. 3.2
   trains Z by back-propagating into the key and value vectors with the model
   frozen, so dZ sums every query of every sequence in the batch.
+  attn_varlen_fwd / attn_varlen_bwd -- the same over a packed batch of
+  sequences of different lengths (the ragged Self-Study batches of App. A.1).
 * distill_kl -- Eq. 3 (Sec. 4.2), the KL divergence from the teacher's to the
   student's next-token distribution, restricted to the teacher entries that
   were recorded (App. A.2 "Training Objective": top output probabilities are
@@ -46,7 +48,7 @@ from typing import Optional, Tuple
 
 import numpy as np
 
-__all__ = ["attn_fwd", "attn_bwd", "distill_kl", "distill_kl_rest_bucket", "ntp_cross_entropy", "decode", "decode_composed", "teacher_topk"]
+__all__ = ["attn_fwd", "attn_bwd", "distill_kl", "distill_kl_rest_bucket", "ntp_cross_entropy", "decode", "decode_composed", "teacher_topk", "attn_varlen_fwd", "attn_varlen_bwd"]
 
 
 def _f64(x) -> np.ndarray:
@@ -321,3 +323,39 @@ def teacher_topk(logits, k: int):
         idx[n] = order
         logp[n] = z[n, order] - lse
     return idx, logp
+
+
+def attn_varlen_fwd(q, k_own, v_own, z_k, z_v, cu_seqlens, scale: Optional[float] = None):
+    """attn_fwd over a packed batch of sequences of different lengths (App. A.1: Self-Study
+    conversations are short and ragged; a training batch is their concatenation).
+
+    q [T,Hq,d]; k_own, v_own [T,Hkv,d]; sequence b owns rows cu_seqlens[b] .. cu_seqlens[b+1]-1 and
+    attends over [Z ; its own rows, causally] exactly as a batch of one in attn_fwd.
+    Returns o [T,Hq,d] and lse [Hq,T]."""
+    q, k_own, v_own = map(_f64, (q, k_own, v_own))
+    cu = np.asarray(cu_seqlens, dtype=np.int64)
+    T, Hq, d = q.shape
+    o = np.zeros((T, Hq, d))
+    lse = np.zeros((Hq, T))
+    for b in range(len(cu) - 1):
+        sl = slice(cu[b], cu[b + 1])
+        ob, lb = attn_fwd(q[None, sl], k_own[None, sl], v_own[None, sl], z_k, z_v, scale)
+        o[sl] = ob[0]
+        lse[:, sl] = lb[0]
+    return o, lse
+
+
+def attn_varlen_bwd(q, k_own, v_own, z_k, z_v, d_o, cu_seqlens, scale: Optional[float] = None):
+    """Gradient of attn_varlen_fwd: per sequence as attn_bwd; the prefix gradients add up over the
+    sequences of the packed batch.  Returns (d_q, d_k_own, d_v_own [packed], d_z_k, d_z_v)."""
+    q, k_own, v_own, d_o = map(_f64, (q, k_own, v_own, d_o))
+    cu = np.asarray(cu_seqlens, dtype=np.int64)
+    d_q, d_k, d_v = np.zeros_like(q), np.zeros_like(k_own), np.zeros_like(v_own)
+    d_zk, d_zv = np.zeros_like(_f64(z_k)), np.zeros_like(_f64(z_v))
+    for b in range(len(cu) - 1):
+        sl = slice(cu[b], cu[b + 1])
+        g = attn_bwd(q[None, sl], k_own[None, sl], v_own[None, sl], z_k, z_v, d_o[None, sl], scale)
+        d_q[sl], d_k[sl], d_v[sl] = g[0][0], g[1][0], g[2][0]
+        d_zk += g[3]
+        d_zv += g[4]
+    return d_q, d_k, d_v, d_zk, d_zv
