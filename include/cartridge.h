@@ -115,9 +115,24 @@ typedef struct {
     float softmax_scale;        /* 0 selects 1/sqrt(D) */
 } cart_decode_composed_desc;
 
+/* A packed batch of sequences of different lengths for cart_attn_varlen_fwd / _bwd (App. A.1:
+ * Self-Study conversations are short and ragged; they are trained on concatenated, not padded). */
+typedef struct {
+    int32_t T;              /* packed rows = sum of the sequence lengths, >= 1 */
+    int32_t B;              /* sequences, >= 1 */
+    int32_t max_seqlen;     /* an upper bound of every sequence length, 1 <= max_seqlen <= T */
+    int32_t Hq, Hkv, D, P;  /* as in cart_attn_desc; D = 128 */
+    cart_dtype dtype;       /* CART_BF16 */
+    float softmax_scale;    /* 0 selects 1/sqrt(D) */
+    int32_t n_frozen;       /* as in cart_attn_desc */
+    int32_t dz_accumulate;  /* as in cart_attn_desc */
+} cart_attn_varlen_desc;
+
 /* Bytes of workspace each entry point needs for the given descriptor (0 on an invalid one). */
 size_t cart_attn_fwd_workspace(const cart_attn_desc *desc);
 size_t cart_attn_bwd_workspace(const cart_attn_desc *desc);
+size_t cart_attn_varlen_fwd_workspace(const cart_attn_varlen_desc *desc);
+size_t cart_attn_varlen_bwd_workspace(const cart_attn_varlen_desc *desc);
 size_t cart_kl_workspace(const cart_kl_desc *desc);
 size_t cart_decode_workspace(const cart_decode_desc *desc);
 size_t cart_decode_composed_workspace(const cart_decode_composed_desc *desc, const cart_segment *shared);
@@ -222,10 +237,35 @@ cart_status cart_decode_composed(const cart_decode_composed_desc *desc, const vo
                                  size_t workspace_bytes, void *stream);
 
 /*
+ * cart_attn_varlen_fwd / cart_attn_varlen_bwd -- cart_attn_fwd / cart_attn_bwd (Eq. 1 over the
+ * cache of Sec. 3.2, and its gradient) over a packed batch: sequence b owns rows
+ * cu_seqlens[b] .. cu_seqlens[b+1]-1 of the T packed rows and attends over [Z ; its own rows,
+ * causally] exactly as one sequence of a cart_attn_fwd batch; d_z_k / d_z_v sum over all
+ * sequences.  Sequences never see each other.
+ *   q, o, d_o, d_q [T,Hq,D];  k_own, v_own, d_k_own, d_v_own [T,Hkv,D];  z_k, z_v [Hkv,P,D];
+ *   lse [Hq,T] fp32;  d_z_k, d_z_v [Hkv,P,D] fp32 (n_frozen / dz_accumulate as in cart_attn_bwd);
+ *   cu_seqlens [B+1] int32 in (device): cu_seqlens[0] = 0, non-decreasing, cu_seqlens[B] = T,
+ *   no length above max_seqlen.  The library cannot see the array's contents: offsets outside
+ *   [0, T] are the caller's error and are not detected; a sequence may be empty.
+ * bf16 with D = 128 only (CART_ERR_UNSUPPORTED otherwise).  Other rules as in cart_attn_fwd /
+ * cart_attn_bwd.
+ */
+cart_status cart_attn_varlen_fwd(const cart_attn_varlen_desc *desc, const void *q, const void *k_own,
+                                 const void *v_own, const void *z_k, const void *z_v,
+                                 const int32_t *cu_seqlens, void *o, float *lse, void *workspace,
+                                 size_t workspace_bytes, void *stream);
+cart_status cart_attn_varlen_bwd(const cart_attn_varlen_desc *desc, const void *q, const void *k_own,
+                                 const void *v_own, const void *z_k, const void *z_v,
+                                 const int32_t *cu_seqlens, const void *o, const float *lse,
+                                 const void *d_o, void *d_q, void *d_k_own, void *d_v_own,
+                                 float *d_z_k, float *d_z_v, void *workspace, size_t workspace_bytes,
+                                 void *stream);
+
+/*
  * cart_trace_events -- optional per-kernel timing hook for benchmarks (not part of the paper).
  * `events` is a host array of `count` hipEvent_t handles (passed as void*), or NULL to switch
- * the hook off.  While set, every later cart_attn_fwd / cart_attn_bwd / cart_distill_kl_fwd_bwd /
- * cart_decode call records events[0] on its stream before its first kernel and events[i] after
+ * the hook off.  While set, every later cart_attn_fwd / cart_attn_bwd (also the packed
+ * variants) / cart_distill_kl_fwd_bwd / cart_decode call records events[0] on its stream before its first kernel and events[i] after
  * its i-th kernel (as many as `count` allows; the call's kernel order is listed in the library's
  * design notes).  The array must stay valid while the hook is set.  Process-global, not
  * thread-safe; the caller owns the events and reads them after synchronising the stream.

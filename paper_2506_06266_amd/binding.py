@@ -22,7 +22,9 @@ STATUS_NAMES = ["CART_OK", "CART_ERR_NULL", "CART_ERR_SHAPE", "CART_ERR_UNSUPPOR
 
 EXPORTS = ["cart_attn_fwd_workspace", "cart_attn_bwd_workspace", "cart_kl_workspace",
            "cart_decode_workspace", "cart_attn_fwd", "cart_attn_bwd", "cart_distill_kl_fwd_bwd",
-           "cart_decode", "cart_decode_composed_workspace", "cart_decode_composed", "cart_teacher_topk", "cart_trace_events",
+           "cart_decode", "cart_decode_composed_workspace", "cart_decode_composed", "cart_teacher_topk",
+           "cart_attn_varlen_fwd_workspace", "cart_attn_varlen_bwd_workspace", "cart_attn_varlen_fwd",
+           "cart_attn_varlen_bwd", "cart_trace_events",
            "cart_status_str", "cart_version"]
 
 
@@ -30,6 +32,12 @@ class AttnDesc(C.Structure):
     _fields_ = [("B", C.c_int32), ("S", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32),
                 ("D", C.c_int32), ("P", C.c_int32), ("dtype", C.c_int), ("softmax_scale", C.c_float),
                 ("n_frozen", C.c_int32), ("dz_accumulate", C.c_int32), ("impl", C.c_int)]
+
+
+class AttnVarlenDesc(C.Structure):
+    _fields_ = [("T", C.c_int32), ("B", C.c_int32), ("max_seqlen", C.c_int32), ("Hq", C.c_int32),
+                ("Hkv", C.c_int32), ("D", C.c_int32), ("P", C.c_int32), ("dtype", C.c_int),
+                ("softmax_scale", C.c_float), ("n_frozen", C.c_int32), ("dz_accumulate", C.c_int32)]
 
 
 class KlDesc(C.Structure):
@@ -79,13 +87,19 @@ def load() -> C.CDLL:
     lib = C.CDLL(LIB_PATH)
     vp, sz = C.c_void_p, C.c_size_t
     for name, desc in (("cart_attn_fwd_workspace", AttnDesc), ("cart_attn_bwd_workspace", AttnDesc),
-                       ("cart_kl_workspace", KlDesc), ("cart_decode_workspace", DecodeDesc)):
+                       ("cart_kl_workspace", KlDesc), ("cart_decode_workspace", DecodeDesc),
+                       ("cart_attn_varlen_fwd_workspace", AttnVarlenDesc),
+                       ("cart_attn_varlen_bwd_workspace", AttnVarlenDesc)):
         f = getattr(lib, name)
         f.restype, f.argtypes = sz, [C.POINTER(desc)]
     lib.cart_attn_fwd.restype = C.c_int
     lib.cart_attn_fwd.argtypes = [C.POINTER(AttnDesc)] + [vp] * 8 + [sz, vp]
     lib.cart_attn_bwd.restype = C.c_int
     lib.cart_attn_bwd.argtypes = [C.POINTER(AttnDesc)] + [vp] * 14 + [sz, vp]
+    lib.cart_attn_varlen_fwd.restype = C.c_int
+    lib.cart_attn_varlen_fwd.argtypes = [C.POINTER(AttnVarlenDesc)] + [vp] * 9 + [sz, vp]
+    lib.cart_attn_varlen_bwd.restype = C.c_int
+    lib.cart_attn_varlen_bwd.argtypes = [C.POINTER(AttnVarlenDesc)] + [vp] * 15 + [sz, vp]
     lib.cart_distill_kl_fwd_bwd.restype = C.c_int
     lib.cart_distill_kl_fwd_bwd.argtypes = [C.POINTER(KlDesc)] + [vp] * 7 + [sz, vp]
     lib.cart_decode.restype = C.c_int
@@ -191,6 +205,53 @@ def cart_attn_bwd(q, k_own, v_own, z_k, z_v, o, lse, d_o, *, scale: float = 0.0,
                            _ptr(d_z_k), _ptr(d_z_v), _ptr(ws), 0 if ws is None else ws.numel(),
                            _stream(stream))
     _check(st, "cart_attn_bwd")
+    return d_q, d_k_own, d_v_own, d_z_k, d_z_v
+
+
+def cart_attn_varlen_fwd(q, k_own, v_own, z_k, z_v, cu_seqlens, max_seqlen: int, *, scale: float = 0.0,
+                         o=None, lse=None, workspace=None, stream=None):
+    """Packed batch: q [T,Hq,D]; k_own, v_own [T,Hkv,D]; z_k, z_v [Hkv,P,D]; cu_seqlens [B+1] int32
+    (device) -> (o [T,Hq,D], lse [Hq,T])."""
+    lib = load()
+    T, Hq, D = q.shape
+    p = 0 if z_k is None else z_k.shape[1]
+    d = AttnVarlenDesc(T, cu_seqlens.numel() - 1, max_seqlen, Hq, k_own.shape[1], D, p, _dtype_code(q), scale, 0, 0)
+    o = torch.empty_like(q) if o is None else o
+    lse = torch.empty(Hq, T, dtype=torch.float32, device=q.device) if lse is None else lse
+    need = lib.cart_attn_varlen_fwd_workspace(C.byref(d))
+    ws = _workspace(need, workspace, q.device)
+    st = lib.cart_attn_varlen_fwd(C.byref(d), _ptr(q), _ptr(k_own), _ptr(v_own), _ptr(z_k), _ptr(z_v),
+                                  _ptr(cu_seqlens), _ptr(o), _ptr(lse), _ptr(ws),
+                                  0 if ws is None else ws.numel(), _stream(stream))
+    _check(st, "cart_attn_varlen_fwd")
+    return o, lse
+
+
+def cart_attn_varlen_bwd(q, k_own, v_own, z_k, z_v, cu_seqlens, max_seqlen: int, o, lse, d_o, *,
+                         scale: float = 0.0, n_frozen: int = 0, d_z_k=None, d_z_v=None,
+                         dz_accumulate: bool = False, d_q=None, d_k_own=None, d_v_own=None,
+                         workspace=None, stream=None):
+    """Returns (d_q, d_k_own, d_v_own [packed], d_z_k, d_z_v [Hkv,P,D] fp32)."""
+    lib = load()
+    T, Hq, D = q.shape
+    p = 0 if z_k is None else z_k.shape[1]
+    d = AttnVarlenDesc(T, cu_seqlens.numel() - 1, max_seqlen, Hq, k_own.shape[1], D, p, _dtype_code(q), scale,
+                       n_frozen, int(dz_accumulate))
+    d_q = torch.empty_like(q) if d_q is None else d_q
+    d_k_own = torch.empty_like(k_own) if d_k_own is None else d_k_own
+    d_v_own = torch.empty_like(v_own) if d_v_own is None else d_v_own
+    if p > 0 and d_z_k is None:
+        if dz_accumulate:
+            raise ValueError("dz_accumulate needs d_z_k / d_z_v")
+        d_z_k = torch.empty(z_k.shape, dtype=torch.float32, device=q.device)
+        d_z_v = torch.empty(z_v.shape, dtype=torch.float32, device=q.device)
+    need = lib.cart_attn_varlen_bwd_workspace(C.byref(d))
+    ws = _workspace(need, workspace, q.device)
+    st = lib.cart_attn_varlen_bwd(C.byref(d), _ptr(q), _ptr(k_own), _ptr(v_own), _ptr(z_k), _ptr(z_v),
+                                  _ptr(cu_seqlens), _ptr(o), _ptr(lse), _ptr(d_o), _ptr(d_q), _ptr(d_k_own),
+                                  _ptr(d_v_own), _ptr(d_z_k), _ptr(d_z_v), _ptr(ws),
+                                  0 if ws is None else ws.numel(), _stream(stream))
+    _check(st, "cart_attn_varlen_bwd")
     return d_q, d_k_own, d_v_own, d_z_k, d_z_v
 
 

@@ -38,6 +38,21 @@ inline bool use_mfma_bwd(const cart_attn_desc& d) {
 }
 inline float attn_scale(float s, int D) { return s > 0.f ? s : 1.0f / sqrtf(static_cast<float>(D)); }
 
+// the packed batch as the batched descriptor the kernels take: S = the longest sequence
+cart_status check_varlen(const cart_attn_varlen_desc* d, cart_attn_desc* a) {
+    if (!d) return CART_ERR_NULL;
+    if (d->T < 1 || d->B < 1 || d->max_seqlen < 1 || d->max_seqlen > d->T) return CART_ERR_SHAPE;
+    cart_attn_desc x;
+    x.B = d->B; x.S = d->max_seqlen; x.Hq = d->Hq; x.Hkv = d->Hkv; x.D = d->D; x.P = d->P;
+    x.dtype = d->dtype; x.softmax_scale = d->softmax_scale; x.n_frozen = d->n_frozen;
+    x.dz_accumulate = d->dz_accumulate; x.impl = CART_IMPL_MFMA;
+    cart_status s = check_attn(&x);
+    if (s != CART_OK) return s;
+    if (static_cast<long>(d->T) * d->Hq * static_cast<long>(d->D) > (1L << 40)) return CART_ERR_SHAPE;
+    *a = x;
+    return CART_OK;
+}
+
 cart_status check_kl(const cart_kl_desc* d) {
     if (!d) return CART_ERR_NULL;
     if (d->N < 1 || d->V < 1 || d->K < 1 || d->K > d->V) return CART_ERR_SHAPE;
@@ -82,6 +97,18 @@ size_t cart_attn_bwd_workspace(const cart_attn_desc* d) {
     if (check_attn(d) != CART_OK) return 0;
     size_t delta = round256(static_cast<size_t>(d->B) * d->Hq * d->S * sizeof(float));
     return delta + (use_mfma_bwd(*d) ? cart::attn_mfma_bwd_workspace(*d) : 0);
+}
+
+size_t cart_attn_varlen_fwd_workspace(const cart_attn_varlen_desc* d) {
+    cart_attn_desc a;
+    if (check_varlen(d, &a) != CART_OK) return 0;
+    return cart::attn_mfma_fwd_workspace(a);
+}
+
+size_t cart_attn_varlen_bwd_workspace(const cart_attn_varlen_desc* d) {
+    cart_attn_desc a;
+    if (check_varlen(d, &a) != CART_OK) return 0;
+    return round256(static_cast<size_t>(d->T) * d->Hq * sizeof(float)) + cart::attn_mfma_bwd_workspace(a, d->T);
 }
 
 size_t cart_kl_workspace(const cart_kl_desc* d) {
@@ -187,6 +214,47 @@ cart_status cart_attn_bwd(const cart_attn_desc* d, const void* q, const void* k_
                                              d_k_own, d_v_own, d_z_k, d_z_v, workspace, st)
                 : cart::launch_attn_bwd_vector(*d, scale, q, k_own, v_own, z_k, z_v, o, lse, d_o,
                                                d_q, d_k_own, d_v_own, d_z_k, d_z_v, workspace, st);
+    return e == 0 ? CART_OK : CART_ERR_LAUNCH;
+}
+
+cart_status cart_attn_varlen_fwd(const cart_attn_varlen_desc* d, const void* q, const void* k_own,
+                                 const void* v_own, const void* z_k, const void* z_v,
+                                 const int32_t* cu_seqlens, void* o, float* lse, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+    cart_attn_desc a;
+    cart_status s = check_varlen(d, &a);
+    if (s != CART_OK) return s;
+    REQUIRE(q); REQUIRE(k_own); REQUIRE(v_own); REQUIRE(cu_seqlens); REQUIRE(o); REQUIRE(lse);
+    if (d->P > 0) { REQUIRE(z_k); REQUIRE(z_v); }
+    ALIGNED(q); ALIGNED(k_own); ALIGNED(v_own); ALIGNED(z_k); ALIGNED(z_v); ALIGNED(o); ALIGNED(lse);
+    ALIGNED(workspace);
+    const size_t need = cart_attn_varlen_fwd_workspace(d);
+    if (!workspace || workspace_bytes < need) return CART_ERR_WORKSPACE;
+    int e = cart::launch_attn_fwd_mfma(a, attn_scale(d->softmax_scale, d->D), q, k_own, v_own, z_k, z_v, o, lse,
+                                       workspace, static_cast<hipStream_t>(stream), cu_seqlens, d->T);
+    return e == 0 ? CART_OK : CART_ERR_LAUNCH;
+}
+
+cart_status cart_attn_varlen_bwd(const cart_attn_varlen_desc* d, const void* q, const void* k_own,
+                                 const void* v_own, const void* z_k, const void* z_v,
+                                 const int32_t* cu_seqlens, const void* o, const float* lse,
+                                 const void* d_o, void* d_q, void* d_k_own, void* d_v_own,
+                                 float* d_z_k, float* d_z_v, void* workspace, size_t workspace_bytes,
+                                 void* stream) {
+    cart_attn_desc a;
+    cart_status s = check_varlen(d, &a);
+    if (s != CART_OK) return s;
+    REQUIRE(q); REQUIRE(k_own); REQUIRE(v_own); REQUIRE(cu_seqlens); REQUIRE(o); REQUIRE(lse); REQUIRE(d_o);
+    REQUIRE(d_q); REQUIRE(d_k_own); REQUIRE(d_v_own);
+    if (d->P > 0) { REQUIRE(z_k); REQUIRE(z_v); REQUIRE(d_z_k); REQUIRE(d_z_v); }
+    ALIGNED(q); ALIGNED(k_own); ALIGNED(v_own); ALIGNED(z_k); ALIGNED(z_v); ALIGNED(o); ALIGNED(lse);
+    ALIGNED(d_o); ALIGNED(d_q); ALIGNED(d_k_own); ALIGNED(d_v_own); ALIGNED(d_z_k); ALIGNED(d_z_v);
+    ALIGNED(workspace);
+    const size_t need = cart_attn_varlen_bwd_workspace(d);
+    if (!workspace || workspace_bytes < need) return CART_ERR_WORKSPACE;
+    int e = cart::launch_attn_bwd_mfma(a, attn_scale(d->softmax_scale, d->D), q, k_own, v_own, z_k, z_v, o, lse,
+                                       d_o, d_q, d_k_own, d_v_own, d_z_k, d_z_v, workspace,
+                                       static_cast<hipStream_t>(stream), cu_seqlens, d->T);
     return e == 0 ? CART_OK : CART_ERR_LAUNCH;
 }
 

@@ -29,6 +29,28 @@ __device__ __forceinline__ void static_for(F&& f) {
     static_for_impl(static_cast<F&&>(f), std::make_integer_sequence<int, N>{});
 }
 
+// Rows of sequence b, and where the per-row statistics (lse, delta) of its heads live: the value
+// of token i of head h is at stat_b + h * stat_h + i.
+//   batched layout (cu == nullptr): rows b*S .. b*S+S-1 of [B,S,...]; statistics [B,Hq,S]
+//   packed layout: rows cu[b] .. cu[b+1]-1 of [T,...];                statistics [Hq,T]
+struct SeqSpan { size_t t0; size_t stat_b; size_t stat_h; int len; };
+__device__ __forceinline__ SeqSpan seq_span(const int32_t* cu, int b, int T, int S, int Hq) {
+    SeqSpan sp;
+    if (cu) {
+        const int c0 = cu[b];
+        sp.t0 = static_cast<size_t>(c0);
+        sp.len = cu[b + 1] - c0;
+        sp.stat_b = sp.t0;
+        sp.stat_h = static_cast<size_t>(T);
+    } else {
+        sp.t0 = static_cast<size_t>(b) * S;
+        sp.len = S;
+        sp.stat_b = static_cast<size_t>(b) * Hq * S;
+        sp.stat_h = static_cast<size_t>(S);
+    }
+    return sp;
+}
+
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));

@@ -36,10 +36,12 @@ __global__ __launch_bounds__(256) void attn_bwd_prep_kernel(const bf16_t* __rest
                                                             const bf16_t* __restrict__ d_o,
                                                             const float* __restrict__ lse,
                                                             float* __restrict__ ndelta,
-                                                            float* __restrict__ nlse2, int B, int S,
-                                                            int Hq) {
+                                                            float* __restrict__ nlse2, long tokens,
+                                                            int S, int Hq, int packed) {
+    // rows of o / d_o are (token, head) pairs in both layouts; the statistics are [B,Hq,S]
+    // (batched, tokens = B S) or [Hq,tokens] (packed)
     const long row = static_cast<long>(blockIdx.x) * 16 + (threadIdx.x >> 4);
-    const long rows = static_cast<long>(B) * S * Hq;
+    const long rows = tokens * Hq;
     if (row >= rows) return;
     const int sub = threadIdx.x & 15;
     const u32x4 a = *reinterpret_cast<const u32x4*>(o + row * HD + sub * 8);
@@ -53,8 +55,10 @@ __global__ __launch_bounds__(256) void attn_bwd_prep_kernel(const bf16_t* __rest
 #pragma unroll
     for (int off = 8; off > 0; off >>= 1) s += __shfl_xor(s, off, 16);
     if (sub == 0) {
-        const int h = row % Hq, i = (row / Hq) % S, b = row / (static_cast<long>(Hq) * S);
-        const size_t st = (static_cast<size_t>(b) * Hq + h) * S + i;
+        const int h = row % Hq;
+        const long t = row / Hq;
+        const size_t st = packed ? static_cast<size_t>(h) * tokens + t
+                                 : (static_cast<size_t>(t / S) * Hq + h) * S + t % S;
         ndelta[st] = -s;
         nlse2[st] = -lse[st] * CART_LOG2E;
     }
@@ -107,14 +111,14 @@ struct DqSmem {
 __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
     const bf16_t* __restrict__ zk, const bf16_t* __restrict__ zv, const bf16_t* __restrict__ d_o,
-    const float* __restrict__ nlse2, const float* __restrict__ ndelta, bf16_t* __restrict__ dq, int B,
-    int S, int Hq, int Hkv, int P, float c, float scale) {
+    const float* __restrict__ nlse2, const float* __restrict__ ndelta, bf16_t* __restrict__ dq,
+    const int32_t* __restrict__ cu, int n_tok, int B, int Smax, int Hq, int Hkv, int P, float c, float scale) {
     constexpr int NBUF = DQ_NBUF;
     constexpr int BUF_B = 2 * BWD_TILE_B;
     constexpr int V_OFF = BWD_TILE_B;
     __shared__ DqSmem sm;
     const int G = Hq / Hkv;
-    const int nQt = (S + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
+    const int nQt = (Smax + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
     int id = blockIdx.x;
     const int hk = id % Hkv; id /= Hkv;
     const int g_ = id % G; id /= G;
@@ -124,6 +128,11 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
     const int lane = threadIdx.x & 63, lg = lane >> 5, lc = lane & 31;
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int q0 = qt * BWD_WG_ROWS, wrow0 = q0 + 64 * wv;
+    // packed layout: the grid covers the longest sequence; nothing to do past the end of this one
+    const SeqSpan sp = seq_span(cu, b, n_tok, Smax, Hq);
+    const int S = sp.len;
+    const size_t t0 = sp.t0;
+    if (q0 >= S) return;
 
     u32x4 qf[2][8], gf[2][8];     // B operands: column = query, k = head element
     float nl2[2], ndl[2];         // -lse2, -delta of the lane's queries
@@ -131,7 +140,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
     for (int cb = 0; cb < 2; ++cb) {
         int qi = wrow0 + 32 * cb + lc;
         qi = qi < S ? qi : S - 1;
-        const size_t row = (static_cast<size_t>(b) * S + qi) * Hq + h;
+        const size_t row = (t0 + qi) * Hq + h;
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
             const u32x4 w = *reinterpret_cast<const u32x4*>(q + row * HD + 8 * lg + 16 * t);
@@ -144,7 +153,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
 #endif
             gf[cb][t] = *reinterpret_cast<const u32x4*>(d_o + row * HD + 8 * lg + 16 * t);
         }
-        const size_t st = (static_cast<size_t>(b) * Hq + h) * S + qi;
+        const size_t st = sp.stat_b + h * sp.stat_h + qi;
         nl2[cb] = nlse2[st];
         ndl[cb] = ndelta[st];
     }
@@ -180,8 +189,8 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
     const char* zk_b = reinterpret_cast<const char*>(zk) + static_cast<size_t>(hk) * P * ROW_B;
     const char* zv_b = reinterpret_cast<const char*>(zv) + static_cast<size_t>(hk) * P * ROW_B;
     const uint32_t own_pitch = static_cast<uint32_t>(Hkv) * ROW_B;
-    const char* k_b = reinterpret_cast<const char*>(k) + (static_cast<size_t>(b) * S * Hkv + hk) * ROW_B;
-    const char* v_b = reinterpret_cast<const char*>(v) + (static_cast<size_t>(b) * S * Hkv + hk) * ROW_B;
+    const char* k_b = reinterpret_cast<const char*>(k) + (t0 * Hkv + hk) * ROW_B;
+    const char* v_b = reinterpret_cast<const char*>(v) + (t0 * Hkv + hk) * ROW_B;
     auto tile_pre = [&](int t) __attribute__((always_inline)) { return t < nPf || (rag && t == nMain); };
     auto tile_j0 = [&](int t) __attribute__((always_inline)) {
         return (t < nPf ? t : t < nMain ? t - nPf : (rag && t == nMain) ? nPf : t - nPf - rag) * BWD_TILE;
@@ -368,7 +377,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
     for (int cb = 0; cb < 2; ++cb) {
         const int qi = wrow0 + 32 * cb + lc;
         f32x16 col[4] = {acc[0][cb], acc[1][cb], acc[2][cb], acc[3][cb]};
-        store_rows_bf16(col, qi < S ? dq + ((static_cast<size_t>(b) * S + qi) * Hq + h) * HD : nullptr, lg, scale);
+        store_rows_bf16(col, qi < S ? dq + ((t0 + qi) * Hq + h) * HD : nullptr, lg, scale);
     }
 }
 
@@ -399,7 +408,8 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
     const bf16_t* __restrict__ zk, const bf16_t* __restrict__ zv, const bf16_t* __restrict__ d_o,
     const float* __restrict__ nlse2, const float* __restrict__ ndelta, bf16_t* __restrict__ out_own,
-    float* __restrict__ part, int B, int S, int Hq, int Hkv, int P, float c, float scale) {
+    float* __restrict__ part, const int32_t* __restrict__ cu, int n_tok, int B, int Smax, int Hq, int Hkv,
+    int P, float c, float scale) {
     // dV fetches every fragment a whole iteration ahead: a tile is read in two consecutive tile
     // iterations, three buffers.  dK fetches the transposed fragments of the previous sub-tile a
     // few groups ahead of their use, i.e. one tile iteration later: four buffers.
@@ -408,7 +418,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
     constexpr int G_OFF = BWD_TILE_B;         // dO tile inside a buffer
     __shared__ KsSmem<NBUF> sm;
     const int G = Hq / Hkv;
-    const int nPb = (P + BWD_WG_ROWS - 1) / BWD_WG_ROWS, nOb = (S + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
+    const int nPb = (P + BWD_WG_ROWS - 1) / BWD_WG_ROWS, nOb = (Smax + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
     const int nKb = nPb + nOb;
     // workgroup -> (sequence, key block, KV head): KV head fastest (one head per XCD with 8 KV
     // heads); the key blocks of one sequence run together and share its Q / dO stream in L2
@@ -418,10 +428,29 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
     const int b = id / nKb;
     const bool pre = kb < nPb;
     const int key0 = (pre ? kb : kb - nPb) * BWD_WG_ROWS;
+    const SeqSpan sp = seq_span(cu, b, n_tok, Smax, Hq);
+    const int S = sp.len;
+    const size_t t0 = sp.t0;
     const int nkeys = pre ? P : S;
     const int lane = threadIdx.x & 63, lg = lane >> 5, lc = lane & 31;
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wkey0 = key0 + 64 * wv;
+    // packed layout: the grid covers the longest sequence; an own-key block past the end of this
+    // one has nothing to do, and an empty sequence adds nothing to the prefix gradient
+    if (!pre && key0 >= S) return;
+    if (S == 0) {
+        f32x16 z[4];
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) z[db][r] = 0.f;
+#pragma unroll
+        for (int kc = 0; kc < 2; ++kc) {
+            const int key = wkey0 + 32 * kc + lc;
+            store_rows_f32(z, key < P ? part + ((static_cast<size_t>(b) * Hkv + hk) * P + key) * HD : nullptr, lg, 1.f);
+        }
+        return;
+    }
 
     // this wavefront's 64 keys as B operands: column = key, k = head element
     u32x4 kf[2][8], vf[2][8];
@@ -429,7 +458,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
     for (int kc = 0; kc < 2; ++kc) {
         const int key = min(wkey0 + 32 * kc + lc, nkeys - 1);
         const size_t row = pre ? static_cast<size_t>(hk) * P + key
-                               : (static_cast<size_t>(b) * S + key) * Hkv + hk;
+                               : (t0 + key) * Hkv + hk;
         const bf16_t* kp = (pre ? zk : k) + row * HD + 8 * lg;
         const bf16_t* vp = (pre ? zv : v) + row * HD + 8 * lg;
 #pragma unroll
@@ -492,12 +521,12 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
         const int h = hk * G + it_g;
         TileSrc ts;
         ts.i0 = qt * BWD_TILE;
-        const size_t base = (static_cast<size_t>(b) * S * Hq + h) * ROW_B + static_cast<size_t>(ts.i0) * q_pitch;
+        const size_t base = (t0 * Hq + h) * ROW_B + static_cast<size_t>(ts.i0) * q_pitch;
         ts.qb = q_c + base;
         ts.gb = g_c + base;
         ts.lim = S - 1 - ts.i0;
         // wavefronts 0 / 2 fetch the rows' -lse2, 1 / 3 their -delta (twice each: no branch)
-        ts.rb = reinterpret_cast<const char*>(((wv & 1) ? ndelta : nlse2) + (static_cast<size_t>(b) * Hq + h) * S + ts.i0);
+        ts.rb = reinterpret_cast<const char*>(((wv & 1) ? ndelta : nlse2) + sp.stat_b + h * sp.stat_h + ts.i0);
         ts.lds_q = lds_addr(sm.t[buf].q);
         ts.lds_g = lds_addr(sm.t[buf].g);
         ts.lds_r = lds_addr((wv & 1) ? sm.ndl[buf] : sm.nl2[buf]);
@@ -810,8 +839,8 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
         i0_cur = i0_nx;
         i0_nx = ts.i0;
     };
-    for (int T = 0; T < nMain; ++T) tile_iter(std::false_type{});
-    for (int T = nMain; T < nT; ++T) tile_iter(std::true_type{});
+    for (int ti = 0; ti < nMain; ++ti) tile_iter(std::false_type{});
+    for (int ti = nMain; ti < nT; ++ti) tile_iter(std::true_type{});
     {   // drain: the last sub-tile's contribution
         pin();
         if (IS_DK) {
@@ -836,7 +865,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
         if (pre)
             store_rows_f32(col, key < P ? part + ((static_cast<size_t>(b) * Hkv + hk) * P + key) * HD : nullptr, lg, mul);
         else
-            store_rows_bf16(col, key < S ? out_own + ((static_cast<size_t>(b) * S + key) * Hkv + hk) * HD : nullptr, lg, mul);
+            store_rows_bf16(col, key < S ? out_own + ((t0 + key) * Hkv + hk) * HD : nullptr, lg, mul);
     }
 }
 
@@ -861,9 +890,11 @@ bool attn_mfma_bwd_supported(const cart_attn_desc& d) { return d.dtype == CART_B
 
 static size_t r256(size_t n) { return (n + 255) & ~static_cast<size_t>(255); }
 
-// beyond the delta array: lse2 [B,Hq,S] and the two per-sequence dZ partial buffers [B,Hkv,P,128]
-size_t attn_mfma_bwd_workspace(const cart_attn_desc& d) {
-    const size_t rows = r256(static_cast<size_t>(d.B) * d.Hq * d.S * sizeof(float));
+// beyond the delta array: lse2 (one value per token and head) and the two per-sequence dZ partial
+// buffers [B,Hkv,P,128].  tokens = B S (batched layout) or the packed row count.
+size_t attn_mfma_bwd_workspace(const cart_attn_desc& d, long tokens) {
+    if (tokens < 0) tokens = static_cast<long>(d.B) * d.S;
+    const size_t rows = r256(static_cast<size_t>(tokens) * d.Hq * sizeof(float));
     const size_t part = r256(static_cast<size_t>(d.B) * d.Hkv * d.P * HD * sizeof(float));
     return rows + 2 * part;
 }
@@ -871,8 +902,9 @@ size_t attn_mfma_bwd_workspace(const cart_attn_desc& d) {
 int launch_attn_bwd_mfma(const cart_attn_desc& d, float scale, const void* q, const void* k,
                          const void* v, const void* zk, const void* zv, const void* o,
                          const float* lse, const void* d_o, void* dq, void* dk, void* dv,
-                         float* dzk, float* dzv, void* ws, hipStream_t st) {
-    const size_t rows_b = r256(static_cast<size_t>(d.B) * d.Hq * d.S * sizeof(float));
+                         float* dzk, float* dzv, void* ws, hipStream_t st, const int32_t* cu, int T) {
+    const long tokens = cu ? T : static_cast<long>(d.B) * d.S;
+    const size_t rows_b = r256(static_cast<size_t>(tokens) * d.Hq * sizeof(float));
     const size_t part_b = r256(static_cast<size_t>(d.B) * d.Hkv * d.P * HD * sizeof(float));
     char* w = static_cast<char*>(ws);
     float* delta = reinterpret_cast<float*>(w);
@@ -883,23 +915,23 @@ int launch_attn_bwd_mfma(const cart_attn_desc& d, float scale, const void* q, co
                  *V = static_cast<const bf16_t*>(v), *ZK = static_cast<const bf16_t*>(zk),
                  *ZV = static_cast<const bf16_t*>(zv), *DO = static_cast<const bf16_t*>(d_o);
     const float c = scale * CART_LOG2E;
-    const long rows = static_cast<long>(d.B) * d.S * d.Hq;
+    const long rows = tokens * d.Hq;
     trace_begin(st);   // kernel order: prep, dq, dk, dv, dz reduce (k, v)
     hipLaunchKernelGGL(attn_bwd_prep_kernel, dim3(static_cast<unsigned>((rows + 15) / 16)), dim3(256), 0, st,
-                       static_cast<const bf16_t*>(o), DO, lse, delta, lse2, d.B, d.S, d.Hq);
+                       static_cast<const bf16_t*>(o), DO, lse, delta, lse2, tokens, d.S, d.Hq, cu ? 1 : 0);
     trace_mark(st);
     const int nQt = (d.S + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
     hipLaunchKernelGGL(attn_bwd_dq_kernel, dim3(static_cast<unsigned>(static_cast<long>(nQt) * d.B * d.Hq)), dim3(256),
-                       0, st, Q, K, V, ZK, ZV, DO, lse2, delta, static_cast<bf16_t*>(dq), d.B, d.S, d.Hq,
-                       d.Hkv, d.P, c, scale);
+                       0, st, Q, K, V, ZK, ZV, DO, lse2, delta, static_cast<bf16_t*>(dq), cu, T, d.B, d.S,
+                       d.Hq, d.Hkv, d.P, c, scale);
     trace_mark(st);
     const int nKb = (d.P + BWD_WG_ROWS - 1) / BWD_WG_ROWS + (d.S + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
     const unsigned kgrid = static_cast<unsigned>(static_cast<long>(nKb) * d.B * d.Hkv);
     hipLaunchKernelGGL(attn_bwd_kstat_kernel<true>, dim3(kgrid), dim3(256), 0, st, Q, K, V, ZK, ZV, DO, lse2,
-                       delta, static_cast<bf16_t*>(dk), part_k, d.B, d.S, d.Hq, d.Hkv, d.P, c, scale);
+                       delta, static_cast<bf16_t*>(dk), part_k, cu, T, d.B, d.S, d.Hq, d.Hkv, d.P, c, scale);
     trace_mark(st);
     hipLaunchKernelGGL(attn_bwd_kstat_kernel<false>, dim3(kgrid), dim3(256), 0, st, Q, K, V, ZK, ZV, DO, lse2,
-                       delta, static_cast<bf16_t*>(dv), part_v, d.B, d.S, d.Hq, d.Hkv, d.P, c, scale);
+                       delta, static_cast<bf16_t*>(dv), part_v, cu, T, d.B, d.S, d.Hq, d.Hkv, d.P, c, scale);
     trace_mark(st);
     if (d.P > 0) {
         const long n4 = static_cast<long>(d.Hkv) * d.P * HD / 4;

@@ -45,12 +45,12 @@ struct FwdSmem {
 __global__ __launch_bounds__(256, 1) void attn_fwd_mfma_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
     const bf16_t* __restrict__ zk, const bf16_t* __restrict__ zv, bf16_t* __restrict__ o,
-    float* __restrict__ lse, int* __restrict__ flags, int B, int S, int Hq, int Hkv, int P,
-    float c /* scale*log2(e) */) {
+    float* __restrict__ lse, int* __restrict__ flags, const int32_t* __restrict__ cu, int n_tok, int B,
+    int Smax, int Hq, int Hkv, int P, float c /* scale*log2(e) */) {
     __shared__ FwdSmem sm;
     __shared__ int sm_bad;
     const int G = Hq / Hkv;
-    const int nQt = (S + FWD_BM - 1) / FWD_BM;
+    const int nQt = (Smax + FWD_BM - 1) / FWD_BM;
     // workgroup -> (query tile, sequence, head).  KV head is the fastest index so that, with 8
     // KV heads, blockIdx % 8 (the XCD a workgroup lands on) is the KV head and each XCD's L2 keeps
     // one head's prefix; the heaviest query tiles (longest causal part) are issued first.
@@ -63,6 +63,16 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_mfma_kernel(
     const int lane = threadIdx.x & 63, lg = lane >> 5, lc = lane & 31;
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform, in a scalar register
     const int q0 = qt * FWD_BM, wrow0 = q0 + 64 * wv;
+    // Rows of sequence b: [t0, t0 + S).  Batched layout: S rows each; packed layout (cu given):
+    // rows cu[b] .. cu[b+1]-1 of T, the grid is sized for the longest sequence and a workgroup
+    // whose query tile lies past the end of its sequence has nothing to do.
+    const SeqSpan sp = seq_span(cu, b, n_tok, Smax, Hq);
+    const int S = sp.len;
+    const size_t t0 = sp.t0;
+    if (q0 >= S) {
+        if (threadIdx.x == 0) flags[blockIdx.x] = 0;
+        return;
+    }
     if (threadIdx.x == 0) sm_bad = 0;
 
     // this wavefront's 64 queries as B-operand fragments: column = query, k = head element
@@ -73,7 +83,7 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_mfma_kernel(
     for (int cb = 0; cb < 2; ++cb) {
         int qi = wrow0 + 32 * cb + lc;
         qi = qi < S ? qi : S - 1;
-        const bf16_t* qp = q + ((static_cast<size_t>(b) * S + qi) * Hq + h) * HD + 8 * lg;
+        const bf16_t* qp = q + ((t0 + qi) * Hq + h) * HD + 8 * lg;
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
             const u32x4 w = *reinterpret_cast<const u32x4*>(qp + 16 * t);
@@ -121,8 +131,8 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_mfma_kernel(
     const char* zk_b = reinterpret_cast<const char*>(zk) + static_cast<size_t>(hk) * P * ROW_B;
     const char* zv_b = reinterpret_cast<const char*>(zv) + static_cast<size_t>(hk) * P * ROW_B;
     const uint32_t own_pitch = static_cast<uint32_t>(Hkv) * ROW_B;
-    const char* k_b = reinterpret_cast<const char*>(k) + (static_cast<size_t>(b) * S * Hkv + hk) * ROW_B;
-    const char* v_b = reinterpret_cast<const char*>(v) + (static_cast<size_t>(b) * S * Hkv + hk) * ROW_B;
+    const char* k_b = reinterpret_cast<const char*>(k) + (t0 * Hkv + hk) * ROW_B;
+    const char* v_b = reinterpret_cast<const char*>(v) + (t0 * Hkv + hk) * ROW_B;
     // tile t of that order: prefix or own, first key (all scalar)
     auto tile_pre = [&](int t) __attribute__((always_inline)) {
         return t < nPf || (rag && t == nMain);
@@ -377,7 +387,7 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_mfma_kernel(
         const float inv = 1.f / l_tot;
         float chk = 0.f;
         if (qi < S) {
-            bf16_t* op = o + ((static_cast<size_t>(b) * S + qi) * Hq + h) * HD;
+            bf16_t* op = o + ((t0 + qi) * Hq + h) * HD;
 #pragma unroll
             for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -389,7 +399,7 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_mfma_kernel(
                     *reinterpret_cast<u32x2*>(op + 32 * db + 8 * r4 + 4 * lg) = w;
                 }
             if (lg == 0)
-                lse[(static_cast<size_t>(b) * Hq + h) * S + qi] = (m_ref[cb] + fast_log2(l_tot)) * CART_LN2;
+                lse[sp.stat_b + h * sp.stat_h + qi] = (m_ref[cb] + fast_log2(l_tot)) * CART_LN2;
             // overflow of the fixed-reference softmax shows as a non-finite row sum or output
             bad |= !(l_tot < 3.0e38f) || !(fabsf(chk) < 3.0e38f);
         }
@@ -405,11 +415,11 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_mfma_kernel(
 __global__ __launch_bounds__(256) void attn_fwd_repair_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
     const bf16_t* __restrict__ zk, const bf16_t* __restrict__ zv, bf16_t* __restrict__ o,
-    float* __restrict__ lse, const int* __restrict__ flags, int B, int S, int Hq, int Hkv, int P,
-    float c) {
+    float* __restrict__ lse, const int* __restrict__ flags, const int32_t* __restrict__ cu, int n_tok,
+    int B, int Smax, int Hq, int Hkv, int P, float c) {
     if (flags[blockIdx.x] == 0) return;
     const int G = Hq / Hkv;
-    const int nQt = (S + FWD_BM - 1) / FWD_BM;
+    const int nQt = (Smax + FWD_BM - 1) / FWD_BM;
     int id = blockIdx.x;
     const int hk = id % Hkv; id /= Hkv;
     const int g_ = id % G; id /= G;
@@ -417,14 +427,17 @@ __global__ __launch_bounds__(256) void attn_fwd_repair_kernel(
     const int qt = nQt - 1 - id;
     const int h = hk * G + g_;
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const SeqSpan sp = seq_span(cu, b, n_tok, Smax, Hq);
+    const int S = sp.len;
+    const size_t t0 = sp.t0;
     for (int i = qt * FWD_BM + wv; i < min(S, (qt + 1) * FWD_BM); i += 4) {
-        const size_t row = (static_cast<size_t>(b) * S + i) * Hq + h;
+        const size_t row = (t0 + i) * Hq + h;
         const uint32_t qw = *reinterpret_cast<const uint32_t*>(q + row * HD + 2 * lane);
         const float q0 = __uint_as_float(qw << 16), q1 = __uint_as_float(qw & 0xffff0000u);
         float m = -3.0e38f, l = 0.f, a0 = 0.f, a1 = 0.f;
         for (int j = 0; j < P + i + 1; ++j) {
             const size_t kr = j < P ? static_cast<size_t>(hk) * P + j
-                                    : (static_cast<size_t>(b) * S + (j - P)) * Hkv + hk;
+                                    : (t0 + (j - P)) * Hkv + hk;
             const uint32_t kw = *reinterpret_cast<const uint32_t*>((j < P ? zk : k) + kr * HD + 2 * lane);
             const uint32_t vw = *reinterpret_cast<const uint32_t*>((j < P ? zv : v) + kr * HD + 2 * lane);
             const float sc = wave_sum(q0 * __uint_as_float(kw << 16) + q1 * __uint_as_float(kw & 0xffff0000u)) * c;
@@ -437,7 +450,7 @@ __global__ __launch_bounds__(256) void attn_fwd_repair_kernel(
         }
         const float inv = 1.f / l;
         *reinterpret_cast<uint32_t*>(o + row * HD + 2 * lane) = pack_bf16x2(a0 * inv, a1 * inv);
-        if (lane == 0) lse[(static_cast<size_t>(b) * Hq + h) * S + i] = (m + fast_log2(l)) * CART_LN2;
+        if (lane == 0) lse[sp.stat_b + h * sp.stat_h + i] = (m + fast_log2(l)) * CART_LN2;
     }
 }
 
@@ -452,9 +465,11 @@ size_t attn_mfma_fwd_workspace(const cart_attn_desc& d) {
     return (static_cast<size_t>(fwd_grid(d)) * sizeof(int) + 255) & ~static_cast<size_t>(255);
 }
 
+// cu == nullptr: batched layout [B,S,...].  Otherwise the packed layout: d.S is the longest
+// sequence, T the number of packed rows, cu (device) the B+1 row offsets.
 int launch_attn_fwd_mfma(const cart_attn_desc& d, float scale, const void* q, const void* k,
                          const void* v, const void* zk, const void* zv, void* o, float* lse,
-                         void* ws, hipStream_t st) {
+                         void* ws, hipStream_t st, const int32_t* cu, int T) {
     const unsigned grid = static_cast<unsigned>(fwd_grid(d));
     int* flags = static_cast<int*>(ws);
     const bf16_t *Q = static_cast<const bf16_t*>(q), *K = static_cast<const bf16_t*>(k),
@@ -462,10 +477,10 @@ int launch_attn_fwd_mfma(const cart_attn_desc& d, float scale, const void* q, co
                  *ZV = static_cast<const bf16_t*>(zv);
     trace_begin(st);   // kernel order: forward, repair
     hipLaunchKernelGGL(attn_fwd_mfma_kernel, dim3(grid), dim3(256), 0, st, Q, K, V, ZK, ZV,
-                       static_cast<bf16_t*>(o), lse, flags, d.B, d.S, d.Hq, d.Hkv, d.P, scale * CART_LOG2E);
+                       static_cast<bf16_t*>(o), lse, flags, cu, T, d.B, d.S, d.Hq, d.Hkv, d.P, scale * CART_LOG2E);
     trace_mark(st);
     hipLaunchKernelGGL(attn_fwd_repair_kernel, dim3(grid), dim3(256), 0, st, Q, K, V, ZK, ZV,
-                       static_cast<bf16_t*>(o), lse, flags, d.B, d.S, d.Hq, d.Hkv, d.P, scale * CART_LOG2E);
+                       static_cast<bf16_t*>(o), lse, flags, cu, T, d.B, d.S, d.Hq, d.Hkv, d.P, scale * CART_LOG2E);
     trace_mark(st);
     return static_cast<int>(hipGetLastError());
 }

@@ -98,14 +98,15 @@ int launch_decode_vector(const cart_decode_desc& d, float scale, const void* q, 
 bool attn_mfma_supported(const cart_attn_desc& d);       // forward
 bool attn_mfma_bwd_supported(const cart_attn_desc& d);
 size_t attn_mfma_fwd_workspace(const cart_attn_desc& d);
-size_t attn_mfma_bwd_workspace(const cart_attn_desc& d);   // beyond the delta array
+size_t attn_mfma_bwd_workspace(const cart_attn_desc& d, long tokens = -1);   // beyond the delta array
 int launch_attn_fwd_mfma(const cart_attn_desc& d, float scale, const void* q, const void* k,
                          const void* v, const void* zk, const void* zv, void* o, float* lse,
-                         void* ws, hipStream_t st);
+                         void* ws, hipStream_t st, const int32_t* cu = nullptr, int T = 0);
 int launch_attn_bwd_mfma(const cart_attn_desc& d, float scale, const void* q, const void* k,
                          const void* v, const void* zk, const void* zv, const void* o,
                          const float* lse, const void* d_o, void* dq, void* dk, void* dv,
-                         float* dzk, float* dzv, void* ws, hipStream_t st);
+                         float* dzk, float* dzv, void* ws, hipStream_t st, const int32_t* cu = nullptr,
+                         int T = 0);
 int launch_topk(const cart_topk_desc& d, const void* logits, int32_t* idx, float* logp, hipStream_t st);
 bool decode_composed_supported(const cart_decode_composed_desc& d);
 size_t decode_composed_workspace(const cart_decode_composed_desc& d, const cart_segment* shared);

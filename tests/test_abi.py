@@ -104,3 +104,28 @@ def test_kl_and_decode_argument_validation(lib):
     args = [0x1000] * 9
     args[5] = None                                       # cu_lens
     assert lib.cart_decode(C.byref(d), *args, 0, None) == 1
+
+
+def test_varlen_attention_argument_validation(lib):
+    mk = lambda **kw: binding.AttnVarlenDesc(**{**dict(T=500, B=3, max_seqlen=300, Hq=8, Hkv=2, D=128, P=64,
+                                                       dtype=binding.CART_BF16, softmax_scale=0.0, n_frozen=0,
+                                                       dz_accumulate=0), **kw})
+    d = mk()
+    need_f, need_b = lib.cart_attn_varlen_fwd_workspace(C.byref(d)), lib.cart_attn_varlen_bwd_workspace(C.byref(d))
+    # one flag per workgroup of the grid sized for max_seqlen; two row arrays and two partial buffers
+    assert need_f >= 2 * 3 * 8 * 4
+    assert need_b >= 2 * 500 * 8 * 4 + 2 * 3 * 2 * 64 * 128 * 4
+    fwd = lambda d, args, ws=0x1000, n=1 << 30: lib.cart_attn_varlen_fwd(C.byref(d), *args, ws, n, None)
+    ok = [0x1000] * 8
+    assert fwd(mk(max_seqlen=501), ok) == 2 and fwd(mk(max_seqlen=0), ok) == 2 and fwd(mk(T=0), ok) == 2
+    assert fwd(mk(dtype=binding.CART_F32), ok) == 3 and fwd(mk(D=64), ok) == 3
+    assert fwd(mk(Hkv=3), ok) == 2
+    a = list(ok); a[5] = None                            # cu_seqlens
+    assert fwd(d, a) == 1
+    assert fwd(d, ok, 0x1000, need_f - 1) == 4
+    a = list(ok); a[0] = 0x1004
+    assert fwd(d, a) == 6
+    assert lib.cart_attn_varlen_bwd(C.byref(d), *([0x1000] * 14), 0x1000, need_b - 1, None) == 4
+    a = [0x1000] * 14; a[12] = None                      # d_z_k with P > 0
+    assert lib.cart_attn_varlen_bwd(C.byref(d), *a, 0x1000, need_b, None) == 1
+    assert lib.cart_attn_varlen_bwd(C.byref(mk(n_frozen=65)), *([0x1000] * 14), 0x1000, need_b, None) == 2

@@ -497,3 +497,75 @@ def test_teacher_topk_feeds_the_loss():
     loss, dl = cb.cart_distill_kl_fwd_bwd(z, idx, lp, 1.0, mode=cb.KL_REST)
     torch.cuda.synchronize()
     assert abs(loss.item()) < 1e-4 and dl.float().abs().max().item() < 1e-4
+
+
+# ------------------------------------------------------------------------------------------------
+# packed variable-length attention
+# ------------------------------------------------------------------------------------------------
+def _varlen_case(seed, lens, Hq, Hkv, P):
+    D = 128
+    g = torch.Generator().manual_seed(seed)
+    rn = lambda *sz, std=1.0: (std * torch.randn(*sz, generator=g)).to(torch.bfloat16)
+    T = int(sum(lens))
+    cu = torch.tensor(np.concatenate([[0], np.cumsum(lens)]), dtype=torch.int32)
+    return dict(q=rn(T, Hq, D, std=0.5), k=rn(T, Hkv, D, std=0.5), v=rn(T, Hkv, D), zk=rn(Hkv, P, D, std=0.5),
+                zv=rn(Hkv, P, D), do=rn(T, Hq, D), cu=cu)
+
+
+VARLEN_CASES = [
+    ("ragged_mix", [100, 1, 300, 257, 64], 4, 2, 65, None),
+    ("with_empty_sequences", [130, 0, 70, 0], 4, 4, 40, None),
+    ("no_prefix", [33, 290], 2, 1, 0, None),
+    ("loose_max_seqlen", [65, 200, 7], 8, 2, 128, 272),
+    ("one_sequence", [513], 2, 2, 300, None),
+]
+
+
+@pytest.mark.parametrize("case", VARLEN_CASES, ids=lambda c: c[0])
+def test_attention_varlen_matches_oracle(case):
+    name, lens, Hq, Hkv, P, max_len = case
+    print("case", name, flush=True)
+    c = _varlen_case(77 + len(lens) + P, lens, Hq, Hkv, P)
+    f = to_np
+    cu_np = c["cu"].numpy()
+    o_ref, lse_ref = orc.attn_varlen_fwd(f(c["q"]), f(c["k"]), f(c["v"]), f(c["zk"]), f(c["zv"]), cu_np)
+    g_ref = orc.attn_varlen_bwd(f(c["q"]), f(c["k"]), f(c["v"]), f(c["zk"]), f(c["zv"]), f(c["do"]), cu_np)
+    d = dev(c)
+    z = (d["zk"], d["zv"]) if P > 0 else (None, None)
+    ml = max(lens) if max_len is None else max_len
+    o, lse = cb.cart_attn_varlen_fwd(d["q"], d["k"], d["v"], *z, d["cu"], ml)
+    grads = cb.cart_attn_varlen_bwd(d["q"], d["k"], d["v"], *z, d["cu"], ml, o, lse, d["do"])
+    torch.cuda.synchronize()
+    errs = {"o": rel_err(to_np(o), o_ref), "lse": rel_err(to_np(lse), lse_ref)}
+    for nm, x, r in list(zip(["d_q", "d_k_own", "d_v_own", "d_z_k", "d_z_v"], grads, g_ref))[: 3 if P == 0 else 5]:
+        errs[nm] = rel_err(to_np(x), r)
+    print(name, errs, flush=True)
+    for kk, e in errs.items():
+        assert e <= TOL["bf16"], (name, kk, e)
+
+
+def test_attention_varlen_equal_lengths_is_the_batched_call_bit_for_bit():
+    B, S, Hq, Hkv, P = 3, 300, 4, 2, 100
+    c = dev(_varlen_case(5, [S] * B, Hq, Hkv, P))
+    o, lse = cb.cart_attn_varlen_fwd(c["q"], c["k"], c["v"], c["zk"], c["zv"], c["cu"], S)
+    gv = cb.cart_attn_varlen_bwd(c["q"], c["k"], c["v"], c["zk"], c["zv"], c["cu"], S, o, lse, c["do"], n_frozen=3)
+    rs = lambda x: x.view(B, S, *x.shape[1:])
+    o2, lse2 = cb.cart_attn_fwd(rs(c["q"]), rs(c["k"]), rs(c["v"]), c["zk"], c["zv"], impl=cb.IMPL_MFMA)
+    gb = cb.cart_attn_bwd(rs(c["q"]), rs(c["k"]), rs(c["v"]), c["zk"], c["zv"], o2, lse2, rs(c["do"]), n_frozen=3,
+                          impl=cb.IMPL_MFMA)
+    torch.cuda.synchronize()
+    assert torch.equal(o.view(B, S, Hq, 128), o2)
+    assert torch.equal(lse.view(Hq, B, S).permute(1, 0, 2), lse2)
+    for a, b in zip(gv[:3], gb[:3]):
+        assert torch.equal(a.view(b.shape), b)
+    assert torch.equal(gv[3], gb[3]) and torch.equal(gv[4], gb[4])
+    assert (gv[3][:, :3] == 0).all()
+
+
+def test_attention_varlen_rejects_what_it_cannot_run():
+    c = dev(_varlen_case(6, [40, 50], 2, 1, 16))
+    with pytest.raises(cb.CartridgeError):      # fp32 has no packed kernels
+        cb.cart_attn_varlen_fwd(c["q"].float(), c["k"].float(), c["v"].float(), c["zk"].float(), c["zv"].float(),
+                                c["cu"], 50)
+    with pytest.raises(cb.CartridgeError):      # max_seqlen above the row count
+        cb.cart_attn_varlen_fwd(c["q"], c["k"], c["v"], c["zk"], c["zv"], c["cu"], 91)
