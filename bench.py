@@ -176,6 +176,26 @@ def main() -> int:
     pool_bytes = 2 * pool_k.numel() * 2 + 2 * own_tokens * dcfg.Hkv * dcfg.D * 2 + 2 * dcfg.B * dcfg.Hq * dcfg.D * 2
     del pool_k, pool_v
 
+    # one packed global batch of 64 ragged conversations (<= 1024 tokens) at the same layer shape
+    pcfg = synth.PACKED_CONFIGS["cfg3_packed"]
+    pk = synth.attn_packed_inputs(pcfg, dev)
+    plens = synth.packed_lengths(pcfg)
+    pmax = int(plens.max())
+    pk_o, pk_lse = cb.cart_attn_varlen_fwd(pk["q"], pk["k_own"], pk["v_own"], pk["z_k"], pk["z_v"],
+                                           pk["cu_seqlens"], pmax)
+    pk_g = cb.cart_attn_varlen_bwd(pk["q"], pk["k_own"], pk["v_own"], pk["z_k"], pk["z_v"], pk["cu_seqlens"], pmax,
+                                   pk_o, pk_lse, pk["d_o"])
+    def packed_step():
+        cb.cart_attn_varlen_fwd(pk["q"], pk["k_own"], pk["v_own"], pk["z_k"], pk["z_v"], pk["cu_seqlens"], pmax,
+                                o=pk_o, lse=pk_lse)
+        cb.cart_attn_varlen_bwd(pk["q"], pk["k_own"], pk["v_own"], pk["z_k"], pk["z_v"], pk["cu_seqlens"], pmax,
+                                pk_o, pk_lse, pk["d_o"], d_q=pk_g[0], d_k_own=pk_g[1], d_v_own=pk_g[2],
+                                d_z_k=pk_g[3], d_z_v=pk_g[4])
+    packed_ms = timed(packed_step)
+    packed_pairs = sum(int(n) * acfg.P + int(n) * (int(n) + 1) // 2 for n in plens.tolist()) * acfg.Hq
+    packed_tflops = packed_pairs * 14 * acfg.D / packed_ms / 1e9
+    del pk, pk_o, pk_lse, pk_g
+
     pairs = attn_pairs(acfg) * acfg.B * acfg.Hq
     fwd_flop, bwd_flop = pairs * 4 * acfg.D, pairs * 10 * acfg.D
     attn_ms = part_ms["attn_fwd"] + part_ms["attn_bwd"]
@@ -227,7 +247,9 @@ def main() -> int:
                       "teacher_topk_gbs": round(kcfg.N * kcfg.V * 2 / topk_ms / 1e6, 1),
                       "decode_4_shared_segments_ms": round(seg_ms, 4),
                       "decode_cartridge_per_request_ms": round(pool_ms, 4),
-                      "decode_cartridge_per_request_gbs": round(pool_bytes / pool_ms / 1e6, 1)},
+                      "decode_cartridge_per_request_gbs": round(pool_bytes / pool_ms / 1e6, 1),
+                      "attn_packed_64_conversations_fwd_bwd_ms": round(packed_ms, 4),
+                      "attn_packed_64_conversations_tflops": round(packed_tflops, 1)},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(a, acfg)

@@ -29,6 +29,7 @@ constexpr int BWD_TILE = 64;                      // rows per LDS tile
 constexpr int BWD_TILE_B = BWD_TILE * ROW_B;
 constexpr int BWD_NBUF = 3;
 constexpr int BWD_WG_ROWS = 256;                  // stationary rows per workgroup (4 x 64)
+constexpr int BWD_PACK_CHUNK = 2048;              // packed layout: tokens per prefix-gradient partial
 
 // ---- -delta = -rowsum(dO * O), -lse2 = -lse * log2(e) (negated: they enter the products as
 // init values); 16 lanes per row, 8 elements per lane ----
@@ -421,36 +422,46 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
     const int nPb = (P + BWD_WG_ROWS - 1) / BWD_WG_ROWS, nOb = (Smax + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
     const int nKb = nPb + nOb;
     // workgroup -> (sequence, key block, KV head): KV head fastest (one head per XCD with 8 KV
-    // heads); the key blocks of one sequence run together and share its Q / dO stream in L2
+    // heads); the key blocks of one sequence run together and share its Q / dO stream in L2.
+    // Packed layout: a prefix key sees every token whatever sequence it belongs to, so the prefix
+    // blocks stream the packed rows in chunks of BWD_PACK_CHUNK tokens (one partial dZ per chunk,
+    // not per sequence) and come first; the own-key blocks of the sequences follow.
     int id = blockIdx.x;
     const int hk = id % Hkv; id /= Hkv;
-    const int kb = id % nKb;
-    const int b = id / nKb;
+    int kb_, b_;
+    SeqSpan sp;
+    if (cu) {
+        const int nChunk = (n_tok + BWD_PACK_CHUNK - 1) / BWD_PACK_CHUNK;
+        if (id < nPb * nChunk) {
+            kb_ = id % nPb;
+            b_ = id / nPb;
+            sp.t0 = static_cast<size_t>(b_) * BWD_PACK_CHUNK;
+            sp.len = min(BWD_PACK_CHUNK, n_tok - b_ * BWD_PACK_CHUNK);
+            sp.stat_b = sp.t0;
+            sp.stat_h = static_cast<size_t>(n_tok);
+        } else {
+            id -= nPb * nChunk;
+            kb_ = nPb + id % nOb;
+            b_ = id / nOb;
+            sp = seq_span(cu, b_, n_tok, Smax, Hq);
+        }
+    } else {
+        kb_ = id % nKb;
+        b_ = id / nKb;
+        sp = seq_span(cu, b_, n_tok, Smax, Hq);
+    }
+    const int kb = kb_, b = b_;      // for a prefix block of the packed layout b is the chunk
     const bool pre = kb < nPb;
     const int key0 = (pre ? kb : kb - nPb) * BWD_WG_ROWS;
-    const SeqSpan sp = seq_span(cu, b, n_tok, Smax, Hq);
     const int S = sp.len;
     const size_t t0 = sp.t0;
     const int nkeys = pre ? P : S;
     const int lane = threadIdx.x & 63, lg = lane >> 5, lc = lane & 31;
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wkey0 = key0 + 64 * wv;
-    // packed layout: the grid covers the longest sequence; an own-key block past the end of this
-    // one has nothing to do, and an empty sequence adds nothing to the prefix gradient
+    // packed layout: the grid covers the longest sequence; an own-key block past the end of its
+    // sequence has nothing to do
     if (!pre && key0 >= S) return;
-    if (S == 0) {
-        f32x16 z[4];
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) z[db][r] = 0.f;
-#pragma unroll
-        for (int kc = 0; kc < 2; ++kc) {
-            const int key = wkey0 + 32 * kc + lc;
-            store_rows_f32(z, key < P ? part + ((static_cast<size_t>(b) * Hkv + hk) * P + key) * HD : nullptr, lg, 1.f);
-        }
-        return;
-    }
 
     // this wavefront's 64 keys as B operands: column = key, k = head element
     u32x4 kf[2][8], vf[2][8];
@@ -893,9 +904,10 @@ static size_t r256(size_t n) { return (n + 255) & ~static_cast<size_t>(255); }
 // beyond the delta array: lse2 (one value per token and head) and the two per-sequence dZ partial
 // buffers [B,Hkv,P,128].  tokens = B S (batched layout) or the packed row count.
 size_t attn_mfma_bwd_workspace(const cart_attn_desc& d, long tokens) {
+    const long n_part = tokens < 0 ? d.B : (tokens + BWD_PACK_CHUNK - 1) / BWD_PACK_CHUNK;
     if (tokens < 0) tokens = static_cast<long>(d.B) * d.S;
     const size_t rows = r256(static_cast<size_t>(tokens) * d.Hq * sizeof(float));
-    const size_t part = r256(static_cast<size_t>(d.B) * d.Hkv * d.P * HD * sizeof(float));
+    const size_t part = r256(static_cast<size_t>(n_part) * d.Hkv * d.P * HD * sizeof(float));
     return rows + 2 * part;
 }
 
@@ -905,7 +917,8 @@ int launch_attn_bwd_mfma(const cart_attn_desc& d, float scale, const void* q, co
                          float* dzk, float* dzv, void* ws, hipStream_t st, const int32_t* cu, int T) {
     const long tokens = cu ? T : static_cast<long>(d.B) * d.S;
     const size_t rows_b = r256(static_cast<size_t>(tokens) * d.Hq * sizeof(float));
-    const size_t part_b = r256(static_cast<size_t>(d.B) * d.Hkv * d.P * HD * sizeof(float));
+    const int n_part = cu ? static_cast<int>((tokens + BWD_PACK_CHUNK - 1) / BWD_PACK_CHUNK) : d.B;
+    const size_t part_b = r256(static_cast<size_t>(n_part) * d.Hkv * d.P * HD * sizeof(float));
     char* w = static_cast<char*>(ws);
     float* delta = reinterpret_cast<float*>(w);
     float* lse2 = reinterpret_cast<float*>(w + rows_b);
@@ -925,8 +938,8 @@ int launch_attn_bwd_mfma(const cart_attn_desc& d, float scale, const void* q, co
                        0, st, Q, K, V, ZK, ZV, DO, lse2, delta, static_cast<bf16_t*>(dq), cu, T, d.B, d.S,
                        d.Hq, d.Hkv, d.P, c, scale);
     trace_mark(st);
-    const int nKb = (d.P + BWD_WG_ROWS - 1) / BWD_WG_ROWS + (d.S + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
-    const unsigned kgrid = static_cast<unsigned>(static_cast<long>(nKb) * d.B * d.Hkv);
+    const long nPb = (d.P + BWD_WG_ROWS - 1) / BWD_WG_ROWS, nOb = (d.S + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
+    const unsigned kgrid = static_cast<unsigned>((nPb * n_part + nOb * d.B) * d.Hkv);
     hipLaunchKernelGGL(attn_bwd_kstat_kernel<true>, dim3(kgrid), dim3(256), 0, st, Q, K, V, ZK, ZV, DO, lse2,
                        delta, static_cast<bf16_t*>(dk), part_k, cu, T, d.B, d.S, d.Hq, d.Hkv, d.P, c, scale);
     trace_mark(st);
@@ -936,8 +949,8 @@ int launch_attn_bwd_mfma(const cart_attn_desc& d, float scale, const void* q, co
     if (d.P > 0) {
         const long n4 = static_cast<long>(d.Hkv) * d.P * HD / 4;
         const unsigned rg = static_cast<unsigned>((n4 + 255) / 256);
-        hipLaunchKernelGGL(dz_reduce_kernel, dim3(rg), dim3(256), 0, st, part_k, dzk, d.B, n4, d.P, d.n_frozen, d.dz_accumulate);
-        hipLaunchKernelGGL(dz_reduce_kernel, dim3(rg), dim3(256), 0, st, part_v, dzv, d.B, n4, d.P, d.n_frozen, d.dz_accumulate);
+        hipLaunchKernelGGL(dz_reduce_kernel, dim3(rg), dim3(256), 0, st, part_k, dzk, n_part, n4, d.P, d.n_frozen, d.dz_accumulate);
+        hipLaunchKernelGGL(dz_reduce_kernel, dim3(rg), dim3(256), 0, st, part_v, dzv, n_part, n4, d.P, d.n_frozen, d.dz_accumulate);
         trace_mark(st);
     }
     return static_cast<int>(hipGetLastError());

@@ -147,6 +147,54 @@ def attn_inputs(cfg: AttnConfig, device="cpu") -> Dict[str, torch.Tensor]:
     }
 
 
+@dataclass(frozen=True)
+class PackedConfig:
+    """A packed batch of conversations of different lengths at the layer shape of `base`
+    (whose B and S are not used): n_seq lengths drawn uniformly from [min_len, max_len]."""
+    name: str
+    seed: int
+    base: str
+    n_seq: int
+    min_len: int
+    max_len: int
+
+
+PACKED_CONFIGS: Dict[str, PackedConfig] = {
+    # one global batch of the paper's training runs: 64 conversations of at most 1024 tokens,
+    # Llama-8B layer shape, p = 4096
+    "cfg3_packed": PackedConfig("cfg3_packed", 3101, "cfg3", 64, 64, 1024),
+    "ragged_packed": PackedConfig("ragged_packed", 6102, "ragged", 7, 1, 300),
+}
+
+
+def packed_lengths(cfg: PackedConfig) -> torch.Tensor:
+    """The n_seq sequence lengths (int64, host)."""
+    g = _gen(cfg.seed, "cpu")
+    return torch.randint(cfg.min_len, cfg.max_len + 1, (cfg.n_seq,), generator=g)
+
+
+def attn_packed_inputs(cfg: PackedConfig, device="cpu") -> Dict[str, torch.Tensor]:
+    """Q [T,Hq,D], K_own/V_own [T,Hkv,D], Z_k/Z_v [Hkv,P,D], dO [T,Hq,D], cu_seqlens [n_seq+1]
+    int32 (on `device`), T = the sum of packed_lengths(cfg)."""
+    a = ATTN_CONFIGS[cfg.base]
+    lens = packed_lengths(cfg)
+    T = int(lens.sum())
+    g = _gen(cfg.seed + 1, device)
+    dt = torch_dtype(a.dtype)
+    qk_std = a.q_std if a.q_std is not None else a.qkv_std
+    cu = torch.zeros(cfg.n_seq + 1, dtype=torch.int32)
+    cu[1:] = torch.cumsum(lens, 0).to(torch.int32)
+    return {
+        "q": _normal((T, a.Hq, a.D), qk_std, dt, g, device),
+        "k_own": _normal((T, a.Hkv, a.D), qk_std, dt, g, device),
+        "v_own": _normal((T, a.Hkv, a.D), a.qkv_std, dt, g, device),
+        "z_k": _normal((a.Hkv, a.P, a.D), a.z_std, dt, g, device),
+        "z_v": _normal((a.Hkv, a.P, a.D), a.z_std, dt, g, device),
+        "d_o": _normal((T, a.Hq, a.D), a.do_std, dt, g, device),
+        "cu_seqlens": cu.to(device),
+    }
+
+
 def _distinct_indices(n: int, v: int, k: int, gen: torch.Generator, device) -> torch.Tensor:
     """[n,k] int32, each row k distinct values uniform in [0,v): rows with a repeat are redrawn."""
     idx = torch.randint(0, v, (n, k), generator=gen, device=device, dtype=torch.int64)

@@ -114,7 +114,7 @@ def test_varlen_attention_argument_validation(lib):
     need_f, need_b = lib.cart_attn_varlen_fwd_workspace(C.byref(d)), lib.cart_attn_varlen_bwd_workspace(C.byref(d))
     # one flag per workgroup of the grid sized for max_seqlen; two row arrays and two partial buffers
     assert need_f >= 2 * 3 * 8 * 4
-    assert need_b >= 2 * 500 * 8 * 4 + 2 * 3 * 2 * 64 * 128 * 4
+    assert need_b >= 2 * 500 * 8 * 4 + 2 * 1 * 2 * 64 * 128 * 4
     fwd = lambda d, args, ws=0x1000, n=1 << 30: lib.cart_attn_varlen_fwd(C.byref(d), *args, ws, n, None)
     ok = [0x1000] * 8
     assert fwd(mk(max_seqlen=501), ok) == 2 and fwd(mk(max_seqlen=0), ok) == 2 and fwd(mk(T=0), ok) == 2

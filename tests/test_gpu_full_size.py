@@ -142,3 +142,39 @@ def test_decode_composed_full_size_sampled_requests():
     print("cfg5 composed worst", worst, flush=True)
     assert worst <= TOL
     assert torch.isfinite(o.float()).all() and torch.isfinite(lse).all()
+
+
+def test_attention_packed_full_shape_one_kv_group():
+    """One global batch of 64 ragged conversations at the Llama-8B layer shape: the oracle redoes
+    one whole KV group (every sequence), which fixes every output of that group, dZ included."""
+    cfg = synth.PACKED_CONFIGS["cfg3_packed"]
+    a = synth.ATTN_CONFIGS[cfg.base]
+    hk = 6
+    print("case", cfg.name, "kv head", hk, flush=True)
+    g = synth.attn_packed_inputs(cfg, DEV)
+    ml = int(synth.packed_lengths(cfg).max())
+    args = (g["q"], g["k_own"], g["v_own"], g["z_k"], g["z_v"], g["cu_seqlens"], ml)
+    o, lse = cb.cart_attn_varlen_fwd(*args)
+    dq, dk, dv, dzk, dzv = cb.cart_attn_varlen_bwd(*args, o, lse, g["d_o"])
+    torch.cuda.synchronize()
+    G = a.Hq // a.Hkv
+    hs = slice(hk * G, (hk + 1) * G)
+    cu = g["cu_seqlens"].cpu().numpy()
+    q, do = f64(g["q"][:, hs]), f64(g["d_o"][:, hs])
+    k, v = f64(g["k_own"][:, hk:hk + 1]), f64(g["v_own"][:, hk:hk + 1])
+    zk, zv = f64(g["z_k"][hk:hk + 1]), f64(g["z_v"][hk:hk + 1])
+    o_ref, lse_ref = orc.attn_varlen_fwd(q, k, v, zk, zv, cu)
+    r = orc.attn_varlen_bwd(q, k, v, zk, zv, do, cu)
+    errs = {
+        "o": rel_err(f64(o[:, hs]), o_ref), "lse": rel_err(f64(lse[hs]), lse_ref),
+        "dq": rel_err(f64(dq[:, hs]), r[0]), "dk": rel_err(f64(dk[:, hk:hk + 1]), r[1]),
+        "dv": rel_err(f64(dv[:, hk:hk + 1]), r[2]), "dzk": rel_err(f64(dzk[hk:hk + 1]), r[3]),
+        "dzv": rel_err(f64(dzv[hk:hk + 1]), r[4]),
+    }
+    print(cfg.name, errs, flush=True)
+    for kk, e in errs.items():
+        assert e <= TOL, (cfg.name, kk, e)
+    again = cb.cart_attn_varlen_bwd(*args, o, lse, g["d_o"])
+    torch.cuda.synchronize()
+    for x, y in zip((dq, dk, dv, dzk, dzv), again):
+        assert torch.equal(x, y)

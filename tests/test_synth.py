@@ -41,3 +41,17 @@ def test_decode_inputs_ragged_lengths():
     assert t["k_own"].shape == (int(cu[-1]), cfg.Hkv, cfg.D)
     assert t["k_own"].dtype == torch.bfloat16
     assert abs(t["k_own"].float().std().item() - 1 / math.sqrt(128)) < 0.01
+
+
+def test_packed_inputs_lengths_and_offsets():
+    cfg = synth.PACKED_CONFIGS["ragged_packed"]
+    lens = synth.packed_lengths(cfg)
+    assert lens.numel() == cfg.n_seq and lens.min() >= cfg.min_len and lens.max() <= cfg.max_len
+    t = synth.attn_packed_inputs(cfg)
+    cu = t["cu_seqlens"]
+    assert cu.dtype == torch.int32 and cu[0] == 0 and torch.equal((cu[1:] - cu[:-1]).long(), lens)
+    T = int(lens.sum())
+    assert t["q"].shape == (T, 8, 128) and t["k_own"].shape == (T, 2, 128) and t["z_k"].shape == (2, 333, 128)
+    assert torch.equal(t["q"], synth.attn_packed_inputs(cfg)["q"])
+    big = synth.packed_lengths(synth.PACKED_CONFIGS["cfg3_packed"])
+    assert big.numel() == 64 and big.max() <= 1024 and 30000 < int(big.sum()) < 40000
