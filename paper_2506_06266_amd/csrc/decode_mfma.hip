@@ -3,15 +3,17 @@
 // KV], all visible.
 //
 // The cartridge is shared by every request, so its part is a real GEMM: the B*G query rows
-// that read one KV head (G = Hq/Hkv) are stacked and run against the prefix exactly like the
-// training forward kernel, split along the prefix to fill the chip (decode_prefix_kernel).
-// The ragged own-KV part is bandwidth-bound: one wavefront per (request, KV head, chunk of
-// keys) streams its chunk through a private LDS slot with the G query rows padded into one
-// 32-column MFMA block (decode_own_kernel).  Every split writes a normalised partial (O, lse);
+// that read one KV head (G = Hq/Hkv) are stacked and run against the prefix, split along the
+// prefix into about half as many workgroups as there are CUs (prefix role).  The ragged own-KV
+// part is bandwidth-bound: one wavefront per (request, KV head, chunk of keys) streams its chunk
+// through a private LDS slot with the G query rows padded into one 32-column MFMA block (own
+// role).  Both roles are workgroups of one launch (decode_fused_kernel), sized so that two share
+// a CU: the matrix-core work on the L2-resident cartridge overlaps the HBM streaming of the own
+// caches instead of preceding it.  Every split writes a normalised partial (O, lse);
 // decode_merge_kernel combines them by their log-sum-exps.
 //
 // Composition (Sec. 5.4: cartridges trained apart are concatenated without retraining) and the
-// per-request cartridges of App. B's serving protocol use the same three kernels: the shared
+// per-request cartridges of App. B's serving protocol use the same two kernels: the shared
 // prefix is a list of segments, each split and run like a single cartridge (a segment is never
 // copied next to another), and a request's private cartridge is streamed like its own KV.
 #include "attn_mfma.h"
@@ -19,13 +21,20 @@
 namespace cart {
 using namespace mfma;
 
-constexpr int DEC_BM = 256;            // stacked query rows per prefix workgroup
-constexpr int DEC_BN = 64;             // prefix keys per LDS tile
-constexpr int DEC_NBUF = 3;
+constexpr int DEC_BM = 128;            // stacked query rows per prefix workgroup (4 x 32)
+constexpr int DEC_BN = 32;             // prefix keys per LDS tile
+constexpr int DEC_NBUF = 4;
+// Prefix workgroups aimed at: half the CUs.  Measured on the serving shape (128 requests, 8192
+// shared slots, own caches U[1,1024]): 64 -> 131 us, 128 -> 84 us, 192 -> 90 us, 256 -> 94 us,
+// 512 -> 118 us for the whole call.
+constexpr int DEC_PREFIX_WGS = 128;
 constexpr int DEC_TILE_B = DEC_BN * ROW_B;
 constexpr int DEC_SUB = 32;            // own keys per wavefront step
 constexpr int DEC_SUB_B = DEC_SUB * ROW_B;
 
+#ifndef DEC_OWN_CHUNK
+#define DEC_OWN_CHUNK 256              // most keys per own / private-cartridge chunk of short caches
+#endif
 constexpr int DEC_MAX_SEG = CART_MAX_SEGMENTS;
 
 // The shared prefix as a list of segments (one for a single cartridge), by value in the kernel
@@ -54,7 +63,7 @@ static DecodePlan make_plan(int B, int Hq, int Hkv, int max_own_len, const int* 
     p.n_rb = (rows + DEC_BM - 1) / DEC_BM;
     int total_tiles = 0;
     for (int s = 0; s < n_seg; ++s) total_tiles += (seg_p[s] + DEC_BN - 1) / DEC_BN;
-    int want = (256 + Hkv * p.n_rb - 1) / (Hkv * p.n_rb);           // parts to reach ~256 workgroups
+    int want = (DEC_PREFIX_WGS + Hkv * p.n_rb - 1) / (Hkv * p.n_rb);   // parts to reach that many workgroups
     want = want < 1 ? 1 : (want > total_tiles ? total_tiles : want);
     const int tps = total_tiles ? (total_tiles + want - 1) / want : 0;
     p.tab.n_seg = 0;
@@ -72,7 +81,7 @@ static DecodePlan make_plan(int B, int Hq, int Hkv, int max_own_len, const int* 
         p.tab.blk0[k + 1] = p.tab.blk0[k] + Hkv * p.n_rb * p.tab.n_ps[k];
         p.tab.zk[k] = p.tab.zv[k] = nullptr;                        // filled by the launcher
     }
-    p.chunk = (max_own_len > 4096 || pool_p > 4096) ? 1024 : 256;
+    p.chunk = (max_own_len > 4096 || pool_p > 4096) ? 1024 : DEC_OWN_CHUNK;
     p.n_cc = (pool_p + p.chunk - 1) / p.chunk;
     p.n_oc = (max_own_len + p.chunk - 1) / p.chunk;
     const size_t slots = static_cast<size_t>(p.n_ps + p.n_cc + p.n_oc) * B * Hq;
@@ -81,30 +90,26 @@ static DecodePlan make_plan(int B, int Hq, int Hkv, int max_own_len, const int* 
     return p;
 }
 
-struct DecSmem {
-    char k[DEC_NBUF][DEC_TILE_B];
-    char v[DEC_NBUF][DEC_TILE_B];
-};
-
-// acc *= alpha in place in an accumulation register (see the forward kernel)
-__device__ __forceinline__ void dec_acc_scale(float& x, float alpha) {
-    float tmp;
-    asm volatile(
-        "s_nop 15\n\tv_accvgpr_read_b32 %1, %0\n\ts_nop 1\n\tv_mul_f32 %1, %1, %2\n\ts_nop 1\n\t"
-        "v_accvgpr_write_b32 %0, %1\n\ts_nop 3"
-        : "+a"(x), "=&v"(tmp)
-        : "v"(alpha));
+// Own rows of a request are split evenly over the n_oc chunk slots (in steps of 32 keys), so that
+// every request keeps all its slots busy whatever its length: keys per chunk of a request.
+__host__ __device__ __forceinline__ int own_chunk_keys(int len, int n_oc) {
+    const int ck = ((len + n_oc - 1) / n_oc + DEC_SUB - 1) & ~(DEC_SUB - 1);
+    return ck < DEC_SUB ? DEC_SUB : ck;
 }
 
-// part_o [slot][B][Hq][128] fp32 (normalised), part_l [slot][B][Hq] (natural-log lse)
-__global__ __launch_bounds__(256, 1) void decode_prefix_kernel(
-    const bf16_t* __restrict__ q, const PrefixTable tab, float* __restrict__ part_o,
-    float* __restrict__ part_l, int B, int Hq, int Hkv, float c, int n_rb) {
-    __shared__ DecSmem sm;
+// Prefix role of the fused kernel: 128 stacked query rows (32 per wavefront) against one split of
+// one segment, 32 keys per LDS tile, four tiles in rotation (tile u+1 feeds the next scores while
+// tile u feeds O, tiles u+2 and u+3 are on their way).  Small on purpose -- at most 256 registers
+// per lane and 64 KB of LDS -- so that two workgroups share a CU and the bandwidth-bound own-KV
+// role runs beside it.  part_o [slot][B][Hq][128] fp32 (normalised), part_l [slot][B][Hq]
+// (natural-log lse).
+__device__ __forceinline__ void decode_prefix_role(char* sm, const bf16_t* __restrict__ q, const PrefixTable& tab,
+                                                   float* __restrict__ part_o, float* __restrict__ part_l, int B,
+                                                   int Hq, int Hkv, float c, int n_rb, int blk) {
     const int G = Hq / Hkv;
     int seg = 0;
-    while (seg + 1 < tab.n_seg && static_cast<int>(blockIdx.x) >= tab.blk0[seg + 1]) ++seg;
-    int id = blockIdx.x - tab.blk0[seg];
+    while (seg + 1 < tab.n_seg && blk >= tab.blk0[seg + 1]) ++seg;
+    int id = blk - tab.blk0[seg];
     const int hk = id % Hkv; id /= Hkv;
     const int rb = id % n_rb;
     const int sp = id / n_rb;
@@ -115,174 +120,138 @@ __global__ __launch_bounds__(256, 1) void decode_prefix_kernel(
     const int lane = threadIdx.x & 63, lg = lane >> 5, lc = lane & 31;
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int rows = B * G;
-    const int wrow0 = rb * DEC_BM + 64 * wv;
+    const int rho = rb * DEC_BM + 32 * wv + lc;
 
-    bf16x8 qf[2][8];
+    bf16x8 qf[8];
+    {
+        const int rc = min(rho, rows - 1);
+        const bf16_t* qp = q + (static_cast<size_t>(rc / G) * Hq + hk * G + rc % G) * HD + 8 * lg;
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb) {
-        const int rho = min(wrow0 + 32 * cb + lc, rows - 1);
-        const bf16_t* qp = q + (static_cast<size_t>(rho / G) * Hq + hk * G + rho % G) * HD + 8 * lg;
-#pragma unroll
-        for (int t = 0; t < 8; ++t) qf[cb][t] = *reinterpret_cast<const bf16x8*>(qp + 16 * t);
+        for (int t = 0; t < 8; ++t) qf[t] = *reinterpret_cast<const bf16x8*>(qp + 16 * t);
     }
     const int nPt = (P + DEC_BN - 1) / DEC_BN;
     const int t_lo = sp * tiles_per_split;
     const int nT = min(tiles_per_split, nPt - t_lo);
     const char* zk_b = reinterpret_cast<const char*>(zk) + static_cast<size_t>(hk) * P * ROW_B;
     const char* zv_b = reinterpret_cast<const char*>(zv) + static_cast<size_t>(hk) * P * ROW_B;
-    auto issue = [&](int t, int buf) __attribute__((always_inline)) {
+    char* smk = sm;
+    char* smv = sm + DEC_NBUF * DEC_TILE_B;
+    auto issue = [&](int t, int buf) __attribute__((always_inline)) {   // 2 + 2 loads per wavefront
         const int j0 = (t_lo + t) * DEC_BN;
-        tile_load_async<DEC_BN>(sm.k[buf], zk_b, j0, P - 1, ROW_B);
-        tile_load_async<DEC_BN>(sm.v[buf], zv_b, j0, P - 1, ROW_B);
+        tile_load_async<DEC_BN>(smk + buf * DEC_TILE_B, zk_b, j0, P - 1, ROW_B);
+        tile_load_async<DEC_BN>(smv + buf * DEC_TILE_B, zv_b, j0, P - 1, ROW_B);
     };
 
-    f32x16 acc[4][2];
+    f32x16 acc[4];
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
-        for (int cb = 0; cb < 2; ++cb)
+        for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
+    float m_run = NEG_BIG, l_run = 0.f;
+    f32x16 s;
+    auto scores = [&](const char* kt) __attribute__((always_inline)) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[db][cb][r] = 0.f;
-    float m_run[2] = {NEG_BIG, NEG_BIG}, l_run[2] = {0.f, 0.f};
-    f32x16 s[2];
-    auto scores = [&](const char* kt, int kr0) __attribute__((always_inline)) {
+        for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
-        for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s[cb][r] = 0.f;
-#pragma unroll
-        for (int t8 = 0; t8 < 8; ++t8) {
-            bf16x8 a = lds_frag_n(kt, kr0 + lc, 16 * t8 + 8 * lg);
-            s[0] = mma(a, qf[0][t8], s[0]);
-            s[1] = mma(a, qf[1][t8], s[1]);
-        }
+        for (int t8 = 0; t8 < 8; ++t8) s = mma(lds_frag_n(kt, lc, 16 * t8 + 8 * lg), qf[t8], s);
     };
-    auto prepare = [&](int t, int hb, bool live) __attribute__((always_inline)) {
-        const int j0 = (t_lo + t) * DEC_BN + 32 * hb;
-        if (live && j0 + 32 > P) {
+    // mask the ragged end of the segment, then move the running maximum when the tile's exceeds
+    // it by more than RESCALE_GAP (rare after the first tile)
+    auto prepare = [&](int t, bool live) __attribute__((always_inline)) {
+        const int j0 = (t_lo + t) * DEC_BN;
+        if (live && j0 + DEC_BN > P) {
             const int thr = P - 1 - j0 - 4 * lg;
 #pragma unroll
-            for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    if (8 * (r >> 2) + (r & 3) > thr) s[cb][r] = NEG_BIG;
+            for (int r = 0; r < 16; ++r)
+                if (8 * (r >> 2) + (r & 3) > thr) s[r] = NEG_BIG;
         }
-        float m_new[2];
-        bool moved = false;
+        float tm = s[0];
 #pragma unroll
-        for (int cb = 0; cb < 2; ++cb) {
-            float tm = s[cb][0];
+        for (int r = 1; r < 16; ++r) tm = fmaxf(tm, s[r]);
+        tm = partner_max(tm) * c;
+        const float m_new = (live && tm > m_run + RESCALE_GAP) ? tm : m_run;
+        if (__any(m_new != m_run)) {
+            const float alpha = fast_exp2(m_run - m_new);
+            l_run *= alpha;
+            m_run = m_new;
 #pragma unroll
-            for (int r = 1; r < 16; ++r) tm = fmaxf(tm, s[cb][r]);
-            tm = partner_max(tm) * c;
-            m_new[cb] = (live && tm > m_run[cb] + RESCALE_GAP) ? tm : m_run[cb];
-            moved |= m_new[cb] != m_run[cb];
-        }
-        if (__any(moved)) {
+            for (int db = 0; db < 4; ++db)
 #pragma unroll
-            for (int cb = 0; cb < 2; ++cb) {
-                const float alpha = fast_exp2(m_run[cb] - m_new[cb]);
-                l_run[cb] *= alpha;
-                m_run[cb] = m_new[cb];
-#pragma unroll
-                for (int db = 0; db < 4; ++db)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        float x = acc[db][cb][r];
-                        dec_acc_scale(x, alpha);
-                        acc[db][cb][r] = x;
-                    }
-            }
+                for (int r = 0; r < 16; ++r) acc[db][r] *= alpha;
         }
     };
 
     issue(0, 0);
-    dma_wait();
-    __syncthreads();
     issue(min(1, nT - 1), 1);
-    scores(sm.k[0], 0);
-    prepare(0, 0, true);
-    const int nU = 2 * nT;
-    int buf = 0;
-    for (int u = 0; u < nU; ++u) {
-        const int hb = u & 1, t = u >> 1;
-        const int nbuf = buf + 1 == DEC_NBUF ? 0 : buf + 1;
-        const char* vt = sm.v[0] + buf * DEC_TILE_B;
-        const char* kt_next = sm.k[0] + (hb ? nbuf : buf) * DEC_TILE_B;
-        bf16x8 pf[2][2];
+    issue(min(2, nT - 1), 2);
+    dma_wait_but<8>();          // tile 0
+    __syncthreads();
+    scores(smk);
+    prepare(0, true);
+    for (int u = 0; u < nT; ++u) {
+        const int buf = u & 3;
+        float rs = 0.f;
+        f32x16 p;
 #pragma unroll
-        for (int cb = 0; cb < 2; ++cb) {
-            float rs = 0.f;
-            f32x16 p;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                p[r] = fast_exp2(fmaf(s[cb][r], c, -m_run[cb]));
-                rs += p[r];
-            }
-            l_run[cb] += rs;
-            pf[cb][0] = pack_frag(p, 0);
-            pf[cb][1] = pack_frag(p, 8);
+        for (int r = 0; r < 16; ++r) {
+            p[r] = fast_exp2(fmaf(s[r], c, -m_run));
+            rs += p[r];
         }
-        scores(kt_next, hb ? 0 : 32);
+        l_run += rs;
+        const bf16x8 pf0 = pack_frag(p, 0), pf1 = pack_frag(p, 8);
+        // tile u+1 has landed for every wavefront and tile u-1 is no longer read: its buffer
+        // takes tile u+3 (past the end the last tile again, into a buffer nobody reads)
+        dma_wait_but<4>();
+        __syncthreads();
+        issue(min(u + 3, nT - 1), (u + 3) & 3);
+        if (u + 1 < nT) scores(smk + ((u + 1) & 3) * DEC_TILE_B);
+        const char* vt = smv + buf * DEC_TILE_B;
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-            for (int db = 0; db < 4; ++db) {
-                bf16x8 a = lds_frag_t(vt, 32 * hb + 16 * ks, 32 * db, lane);
-                acc[db][0] = mma(a, pf[0][ks], acc[db][0]);
-                acc[db][1] = mma(a, pf[1][ks], acc[db][1]);
-            }
-        prepare((u + 1) >> 1, (u + 1) & 1, u + 1 < nU);
-        if (!hb) {
-            dma_wait();
-            __syncthreads();
-            issue(min(t + 2, nT - 1), nbuf + 1 == DEC_NBUF ? 0 : nbuf + 1);
-        } else {
-            buf = nbuf;
+        for (int db = 0; db < 4; ++db) {
+            acc[db] = mma(lds_frag_t(vt, 0, 32 * db, lane), pf0, acc[db]);
+            acc[db] = mma(lds_frag_t(vt, 16, 32 * db, lane), pf1, acc[db]);
         }
+        prepare(u + 1, u + 1 < nT);
     }
+    dma_wait();
+    const float l_tot = l_run + partner(l_run);
+    const float inv = 1.f / l_tot;
+    if (rho < rows) {
+        const size_t slot = (static_cast<size_t>(slot_base + sp) * B + rho / G) * Hq + hk * G + rho % G;
+        float* op = part_o + slot * HD;
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb) {
-        const int rho = wrow0 + 32 * cb + lc;
-        const float l_tot = l_run[cb] + partner(l_run[cb]);
-        const float inv = 1.f / l_tot;
-        if (rho < rows) {
-            const size_t slot = (static_cast<size_t>(slot_base + sp) * B + rho / G) * Hq + hk * G + rho % G;
-            float* op = part_o + slot * HD;
+        for (int db = 0; db < 4; ++db)
 #pragma unroll
-            for (int db = 0; db < 4; ++db)
-#pragma unroll
-                for (int r4 = 0; r4 < 4; ++r4) {
-                    typedef float f32x4 __attribute__((ext_vector_type(4)));
-                    f32x4 w = {acc[db][cb][4 * r4] * inv, acc[db][cb][4 * r4 + 1] * inv,
-                               acc[db][cb][4 * r4 + 2] * inv, acc[db][cb][4 * r4 + 3] * inv};
-                    *reinterpret_cast<f32x4*>(op + 32 * db + 8 * r4 + 4 * lg) = w;
-                }
-            if (lg == 0) part_l[slot] = (m_run[cb] + fast_log2(l_tot)) * CART_LN2;
-        }
+            for (int r4 = 0; r4 < 4; ++r4) {
+                typedef float f32x4 __attribute__((ext_vector_type(4)));
+                f32x4 w = {acc[db][4 * r4] * inv, acc[db][4 * r4 + 1] * inv, acc[db][4 * r4 + 2] * inv,
+                           acc[db][4 * r4 + 3] * inv};
+                *reinterpret_cast<f32x4*>(op + 32 * db + 8 * r4 + 4 * lg) = w;
+            }
+        if (lg == 0) part_l[slot] = (m_run + fast_log2(l_tot)) * CART_LN2;
     }
 }
 
 // One wavefront per (request, KV head, chunk of keys): chunks 0 .. n_cc-1 cover the request's
 // private cartridge pool[cart_id[b]] ([Hkv,pool_p,128]; none when cart_id is null or negative),
-// chunks n_cc .. n_cc+n_oc-1 its own KV rows.  32 keys per step through a private 16 KB LDS
+// chunks n_cc .. n_cc+n_oc-1 its own KV rows, split evenly over those slots.  32 keys per step through a private 16 KB LDS
 // slot; the G query rows of the group occupy columns 0..G-1 of one MFMA block.
-__global__ __launch_bounds__(256, 2) void decode_own_kernel(
-    const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
-    const int32_t* __restrict__ cu, const bf16_t* __restrict__ pool_k, const bf16_t* __restrict__ pool_v,
-    const int32_t* __restrict__ cart_id, int pool_p, float* __restrict__ part_o,
-    float* __restrict__ part_l, int B, int Hq, int Hkv, float c, int chunk, int n_cc, int n_oc, int n_ps) {
-    __shared__ char sm[4][2][DEC_SUB_B];   // [wavefront][K, V]
+__device__ __forceinline__ void decode_own_role(
+    char* sm /* [wavefront][K, V][32 rows] */, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+    const bf16_t* __restrict__ v, const int32_t* __restrict__ cu, const bf16_t* __restrict__ pool_k,
+    const bf16_t* __restrict__ pool_v, const int32_t* __restrict__ cart_id, int pool_p,
+    float* __restrict__ part_o, float* __restrict__ part_l, int B, int Hq, int Hkv, float c, int chunk, int n_cc,
+    int n_oc, int n_ps, int blk) {
     const int G = Hq / Hkv;
     const int lane = threadIdx.x & 63, lg = lane >> 5, lc = lane & 31;
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    long item = static_cast<long>(blockIdx.x) * 4 + wv;
+    long item = static_cast<long>(blk) * 4 + wv;
     const int hk = item % Hkv; item /= Hkv;
     const int cc = item % (n_cc + n_oc);
     const int b = static_cast<int>(item / (n_cc + n_oc));
     if (b >= B) return;
     const bool priv = cc < n_cc;
-    int len, k0;
+    int len, k0, ck = chunk;
     uint32_t pitch;
     const char *k_b, *v_b;
     if (priv) {
@@ -297,14 +266,15 @@ __global__ __launch_bounds__(256, 2) void decode_own_kernel(
     } else {
         const int t0 = cu[b];
         len = cu[b + 1] - t0;
-        k0 = (cc - n_cc) * chunk;
+        ck = own_chunk_keys(len, n_oc);
+        k0 = (cc - n_cc) * ck;
         pitch = static_cast<uint32_t>(Hkv) * ROW_B;
         const size_t row0 = static_cast<size_t>(t0 + k0) * Hkv + hk;
         k_b = reinterpret_cast<const char*>(k) + row0 * ROW_B;
         v_b = reinterpret_cast<const char*>(v) + row0 * ROW_B;
     }
     if (k0 >= len) return;
-    const int nk = min(chunk, len - k0);
+    const int nk = min(ck, len - k0);
 
     bf16x8 qf[8];
     {
@@ -312,8 +282,8 @@ __global__ __launch_bounds__(256, 2) void decode_own_kernel(
 #pragma unroll
         for (int t = 0; t < 8; ++t) qf[t] = *reinterpret_cast<const bf16x8*>(qp + 16 * t);
     }
-    char* kt = sm[wv][0];
-    char* vt = sm[wv][1];
+    char* kt = sm + (2 * wv) * DEC_SUB_B;
+    char* vt = kt + DEC_SUB_B;
     // 32 rows x 256 B = 8 direct-to-LDS loads of 4 rows each, per tensor, by this wavefront alone
     auto issue = [&](int j0) __attribute__((always_inline)) {
         const size_t step = static_cast<size_t>(j0) * pitch;
@@ -400,9 +370,31 @@ __global__ __launch_bounds__(256, 2) void decode_own_kernel(
     }
 }
 
+// Both roles in one launch, two workgroups per CU: prefix workgroups (matrix-core and LDS work
+// on data that sits in L2) and own-KV workgroups (HBM streaming) alternate in the grid while
+// both kinds remain, so that the two run side by side instead of one after the other.
+__global__ __launch_bounds__(256, 2) void decode_fused_kernel(
+    const bf16_t* __restrict__ q, const PrefixTable tab, const bf16_t* __restrict__ k,
+    const bf16_t* __restrict__ v, const int32_t* __restrict__ cu, const bf16_t* __restrict__ pool_k,
+    const bf16_t* __restrict__ pool_v, const int32_t* __restrict__ cart_id, int pool_p,
+    float* __restrict__ part_o, float* __restrict__ part_l, int B, int Hq, int Hkv, float c, int n_rb, int chunk,
+    int n_cc, int n_oc, int n_ps, int n_pre_wg, int n_own_wg) {
+    static_assert(2 * DEC_NBUF * DEC_TILE_B == 4 * 2 * DEC_SUB_B, "the two roles share one LDS block");
+    __shared__ __attribute__((aligned(16))) char sm[4 * 2 * DEC_SUB_B];
+    const int i = blockIdx.x;
+    const int both = min(n_pre_wg, n_own_wg);
+    bool pre;
+    int idx;
+    if (i < 2 * both) { pre = !(i & 1); idx = i >> 1; }
+    else              { pre = n_pre_wg > n_own_wg; idx = i - both; }
+    if (pre) decode_prefix_role(sm, q, tab, part_o, part_l, B, Hq, Hkv, c, n_rb, idx);
+    else     decode_own_role(sm, q, k, v, cu, pool_k, pool_v, cart_id, pool_p, part_o, part_l, B, Hq, Hkv, c, chunk,
+                             n_cc, n_oc, n_ps, idx);
+}
+
 // o[b,h,:] = sum_i w_i part_o[i] / sum_i w_i, w_i = exp(lse_i - max lse), over the partial slots
 // that exist for the request: the n_ps prefix parts, the chunks of its private cartridge (when it
-// has one), the ceil(len/chunk) chunks of its own rows.  One wavefront per (b, h): lane i holds
+// has one), the chunks of its own rows (own_chunk_keys(len) keys each).  One wavefront per (b, h): lane i holds
 // slot i's lse and weight (up to 64 slots, else a serial loop), then every lane accumulates its
 // two head elements over the slots with the loads of four slots in flight.
 __global__ __launch_bounds__(256) void decode_merge_kernel(const float* __restrict__ part_o,
@@ -418,7 +410,8 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(const float* __restri
     const int b = row / Hq;
     const int len = cu[b + 1] - cu[b];
     const int priv = (n_cc > 0 && cart_id && cart_id[b] >= 0) ? (pool_p + chunk - 1) / chunk : 0;
-    const int own = (len + chunk - 1) / chunk;
+    const int ck = own_chunk_keys(len, n_oc);
+    const int own = (len + ck - 1) / ck;
     const int n = n_ps + n_cc + n_oc;
     auto valid = [&](int i) { return i < n_ps || (i < n_ps + n_cc ? i - n_ps < priv : i - n_ps - n_cc < own); };
     const size_t stride = static_cast<size_t>(B) * Hq;
@@ -499,19 +492,15 @@ static int run_decode(const DecodePlan& p, int B, int Hq, int Hkv, float scale, 
     float* part_o = static_cast<float*>(ws);
     float* part_l = reinterpret_cast<float*>(static_cast<char*>(ws) + p.part_o_bytes);
     const float c = scale * CART_LOG2E;
-    // (running the prefix kernel beside the own-KV kernel on a second stream was measured: the
-    // event hand-over between the two queues costs more than the overlap gains, 141 vs 131 us)
-    trace_begin(st);   // kernel order: prefix, own, merge
-    if (p.n_ps > 0)
-        hipLaunchKernelGGL(decode_prefix_kernel, dim3(static_cast<unsigned>(p.tab.blk0[p.tab.n_seg])), dim3(256), 0, st,
-                           static_cast<const bf16_t*>(q), p.tab, part_o, part_l, B, Hq, Hkv, c, p.n_rb);
-    trace_mark(st);
     const long items = static_cast<long>(B) * Hkv * (p.n_cc + p.n_oc);
-    hipLaunchKernelGGL(decode_own_kernel, dim3(static_cast<unsigned>((items + 3) / 4)), dim3(256), 0, st,
-                       static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(k),
-                       static_cast<const bf16_t*>(v), cu, static_cast<const bf16_t*>(pool_k),
-                       static_cast<const bf16_t*>(pool_v), cart_id, pool_p, part_o, part_l, B, Hq, Hkv, c, p.chunk,
-                       p.n_cc, p.n_oc, p.n_ps);
+    const int n_own_wg = static_cast<int>((items + 3) / 4);
+    const bf16_t *Q = static_cast<const bf16_t*>(q), *K = static_cast<const bf16_t*>(k), *V = static_cast<const bf16_t*>(v),
+                 *PK = static_cast<const bf16_t*>(pool_k), *PV = static_cast<const bf16_t*>(pool_v);
+    trace_begin(st);   // kernel order: prefix + own (one launch), merge
+    const int n_pre_wg = p.n_ps > 0 ? p.tab.blk0[p.tab.n_seg] : 0;
+    hipLaunchKernelGGL(decode_fused_kernel, dim3(static_cast<unsigned>(n_pre_wg + n_own_wg)), dim3(256), 0, st, Q, p.tab,
+                       K, V, cu, PK, PV, cart_id, pool_p, part_o, part_l, B, Hq, Hkv, c, p.n_rb, p.chunk, p.n_cc,
+                       p.n_oc, p.n_ps, n_pre_wg, n_own_wg);
     trace_mark(st);
     const long rows = static_cast<long>(B) * Hq;
     hipLaunchKernelGGL(decode_merge_kernel, dim3(static_cast<unsigned>((rows + 3) / 4)), dim3(256), 0, st, part_o,
