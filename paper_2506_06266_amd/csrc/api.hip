@@ -102,7 +102,7 @@ size_t cart_attn_bwd_workspace(const cart_attn_desc* d) {
 size_t cart_attn_varlen_fwd_workspace(const cart_attn_varlen_desc* d) {
     cart_attn_desc a;
     if (check_varlen(d, &a) != CART_OK) return 0;
-    return cart::attn_mfma_fwd_workspace(a);
+    return cart::attn_mfma_fwd_workspace(a, d->T);
 }
 
 size_t cart_attn_varlen_bwd_workspace(const cart_attn_varlen_desc* d) {

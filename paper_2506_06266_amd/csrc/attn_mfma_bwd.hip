@@ -113,7 +113,8 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
     const bf16_t* __restrict__ zk, const bf16_t* __restrict__ zv, const bf16_t* __restrict__ d_o,
     const float* __restrict__ nlse2, const float* __restrict__ ndelta, bf16_t* __restrict__ dq,
-    const int32_t* __restrict__ cu, int n_tok, int B, int Smax, int Hq, int Hkv, int P, float c, float scale) {
+    const int32_t* __restrict__ cu, const int32_t* __restrict__ row_lo, int n_tok, int B, int Smax, int Hq,
+    int Hkv, int P, float c, float scale) {
     constexpr int NBUF = DQ_NBUF;
     constexpr int BUF_B = 2 * BWD_TILE_B;
     constexpr int V_OFF = BWD_TILE_B;
@@ -129,7 +130,9 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
     const int lane = threadIdx.x & 63, lg = lane >> 5, lc = lane & 31;
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int q0 = qt * BWD_WG_ROWS, wrow0 = q0 + 64 * wv;
-    // packed layout: the grid covers the longest sequence; nothing to do past the end of this one
+    // packed layout: the grid covers the longest sequence; nothing to do past the end of this one.
+    // With row_lo (B = 1, S = all packed rows) the query tiles are cut from the packed rows as in
+    // the forward kernel and row i sees the own keys row_lo[i] .. i.
     const SeqSpan sp = seq_span(cu, b, n_tok, Smax, Hq);
     const int S = sp.len;
     const size_t t0 = sp.t0;
@@ -137,10 +140,12 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
 
     u32x4 qf[2][8], gf[2][8];     // B operands: column = query, k = head element
     float nl2[2], ndl[2];         // -lse2, -delta of the lane's queries
+    int lo_q[2] = {0, 0};         // first own key the lane's queries see
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb) {
         int qi = wrow0 + 32 * cb + lc;
         qi = qi < S ? qi : S - 1;
+        if (row_lo) lo_q[cb] = row_lo[qi];
         const size_t row = (t0 + qi) * Hq + h;
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
@@ -183,10 +188,13 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
     // tile order: see the forward kernel
     const int nPf = P / BWD_TILE;
     const int rag = (P % BWD_TILE) ? 1 : 0;
-    const int nOf = q0 / BWD_TILE;
     const int own_end = min(S, q0 + BWD_WG_ROWS);
+    const int lo_first = row_lo ? row_lo[q0] : 0, lo_last = row_lo ? row_lo[own_end - 1] : 0;
+    const int tA = lo_first / BWD_TILE, tU0 = (lo_last + BWD_TILE - 1) / BWD_TILE, tD = q0 / BWD_TILE;
+    const int nOf = max(0, tD - tU0);
+    const int nLow = min(tU0, tD) - tA;
     const int nMain = nPf + nOf;
-    const int nT = nMain + rag + (own_end + BWD_TILE - 1) / BWD_TILE - nOf;
+    const int nT = nMain + rag + nLow + (own_end + BWD_TILE - 1) / BWD_TILE - tD;
     const char* zk_b = reinterpret_cast<const char*>(zk) + static_cast<size_t>(hk) * P * ROW_B;
     const char* zv_b = reinterpret_cast<const char*>(zv) + static_cast<size_t>(hk) * P * ROW_B;
     const uint32_t own_pitch = static_cast<uint32_t>(Hkv) * ROW_B;
@@ -194,7 +202,8 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
     const char* v_b = reinterpret_cast<const char*>(v) + (t0 * Hkv + hk) * ROW_B;
     auto tile_pre = [&](int t) __attribute__((always_inline)) { return t < nPf || (rag && t == nMain); };
     auto tile_j0 = [&](int t) __attribute__((always_inline)) {
-        return (t < nPf ? t : t < nMain ? t - nPf : (rag && t == nMain) ? nPf : t - nPf - rag) * BWD_TILE;
+        const int m = t - nMain - rag;
+        return (t < nPf ? t : t < nMain ? tU0 + t - nPf : (rag && t == nMain) ? nPf : m < nLow ? tA + m : tD + m - nLow) * BWD_TILE;
     };
     const uint32_t dma_c0 = (lane & 15) ^ (((lane >> 4) & 3) << 2);
     struct TileSrc { const char* kb; const char* vb; int lim; uint32_t pitch; uint32_t lds_k, lds_v; };
@@ -223,6 +232,12 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
 #pragma unroll
         for (int r = 0; r < 16; ++r)
             if (8 * (r >> 2) + (r & 3) > thr) x[r] = NEG_BIG;
+        if (row_lo && !pre) {
+            const int tlo = lo_q[cb] - j0 - 4 * lg;
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                if (8 * (r >> 2) + (r & 3) < tlo) x[r] = NEG_BIG;
+        }
     };
 
     // per-lane LDS addresses: row-wise K fragments (V: + V_OFF) of the tile of sub-tile u+1,
@@ -901,14 +916,16 @@ bool attn_mfma_bwd_supported(const cart_attn_desc& d) { return d.dtype == CART_B
 
 static size_t r256(size_t n) { return (n + 255) & ~static_cast<size_t>(255); }
 
-// beyond the delta array: lse2 (one value per token and head) and the two per-sequence dZ partial
-// buffers [B,Hkv,P,128].  tokens = B S (batched layout) or the packed row count.
+// beyond the delta array: lse2 (one value per token and head) and the two dZ partial buffers
+// [n_part,Hkv,P,128].  Batched layout (tokens < 0): one partial per sequence.  Packed layout:
+// tokens = the packed row count, one partial per BWD_PACK_CHUNK rows, + the row_lo array.
 size_t attn_mfma_bwd_workspace(const cart_attn_desc& d, long tokens) {
-    const long n_part = tokens < 0 ? d.B : (tokens + BWD_PACK_CHUNK - 1) / BWD_PACK_CHUNK;
-    if (tokens < 0) tokens = static_cast<long>(d.B) * d.S;
+    const bool packed = tokens >= 0;
+    const long n_part = packed ? (tokens + BWD_PACK_CHUNK - 1) / BWD_PACK_CHUNK : d.B;
+    if (!packed) tokens = static_cast<long>(d.B) * d.S;
     const size_t rows = r256(static_cast<size_t>(tokens) * d.Hq * sizeof(float));
     const size_t part = r256(static_cast<size_t>(n_part) * d.Hkv * d.P * HD * sizeof(float));
-    return rows + 2 * part;
+    return rows + 2 * part + (packed ? r256(static_cast<size_t>(tokens) * sizeof(int32_t)) : 0);
 }
 
 int launch_attn_bwd_mfma(const cart_attn_desc& d, float scale, const void* q, const void* k,
@@ -924,6 +941,13 @@ int launch_attn_bwd_mfma(const cart_attn_desc& d, float scale, const void* q, co
     float* lse2 = reinterpret_cast<float*>(w + rows_b);
     float* part_k = reinterpret_cast<float*>(w + 2 * rows_b);
     float* part_v = reinterpret_cast<float*>(w + 2 * rows_b + part_b);
+    // packed batch with a prefix: the dQ kernel cuts its query tiles from the packed rows (it sees
+    // one sequence of T rows and the first row of every row's sequence)
+    int32_t* row_lo = nullptr;
+    if (cu && d.P > 0) {
+        row_lo = reinterpret_cast<int32_t*>(w + 2 * rows_b + 2 * part_b);
+        launch_row_lo(cu, d.B, T, row_lo, st);
+    }
     const bf16_t *Q = static_cast<const bf16_t*>(q), *K = static_cast<const bf16_t*>(k),
                  *V = static_cast<const bf16_t*>(v), *ZK = static_cast<const bf16_t*>(zk),
                  *ZV = static_cast<const bf16_t*>(zv), *DO = static_cast<const bf16_t*>(d_o);
@@ -933,10 +957,17 @@ int launch_attn_bwd_mfma(const cart_attn_desc& d, float scale, const void* q, co
     hipLaunchKernelGGL(attn_bwd_prep_kernel, dim3(static_cast<unsigned>((rows + 15) / 16)), dim3(256), 0, st,
                        static_cast<const bf16_t*>(o), DO, lse, delta, lse2, tokens, d.S, d.Hq, cu ? 1 : 0);
     trace_mark(st);
-    const int nQt = (d.S + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
-    hipLaunchKernelGGL(attn_bwd_dq_kernel, dim3(static_cast<unsigned>(static_cast<long>(nQt) * d.B * d.Hq)), dim3(256),
-                       0, st, Q, K, V, ZK, ZV, DO, lse2, delta, static_cast<bf16_t*>(dq), cu, T, d.B, d.S,
-                       d.Hq, d.Hkv, d.P, c, scale);
+    if (row_lo) {
+        const long nQt = (T + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
+        hipLaunchKernelGGL(attn_bwd_dq_kernel, dim3(static_cast<unsigned>(nQt * d.Hq)), dim3(256), 0, st, Q, K, V, ZK,
+                           ZV, DO, lse2, delta, static_cast<bf16_t*>(dq), nullptr, row_lo, T, 1, T, d.Hq, d.Hkv, d.P,
+                           c, scale);
+    } else {
+        const long nQt = (d.S + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
+        hipLaunchKernelGGL(attn_bwd_dq_kernel, dim3(static_cast<unsigned>(nQt * d.B * d.Hq)), dim3(256), 0, st, Q, K, V,
+                           ZK, ZV, DO, lse2, delta, static_cast<bf16_t*>(dq), cu, nullptr, T, d.B, d.S, d.Hq, d.Hkv,
+                           d.P, c, scale);
+    }
     trace_mark(st);
     const long nPb = (d.P + BWD_WG_ROWS - 1) / BWD_WG_ROWS, nOb = (d.S + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
     const unsigned kgrid = static_cast<unsigned>((nPb * n_part + nOb * d.B) * d.Hkv);

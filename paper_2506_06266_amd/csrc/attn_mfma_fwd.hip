@@ -45,8 +45,9 @@ struct FwdSmem {
 __global__ __launch_bounds__(256, 1) void attn_fwd_mfma_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
     const bf16_t* __restrict__ zk, const bf16_t* __restrict__ zv, bf16_t* __restrict__ o,
-    float* __restrict__ lse, int* __restrict__ flags, const int32_t* __restrict__ cu, int n_tok, int B,
-    int Smax, int Hq, int Hkv, int P, float c /* scale*log2(e) */) {
+    float* __restrict__ lse, int* __restrict__ flags, const int32_t* __restrict__ cu,
+    const int32_t* __restrict__ row_lo, int n_tok, int B, int Smax, int Hq, int Hkv, int P,
+    float c /* scale*log2(e) */) {
     __shared__ FwdSmem sm;
     __shared__ int sm_bad;
     const int G = Hq / Hkv;
@@ -66,6 +67,9 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_mfma_kernel(
     // Rows of sequence b: [t0, t0 + S).  Batched layout: S rows each; packed layout (cu given):
     // rows cu[b] .. cu[b+1]-1 of T, the grid is sized for the longest sequence and a workgroup
     // whose query tile lies past the end of its sequence has nothing to do.
+    // Packed layout with a prefix (row_lo given, B = 1, S = all packed rows): query tiles are cut
+    // from the packed rows regardless of sequence boundaries -- no sequence ends in a partly
+    // filled tile -- and row i sees the own keys row_lo[i] .. i (row_lo = first row of its sequence).
     const SeqSpan sp = seq_span(cu, b, n_tok, Smax, Hq);
     const int S = sp.len;
     const size_t t0 = sp.t0;
@@ -79,10 +83,12 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_mfma_kernel(
     // They are pinned to accumulation registers (the matrix cores read B operands from there
     // directly), which leaves the ordinary vector registers to the softmax arithmetic.
     u32x4 qraw[2][8];
+    int lo_q[2] = {0, 0};     // first own key the lane's queries see
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb) {
         int qi = wrow0 + 32 * cb + lc;
         qi = qi < S ? qi : S - 1;
+        if (row_lo) lo_q[cb] = row_lo[qi];
         const bf16_t* qp = q + ((t0 + qi) * Hq + h) * HD + 8 * lg;
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
@@ -124,10 +130,16 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_mfma_kernel(
     // the (at most four) own tiles on the diagonal, through a copy of the loop that masks.
     const int nPf = P / FWD_BN;                        // whole prefix tiles
     const int rag = (P % FWD_BN) ? 1 : 0;              // ragged prefix tile
-    const int nOf = q0 / FWD_BN;                       // own tiles below the first query
     const int own_end = min(S, q0 + FWD_BM);
+    // own tiles (of 64 rows from row 0): every query of the workgroup sees the whole of tiles
+    // tU0 .. tD-1; tiles tA .. min(tU0, tD)-1 start before the first key of some query and tiles
+    // tD .. tEnd-1 lie on the diagonal (one sequence: tA = tU0 = 0)
+    const int lo_first = row_lo ? row_lo[q0] : 0, lo_last = row_lo ? row_lo[own_end - 1] : 0;
+    const int tA = lo_first / FWD_BN, tU0 = (lo_last + FWD_BN - 1) / FWD_BN, tD = q0 / FWD_BN;
+    const int nOf = max(0, tD - tU0);
+    const int nLow = min(tU0, tD) - tA;
     const int nMain = nPf + nOf;
-    const int nT = nMain + rag + (own_end + FWD_BN - 1) / FWD_BN - nOf;
+    const int nT = nMain + rag + nLow + (own_end + FWD_BN - 1) / FWD_BN - tD;
     const char* zk_b = reinterpret_cast<const char*>(zk) + static_cast<size_t>(hk) * P * ROW_B;
     const char* zv_b = reinterpret_cast<const char*>(zv) + static_cast<size_t>(hk) * P * ROW_B;
     const uint32_t own_pitch = static_cast<uint32_t>(Hkv) * ROW_B;
@@ -138,7 +150,8 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_mfma_kernel(
         return t < nPf || (rag && t == nMain);
     };
     auto tile_j0 = [&](int t) __attribute__((always_inline)) {
-        return (t < nPf ? t : t < nMain ? t - nPf : (rag && t == nMain) ? nPf : t - nPf - rag) * FWD_BN;
+        const int m = t - nMain - rag;      // among the masked own tiles
+        return (t < nPf ? t : t < nMain ? tU0 + t - nPf : (rag && t == nMain) ? nPf : m < nLow ? tA + m : tD + m - nLow) * FWD_BN;
     };
 
     // Direct-to-LDS load of one tile, eight instructions per wavefront (K rows, then V rows),
@@ -173,6 +186,12 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_mfma_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r)
                 if (8 * (r >> 2) + (r & 3) > thr) x[cb][r] = NEG_BIG;
+            if (row_lo && !pre) {           // ... or precedes the first key of the query's sequence
+                const int tlo = lo_q[cb] - j0 - 4 * lg;
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (8 * (r >> 2) + (r & 3) < tlo) x[cb][r] = NEG_BIG;
+            }
         }
     };
 
@@ -415,8 +434,8 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_mfma_kernel(
 __global__ __launch_bounds__(256) void attn_fwd_repair_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
     const bf16_t* __restrict__ zk, const bf16_t* __restrict__ zv, bf16_t* __restrict__ o,
-    float* __restrict__ lse, const int* __restrict__ flags, const int32_t* __restrict__ cu, int n_tok,
-    int B, int Smax, int Hq, int Hkv, int P, float c) {
+    float* __restrict__ lse, const int* __restrict__ flags, const int32_t* __restrict__ cu,
+    const int32_t* __restrict__ row_lo, int n_tok, int B, int Smax, int Hq, int Hkv, int P, float c) {
     if (flags[blockIdx.x] == 0) return;
     const int G = Hq / Hkv;
     const int nQt = (Smax + FWD_BM - 1) / FWD_BM;
@@ -435,9 +454,10 @@ __global__ __launch_bounds__(256) void attn_fwd_repair_kernel(
         const uint32_t qw = *reinterpret_cast<const uint32_t*>(q + row * HD + 2 * lane);
         const float q0 = __uint_as_float(qw << 16), q1 = __uint_as_float(qw & 0xffff0000u);
         float m = -3.0e38f, l = 0.f, a0 = 0.f, a1 = 0.f;
-        for (int j = 0; j < P + i + 1; ++j) {
+        const int own0 = row_lo ? row_lo[i] : 0;      // first own key of the row
+        for (int j = 0; j < P + (i - own0) + 1; ++j) {
             const size_t kr = j < P ? static_cast<size_t>(hk) * P + j
-                                    : (t0 + (j - P)) * Hkv + hk;
+                                    : (t0 + own0 + (j - P)) * Hkv + hk;
             const uint32_t kw = *reinterpret_cast<const uint32_t*>((j < P ? zk : k) + kr * HD + 2 * lane);
             const uint32_t vw = *reinterpret_cast<const uint32_t*>((j < P ? zv : v) + kr * HD + 2 * lane);
             const float sc = wave_sum(q0 * __uint_as_float(kw << 16) + q1 * __uint_as_float(kw & 0xffff0000u)) * c;
@@ -454,15 +474,35 @@ __global__ __launch_bounds__(256) void attn_fwd_repair_kernel(
     }
 }
 
+// row_lo[i] = first packed row of the sequence that row i belongs to (cu: B+1 offsets, cu[B] = T)
+__global__ __launch_bounds__(256) void attn_row_lo_kernel(const int32_t* __restrict__ cu, int B, int T,
+                                                          int32_t* __restrict__ row_lo) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= T) return;
+    int lo = 0, hi = B;                 // largest b with cu[b] <= i
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (cu[mid] <= i) lo = mid; else hi = mid;
+    }
+    row_lo[i] = cu[lo];
+}
+int launch_row_lo(const int32_t* cu, int B, int T, int32_t* row_lo, hipStream_t st) {
+    hipLaunchKernelGGL(attn_row_lo_kernel, dim3((T + 255) / 256), dim3(256), 0, st, cu, B, T, row_lo);
+    return static_cast<int>(hipGetLastError());
+}
+
 bool attn_mfma_supported(const cart_attn_desc& d) {
     return d.dtype == CART_BF16 && d.D == 128;
 }
-static long fwd_grid(const cart_attn_desc& d) {
+// workgroups: per sequence, or over the packed rows (a packed batch with a prefix; T > 0)
+static long fwd_grid(const cart_attn_desc& d, int T) {
+    if (T > 0 && d.P > 0) return static_cast<long>((T + FWD_BM - 1) / FWD_BM) * d.Hq;
     return static_cast<long>((d.S + FWD_BM - 1) / FWD_BM) * d.B * d.Hq;
 }
-// one overflow flag per workgroup
-size_t attn_mfma_fwd_workspace(const cart_attn_desc& d) {
-    return (static_cast<size_t>(fwd_grid(d)) * sizeof(int) + 255) & ~static_cast<size_t>(255);
+static size_t r256(size_t n) { return (n + 255) & ~static_cast<size_t>(255); }
+// one overflow flag per workgroup; packed batches: + the first row of every row's sequence
+size_t attn_mfma_fwd_workspace(const cart_attn_desc& d, int T) {
+    return r256(static_cast<size_t>(fwd_grid(d, T)) * sizeof(int)) + (T > 0 ? r256(static_cast<size_t>(T) * sizeof(int32_t)) : 0);
 }
 
 // cu == nullptr: batched layout [B,S,...].  Otherwise the packed layout: d.S is the longest
@@ -470,17 +510,27 @@ size_t attn_mfma_fwd_workspace(const cart_attn_desc& d) {
 int launch_attn_fwd_mfma(const cart_attn_desc& d, float scale, const void* q, const void* k,
                          const void* v, const void* zk, const void* zv, void* o, float* lse,
                          void* ws, hipStream_t st, const int32_t* cu, int T) {
-    const unsigned grid = static_cast<unsigned>(fwd_grid(d));
+    if (!cu) T = 0;
+    const unsigned grid = static_cast<unsigned>(fwd_grid(d, T));
     int* flags = static_cast<int*>(ws);
+    int32_t* row_lo = nullptr;
+    int B = d.B, S = d.S;
     const bf16_t *Q = static_cast<const bf16_t*>(q), *K = static_cast<const bf16_t*>(k),
                  *V = static_cast<const bf16_t*>(v), *ZK = static_cast<const bf16_t*>(zk),
                  *ZV = static_cast<const bf16_t*>(zv);
+    if (cu && d.P > 0) {   // tiles over the packed rows: the kernels see one sequence of T rows
+        row_lo = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + r256(static_cast<size_t>(grid) * sizeof(int)));
+        launch_row_lo(cu, d.B, T, row_lo, st);
+        cu = nullptr;
+        B = 1;
+        S = T;
+    }
     trace_begin(st);   // kernel order: forward, repair
     hipLaunchKernelGGL(attn_fwd_mfma_kernel, dim3(grid), dim3(256), 0, st, Q, K, V, ZK, ZV,
-                       static_cast<bf16_t*>(o), lse, flags, cu, T, d.B, d.S, d.Hq, d.Hkv, d.P, scale * CART_LOG2E);
+                       static_cast<bf16_t*>(o), lse, flags, cu, row_lo, T, B, S, d.Hq, d.Hkv, d.P, scale * CART_LOG2E);
     trace_mark(st);
     hipLaunchKernelGGL(attn_fwd_repair_kernel, dim3(grid), dim3(256), 0, st, Q, K, V, ZK, ZV,
-                       static_cast<bf16_t*>(o), lse, flags, cu, T, d.B, d.S, d.Hq, d.Hkv, d.P, scale * CART_LOG2E);
+                       static_cast<bf16_t*>(o), lse, flags, cu, row_lo, T, B, S, d.Hq, d.Hkv, d.P, scale * CART_LOG2E);
     trace_mark(st);
     return static_cast<int>(hipGetLastError());
 }

@@ -97,7 +97,8 @@ int launch_decode_vector(const cart_decode_desc& d, float scale, const void* q, 
 // MFMA (bf16, head_dim 128) kernels
 bool attn_mfma_supported(const cart_attn_desc& d);       // forward
 bool attn_mfma_bwd_supported(const cart_attn_desc& d);
-size_t attn_mfma_fwd_workspace(const cart_attn_desc& d);
+size_t attn_mfma_fwd_workspace(const cart_attn_desc& d, int T = 0);        // T > 0: packed rows
+int launch_row_lo(const int32_t* cu, int B, int T, int32_t* row_lo, hipStream_t st);
 size_t attn_mfma_bwd_workspace(const cart_attn_desc& d, long tokens = -1);   // beyond the delta array
 int launch_attn_fwd_mfma(const cart_attn_desc& d, float scale, const void* q, const void* k,
                          const void* v, const void* zk, const void* zv, void* o, float* lse,

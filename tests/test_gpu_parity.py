@@ -518,6 +518,10 @@ VARLEN_CASES = [
     ("no_prefix", [33, 290], 2, 1, 0, None),
     ("loose_max_seqlen", [65, 200, 7], 8, 2, 128, 272),
     ("one_sequence", [513], 2, 2, 300, None),
+    # fewer prefix slots than a key tile: a tile of packed rows that spans sequences starts from
+    # the ragged prefix tile
+    ("short_prefix", [100, 1, 300, 30, 30, 30, 200], 4, 2, 5, None),
+    ("tile_aligned_sequences", [256, 512, 64, 192], 2, 1, 64, None),
     # more than 2048 packed rows: the prefix gradient is gathered over two chunks of rows, the
     # boundary falling inside a sequence
     ("two_chunks_of_rows", [1500, 700, 301], 2, 1, 65, None),
@@ -569,6 +573,9 @@ def test_attention_varlen_workload_distributions():
 
 
 def test_attention_varlen_equal_lengths_is_the_batched_call():
+    """Same problem through both layouts.  The packed path cuts its query tiles from the packed
+    rows and sums the prefix gradient per chunk of rows, so the sums run in another order: equal
+    to a few bf16 roundings, not bit for bit."""
     B, S, Hq, Hkv, P = 3, 300, 4, 2, 100
     c = dev(_varlen_case(5, [S] * B, Hq, Hkv, P))
     o, lse = cb.cart_attn_varlen_fwd(c["q"], c["k"], c["v"], c["zk"], c["zv"], c["cu"], S)
@@ -578,14 +585,22 @@ def test_attention_varlen_equal_lengths_is_the_batched_call():
     gb = cb.cart_attn_bwd(rs(c["q"]), rs(c["k"]), rs(c["v"]), c["zk"], c["zv"], o2, lse2, rs(c["do"]), n_frozen=3,
                           impl=cb.IMPL_MFMA)
     torch.cuda.synchronize()
-    assert torch.equal(o.view(B, S, Hq, 128), o2)
-    assert torch.equal(lse.view(Hq, B, S).permute(1, 0, 2), lse2)
+    assert rel_err(to_np(o.view(B, S, Hq, 128)), to_np(o2)) < 1e-2
+    assert rel_err(to_np(lse.view(Hq, B, S).permute(1, 0, 2)), to_np(lse2)) < 1e-5
+    for a, b in zip(gv[:3], gb[:3]):
+        assert rel_err(to_np(a.view(b.shape)), to_np(b)) < 1e-2
+    for a, b in zip(gv[3:], gb[3:]):
+        assert rel_err(to_np(a), to_np(b)) < 1e-3
+    assert (gv[3][:, :3] == 0).all()
+    # without a prefix the packed path keeps one sequence per query tile: the batched call's bits
+    o, lse = cb.cart_attn_varlen_fwd(c["q"], c["k"], c["v"], None, None, c["cu"], S)
+    gv = cb.cart_attn_varlen_bwd(c["q"], c["k"], c["v"], None, None, c["cu"], S, o, lse, c["do"])
+    o2, lse2 = cb.cart_attn_fwd(rs(c["q"]), rs(c["k"]), rs(c["v"]), None, None, impl=cb.IMPL_MFMA)
+    gb = cb.cart_attn_bwd(rs(c["q"]), rs(c["k"]), rs(c["v"]), None, None, o2, lse2, rs(c["do"]), impl=cb.IMPL_MFMA)
+    torch.cuda.synchronize()
+    assert torch.equal(o.view(B, S, Hq, 128), o2) and torch.equal(lse.view(Hq, B, S).permute(1, 0, 2), lse2)
     for a, b in zip(gv[:3], gb[:3]):
         assert torch.equal(a.view(b.shape), b)
-    # the prefix gradient is summed in a different order (per chunk of packed rows, not per sequence)
-    for a, b in zip(gv[3:], gb[3:]):
-        assert rel_err(to_np(a), to_np(b)) < 1e-5
-    assert (gv[3][:, :3] == 0).all()
 
 
 def test_attention_varlen_rejects_what_it_cannot_run():
