@@ -2,7 +2,8 @@
 // collected while it generates): per position, the K most probable tokens and their
 // log-probabilities, by descending probability, the lower token index first among equal logits.
 //
-// One workgroup per position; a single pass over the logits.
+// One workgroup per position; a single pass over the logits.  topk_row_one_pass (the default for
+// bf16 rows, K <= 256) is described at the kernel.
 // topk_row_resident: 1024 threads hold the whole bf16 row (<= 131072 logits) in registers.  After
 // the log-sum-exp (as in the loss kernel) the K largest are found without sorting the row:
 //   1. every thread takes the maximum of its 128 logits; the K-th largest of these 1024 maxima,
@@ -233,10 +234,13 @@ __global__ __launch_bounds__(1024) void topk_row_resident(const bf16_t* logits, 
     }, idx_out, logp_out, lse, true);
 }
 
-// Two passes over the row with 256 threads, several workgroups per CU (their memory and arithmetic
-// phases overlap; the second pass is served by L2): pass 1 = log-sum-exp and the thread maxima,
-// then tau and the list as above from a second read.  bf16 rows in 16-byte vectors; K <= 256.
-__global__ __launch_bounds__(256) void topk_row_two_pass(const bf16_t* logits, int32_t* idx_out,
+// One pass over the row with 256 threads, several workgroups per CU (their memory and arithmetic
+// phases overlap): log-sum-exp, and per thread its maximum and its two best logits (value and
+// index).  tau = the K-th largest thread maximum as above; the list of logits >= tau is then made
+// of the threads' best logits.  A thread whose second best reaches tau may hold a third: only
+// such a thread reads its vectors again (about one thread per row for K = 20).  bf16 rows in
+// 16-byte vectors; K <= 256.
+__global__ __launch_bounds__(256) void topk_row_one_pass(const bf16_t* logits, int32_t* idx_out,
                                                          float* logp_out, int V, int K) {
     constexpr int THREADS = 256, NW = THREADS / CART_WAVE, CAP = 1024;
     __shared__ float red_max[NW], red_sum[NW];
@@ -254,15 +258,29 @@ __global__ __launch_bounds__(256) void topk_row_two_pass(const bf16_t* logits, i
     logp_out += static_cast<size_t>(n) * K;
     if (tid == 0) list_n = 0;
 
-    // pass 1: per thread a running maximum (raw, as in the resident kernel) and the sum of
-    // 2^(x log2e - reference) against a reference that moves only in whole steps
+    // per thread: a running maximum (raw, as in the resident kernel), the sum of
+    // 2^(x log2e - reference) against a reference that moves only in whole steps, and the two
+    // best (order word: value, then lower index) among its logits above -inf
     float tmax = __uint_as_float(0xff7f0000u), ref = -3.0e38f, sum = 0.f;
-    for (int v = tid; v < nvec; v += THREADS) {
-        const u32x4 q = src[v];
+    uint64_t t1w = 0, t2w = 0;                       // 0 = none yet
+    float t2v = __uint_as_float(0xff800000u);        // value of the second best (-inf: none)
+    auto take = [&](int v, const u32x4 q) __attribute__((always_inline)) {
         const uint32_t w[4] = {q.x, q.y, q.z, q.w};
-        float vm = tmax;
+        float vv = __uint_as_float(0xff800000u);     // maximum of this vector
 #pragma unroll
-        for (int e = 0; e < 4; ++e) vm = max3_raw(vm, w[e] & 0xffff0000u, w[e] << 16);
+        for (int e = 0; e < 4; ++e) vv = max3_raw(vv, w[e] & 0xffff0000u, w[e] << 16);
+        if (vv > t2v) {                              // (rare after the first few vectors)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t bits = (e & 1) ? (w[e >> 1] & 0xffff0000u) : (w[e >> 1] << 16);
+                if (__uint_as_float(bits) > t2v) {   // equal values: the earlier index stays
+                    const uint64_t ow = order_word(bf16_key(bits >> 16), 8u * v + e);
+                    if (ow > t1w) { t2w = t1w; t1w = ow; } else { t2w = ow; }
+                    t2v = t2w ? bf16_key_value(static_cast<uint32_t>(t2w >> 32)) : __uint_as_float(0xff800000u);
+                }
+            }
+        }
+        const float vm = max3_raw(tmax, __float_as_uint(vv), __float_as_uint(vv));
         tmax = vm;
         const float need = __uint_as_float(__float_as_uint(vm) & 0xffff0000u) * CART_LOG2E;
         if (need > ref) {                      // (rare after the first few vectors)
@@ -276,7 +294,10 @@ __global__ __launch_bounds__(256) void topk_row_two_pass(const bf16_t* logits, i
             s1 += fast_exp2(fmaf(__uint_as_float(w[e] & 0xffff0000u), CART_LOG2E, -ref));
         }
         sum += s0 + s1;
-    }
+    };
+    // (more loads in flight per thread were measured and change nothing: at 4 TB/s of logits the
+    // kernel is bound by its arithmetic, one exponential per logit)
+    for (int v = tid; v < nvec; v += THREADS) take(v, src[v]);
     const uint32_t kmax = bf16_key(__float_as_uint(tmax) >> 16);
     all_kmax[tid] = static_cast<uint16_t>(kmax);
     const float wref = wave_max(ref);
@@ -307,30 +328,39 @@ __global__ __launch_bounds__(256) void topk_row_two_pass(const bf16_t* logits, i
     }
     __syncthreads();
     const uint32_t tau = tau_s;
-    // pass 2: the thread re-reads its vectors only if its maximum can reach tau
-    if (kmax >= tau) {
-        const float tau_f = bf16_key_value(tau);
-        for (int v = tid; v < nvec; v += THREADS) {
-            const u32x4 q = src[v];
-            const uint32_t w[4] = {q.x, q.y, q.z, q.w};
-            float vm = __uint_as_float(0xff7f0000u);
+    // (tau at or below -inf: fewer than K threads hold a logit above -inf; the threads' best
+    // logits leave the -inf ones out, so such a row takes the selection rounds below)
+    const bool listed = tau > bf16_key(0xff80u);
+    if (listed) {
+        const uint32_t k1 = static_cast<uint32_t>(t1w >> 32), k2 = static_cast<uint32_t>(t2w >> 32);
+        if (t2w != 0 && k2 >= tau) {
+            // both of the thread's best reach tau: there may be more, read its vectors again
+            const float tau_f = bf16_key_value(tau);
+            for (int v = tid; v < nvec; v += THREADS) {
+                const u32x4 q = src[v];
+                const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+                float vm = __uint_as_float(0xff7f0000u);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) vm = max3_raw(vm, w[e] & 0xffff0000u, w[e] << 16);
-            if (__uint_as_float(__float_as_uint(vm) & 0xffff0000u) >= tau_f) {
+                for (int e = 0; e < 4; ++e) vm = max3_raw(vm, w[e] & 0xffff0000u, w[e] << 16);
+                if (__uint_as_float(__float_as_uint(vm) & 0xffff0000u) >= tau_f) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const uint32_t bits = (e & 1) ? (w[e >> 1] & 0xffff0000u) : (w[e >> 1] << 16);
-                    if (__uint_as_float(bits) >= tau_f) {
-                        const int pos = atomicAdd(&list_n, 1);
-                        if (pos < CAP) { list_key[pos] = bf16_key(bits >> 16); list_idx[pos] = 8u * v + e; }
+                    for (int e = 0; e < 8; ++e) {
+                        const uint32_t bits = (e & 1) ? (w[e >> 1] & 0xffff0000u) : (w[e >> 1] << 16);
+                        if (__uint_as_float(bits) >= tau_f) {
+                            const int pos = atomicAdd(&list_n, 1);
+                            if (pos < CAP) { list_key[pos] = bf16_key(bits >> 16); list_idx[pos] = 8u * v + e; }
+                        }
                     }
                 }
             }
+        } else if (t1w != 0 && k1 >= tau) {
+            const int pos = atomicAdd(&list_n, 1);
+            if (pos < CAP) { list_key[pos] = k1; list_idx[pos] = 0xffffffffu - static_cast<uint32_t>(t1w); }
         }
     }
     __syncthreads();
     const int cnt = list_n;
-    if (cnt >= K && cnt <= CAP) {
+    if (listed && cnt >= K && cnt <= CAP) {
         for (int t = tid; t < cnt; t += THREADS) {
             const uint64_t me = order_word(list_key[t], list_idx[t]);
             int rank = 0;
@@ -400,7 +430,7 @@ int launch_topk(const cart_topk_desc& d, const void* logits, int32_t* idx, float
 #define CART_TOPK_RESIDENT 0
 #endif
     if (vec && d.K <= 256 && !(CART_TOPK_RESIDENT && resident)) {
-        hipLaunchKernelGGL(topk_row_two_pass, dim3(d.N), dim3(256), 0, st, static_cast<const bf16_t*>(logits), idx,
+        hipLaunchKernelGGL(topk_row_one_pass, dim3(d.N), dim3(256), 0, st, static_cast<const bf16_t*>(logits), idx,
                            logp, d.V, d.K);
     } else if (resident) {
         const bf16_t* x = static_cast<const bf16_t*>(logits);
