@@ -82,108 +82,130 @@ __device__ __forceinline__ float max3_raw(float a, uint32_t b, uint32_t c) {
     _Pragma("unroll") for (int i_ = 0; i_ < NV; ++i_)                                      \
         asm volatile("" : "+v"(x[i_].x), "+v"(x[i_].y), "+v"(x[i_].z), "+v"(x[i_].w))
 
+#ifndef KL_RESIDENT_WGS
+#define KL_RESIDENT_WGS 256      // workgroups of the register-resident kernel: one per CU of an MI355X
+#endif
+
 template <int NV>
 __global__ __launch_bounds__(1024) void kl_row_resident(const bf16_t* logits, const int32_t* idx,
                                                         const float* logp, bf16_t* dlogits,
-                                                        float* row_kl, int V, int K, float scale,
+                                                        float* row_kl, int N, int V, int K, float scale,
                                                         int rest) {
     constexpr int THREADS = 1024, NW = THREADS / CART_WAVE;
     __shared__ KlTeacher tc;
     __shared__ float red_max[NW], red_m[NW], red_sum[NW], rest_terms[2];
-    const int n = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const size_t row = static_cast<size_t>(n) * V;
-    const u32x4* src = reinterpret_cast<const u32x4*>(logits + row);
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int nvec = V >> 3;
-
-    u32x4 x[NV];
     const uint32_t FILL = 0xff7fff7fu;   // two bf16 of the most negative finite value
-#pragma unroll
-    for (int i = 0; i < NV; ++i) {
-        int v = i * THREADS + tid;
-        x[i] = u32x4{FILL, FILL, FILL, FILL};
-        if (v < nvec) x[i] = __builtin_nontemporal_load(src + v);
-    }
-    float m_part = kl_stage_teacher<bf16_t, THREADS>(tc, logits + row, idx + static_cast<size_t>(n) * K,
-                                                    logp ? logp + static_cast<size_t>(n) * K : nullptr, V, K);
 
-    // sweep 1: the row maximum; both elements of a packed word widened to fp32 (a word of two
-    // -inf logits read whole would be a NaN) and a three-way maximum
-    float mx = -3.0e38f;
+    // One workgroup fills a CU, so nothing else would cover the latency of a row's load: the
+    // workgroup walks rows n, n + gridDim.x, ... and fetches the next row into the registers of
+    // the current one as the last sweep releases them.
+    int n = blockIdx.x;
+    if (n >= N) return;
+    u32x4 x[NV];
+    {
+        const u32x4* src = reinterpret_cast<const u32x4*>(logits + static_cast<size_t>(n) * V);
 #pragma unroll
-    for (int i = 0; i < NV; ++i) {
-        const uint32_t w[4] = {x[i].x, x[i].y, x[i].z, x[i].w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) mx = max3_raw(mx, w[e] & 0xffff0000u, w[e] << 16);
-    }
-    KL_FORGET(x);
-    mx = wave_max(mx);
-    m_part = wave_sum(m_part);
-    if (lane == 0) { red_max[wv] = mx; red_m[wv] = m_part; }
-    __syncthreads();
-    float M = 0.f;
-    mx = red_max[0];
-#pragma unroll
-    for (int w = 0; w < NW; ++w) { mx = fmaxf(mx, red_max[w]); M += red_m[w]; }
-
-    // sweep 2: sum of exp(x - max), in base 2
-    const float c0 = -mx * CART_LOG2E;
-    float s0 = 0.f, s1 = 0.f;
-#pragma unroll
-    for (int i = 0; i < NV; ++i) {
-        const uint32_t w[4] = {x[i].x, x[i].y, x[i].z, x[i].w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            s0 += fast_exp2(fmaf(__uint_as_float(w[e] << 16), CART_LOG2E, c0));
-            s1 += fast_exp2(fmaf(__uint_as_float(w[e] & 0xffff0000u), CART_LOG2E, c0));
+        for (int i = 0; i < NV; ++i) {
+            int v = i * THREADS + tid;
+            x[i] = u32x4{FILL, FILL, FILL, FILL};
+            if (v < nvec) x[i] = __builtin_nontemporal_load(src + v);
         }
-        __builtin_amdgcn_sched_barrier(0);   // keep the sweeps' temporaries from piling up
     }
-    KL_FORGET(x);
-    float sum = wave_sum(s0 + s1);
-    if (lane == 0) red_sum[wv] = sum;
-    __syncthreads();
-    sum = 0.f;
-#pragma unroll
-    for (int w = 0; w < NW; ++w) sum += red_sum[w];
-    const float lse2 = fast_log2(sum) - c0;          // log2 of the softmax denominator
+    for (;;) {
+        const size_t row = static_cast<size_t>(n) * V;
+        float m_part = kl_stage_teacher<bf16_t, THREADS>(tc, logits + row, idx + static_cast<size_t>(n) * K,
+                                                        logp ? logp + static_cast<size_t>(n) * K : nullptr, V, K);
 
-    // sweep 3: g = c * exp(x - lse) with c = scale * M (rest-bucket mode: the off-support
-    // coefficient scale * (M - S) / (1 - S)); |c| rides in the exponent
-    float coef = M, extra = 0.f;
-    if (rest) {
-        kl_rest_terms(tc, K, lse2, M, rest_terms);
+        // sweep 1: the row maximum; both elements of a packed word widened to fp32 (a word of two
+        // -inf logits read whole would be a NaN) and a three-way maximum
+        float mx = -3.0e38f;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const uint32_t w[4] = {x[i].x, x[i].y, x[i].z, x[i].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) mx = max3_raw(mx, w[e] & 0xffff0000u, w[e] << 16);
+        }
+        KL_FORGET(x);
+        mx = wave_max(mx);
+        m_part = wave_sum(m_part);
+        if (lane == 0) { red_max[wv] = mx; red_m[wv] = m_part; }
         __syncthreads();
-        coef = rest_terms[0];
-        extra = rest_terms[1];
-    }
-    const float c = scale * coef;
-    const float off = -(lse2 - fast_log2(fabsf(c)));  // c == 0 gives -inf, hence g == 0
-    const uint32_t sgn = c < 0.f ? 0x80008000u : 0u;
-    u32x4* dst = reinterpret_cast<u32x4*>(dlogits + row);
+        float M = 0.f;
+        mx = red_max[0];
 #pragma unroll
-    for (int i = 0; i < NV; ++i) {
-        int v = i * THREADS + tid;
-        const uint32_t w[4] = {x[i].x, x[i].y, x[i].z, x[i].w};
-        uint32_t r[4];
+        for (int w = 0; w < NW; ++w) { mx = fmaxf(mx, red_max[w]); M += red_m[w]; }
+
+        // sweep 2: sum of exp(x - max), in base 2
+        const float c0 = -mx * CART_LOG2E;
+        float s0 = 0.f, s1 = 0.f;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            float lo = fast_exp2(fmaf(__uint_as_float(w[e] << 16), CART_LOG2E, off));
-            float hi = fast_exp2(fmaf(__uint_as_float(w[e] & 0xffff0000u), CART_LOG2E, off));
-            r[e] = pack_bf16x2(lo, hi) ^ sgn;
+        for (int i = 0; i < NV; ++i) {
+            const uint32_t w[4] = {x[i].x, x[i].y, x[i].z, x[i].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                s0 += fast_exp2(fmaf(__uint_as_float(w[e] << 16), CART_LOG2E, c0));
+                s1 += fast_exp2(fmaf(__uint_as_float(w[e] & 0xffff0000u), CART_LOG2E, c0));
+            }
+            __builtin_amdgcn_sched_barrier(0);   // keep the sweeps' temporaries from piling up
         }
-        if (v < nvec) __builtin_nontemporal_store(u32x4{r[0], r[1], r[2], r[3]}, dst + v);
-        __builtin_amdgcn_sched_barrier(0);
-    }
-    // recorded tokens: the thread that stored the vector holding idx_j rewrites that element, so
-    // the two stores to one address are in program order
-    for (int j = 0; j < K; ++j) {
-        int id = tc.idx[j];
-        if (id >= 0 && ((id >> 3) & (THREADS - 1)) == tid) {
-            float s = fast_exp2(fmaf(tc.x[j], CART_LOG2E, -lse2));
-            dlogits[row + id] = f32_to_bf16(scale * ((rest ? 1.f : M) * s - tc.t[j]));
+        KL_FORGET(x);
+        float sum = wave_sum(s0 + s1);
+        if (lane == 0) red_sum[wv] = sum;
+        __syncthreads();
+        sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) sum += red_sum[w];
+        const float lse2 = fast_log2(sum) - c0;          // log2 of the softmax denominator
+
+        // sweep 3: g = c * exp(x - lse) with c = scale * M (rest-bucket mode: the off-support
+        // coefficient scale * (M - S) / (1 - S)); |c| rides in the exponent.  Each vector's
+        // registers take the same vector of the next row as soon as its gradient is stored.
+        float coef = M, extra = 0.f;
+        if (rest) {
+            kl_rest_terms(tc, K, lse2, M, rest_terms);
+            __syncthreads();
+            coef = rest_terms[0];
+            extra = rest_terms[1];
         }
+        const float c = scale * coef;
+        const float off = -(lse2 - fast_log2(fabsf(c)));  // c == 0 gives -inf, hence g == 0
+        const uint32_t sgn = c < 0.f ? 0x80008000u : 0u;
+        u32x4* dst = reinterpret_cast<u32x4*>(dlogits + row);
+        const int n_next = n + static_cast<int>(gridDim.x);
+        const bool more = n_next < N;
+        const u32x4* src_next = reinterpret_cast<const u32x4*>(logits + static_cast<size_t>(more ? n_next : n) * V);
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            int v = i * THREADS + tid;
+            const uint32_t w[4] = {x[i].x, x[i].y, x[i].z, x[i].w};
+            uint32_t r[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float lo = fast_exp2(fmaf(__uint_as_float(w[e] << 16), CART_LOG2E, off));
+                float hi = fast_exp2(fmaf(__uint_as_float(w[e] & 0xffff0000u), CART_LOG2E, off));
+                r[e] = pack_bf16x2(lo, hi) ^ sgn;
+            }
+            if (v < nvec) __builtin_nontemporal_store(u32x4{r[0], r[1], r[2], r[3]}, dst + v);
+            x[i] = u32x4{FILL, FILL, FILL, FILL};
+            if (more && v < nvec) x[i] = __builtin_nontemporal_load(src_next + v);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // recorded tokens: the thread that stored the vector holding idx_j rewrites that element,
+        // so the two stores to one address are in program order
+        for (int j = 0; j < K; ++j) {
+            int id = tc.idx[j];
+            if (id >= 0 && ((id >> 3) & (THREADS - 1)) == tid) {
+                float s = fast_exp2(fmaf(tc.x[j], CART_LOG2E, -lse2));
+                dlogits[row + id] = f32_to_bf16(scale * ((rest ? 1.f : M) * s - tc.t[j]));
+            }
+        }
+        kl_row_value(tc, K, lse2 * CART_LN2, extra, row_kl + n);
+        if (!more) break;
+        n = n_next;
+        __syncthreads();    // the teacher staging area and the reduction arrays are reused
     }
-    kl_row_value(tc, K, lse2 * CART_LN2, extra, row_kl + n);
 }
 
 template <typename T>
@@ -269,12 +291,13 @@ int launch_kl(const cart_kl_desc& d, const void* logits, const int32_t* idx, con
         const bf16_t* x = static_cast<const bf16_t*>(logits);
         bf16_t* g = static_cast<bf16_t*>(d_logits);
         const int nvec = d.V / 8;
+        const dim3 grid(static_cast<unsigned>(d.N < KL_RESIDENT_WGS ? d.N : KL_RESIDENT_WGS));
         if (nvec <= 1024 * 4)
-            hipLaunchKernelGGL(kl_row_resident<4>, dim3(d.N), dim3(1024), 0, st, x, idx, logp, g, rows, d.V, d.K, d.scale, rest);
+            hipLaunchKernelGGL(kl_row_resident<4>, grid, dim3(1024), 0, st, x, idx, logp, g, rows, d.N, d.V, d.K, d.scale, rest);
         else if (nvec <= 1024 * 8)
-            hipLaunchKernelGGL(kl_row_resident<8>, dim3(d.N), dim3(1024), 0, st, x, idx, logp, g, rows, d.V, d.K, d.scale, rest);
+            hipLaunchKernelGGL(kl_row_resident<8>, grid, dim3(1024), 0, st, x, idx, logp, g, rows, d.N, d.V, d.K, d.scale, rest);
         else
-            hipLaunchKernelGGL(kl_row_resident<16>, dim3(d.N), dim3(1024), 0, st, x, idx, logp, g, rows, d.V, d.K, d.scale, rest);
+            hipLaunchKernelGGL(kl_row_resident<16>, grid, dim3(1024), 0, st, x, idx, logp, g, rows, d.N, d.V, d.K, d.scale, rest);
     } else if (d.logits_dtype == CART_BF16) {
         hipLaunchKernelGGL(kl_row_stream<bf16_t>, dim3(d.N), dim3(256), 0, st,
                            static_cast<const bf16_t*>(logits), idx, logp,
