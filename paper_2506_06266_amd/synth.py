@@ -96,6 +96,8 @@ KL_CONFIGS: Dict[str, KLConfig] = {
     # shrunken bf16 cases: full vocabulary / few rows, and a vocabulary with a ragged vector tail
     "kl_small": KLConfig("kl_small", 4002, 48, 128256, 20, "bf16", 3.0, 3.0, 0.95),
     "kl_ragged": KLConfig("kl_ragged", 4003, 37, 50257, 20, "bf16", 3.0, 3.0, 0.95),
+    # more rows than the loss kernel has workgroups (each walks several rows), small vocabulary
+    "kl_many_rows": KLConfig("kl_many_rows", 4004, 700, 4096, 20, "bf16", 3.0, 3.0, 0.95),
 }
 
 DECODE_CONFIGS: Dict[str, DecodeConfig] = {

@@ -214,7 +214,7 @@ def test_attention_score_far_above_first_keys(gap_nats):
 # ------------------------------------------------------------------------------------------------
 # distillation loss
 # ------------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("name", ["cfg1_loss", "kl_small", "kl_ragged"])
+@pytest.mark.parametrize("name", ["cfg1_loss", "kl_small", "kl_ragged", "kl_many_rows"])
 def test_distill_kl_matches_oracle(name):
     cfg = synth.KL_CONFIGS[name]
     print("case", name, flush=True)
@@ -247,7 +247,7 @@ def test_distill_kl_matches_oracle(name):
     assert torch.equal(dl2, dl) and loss2.item() == loss.item()
 
 
-@pytest.mark.parametrize("name", ["cfg1_loss", "kl_small", "kl_ragged"])
+@pytest.mark.parametrize("name", ["cfg1_loss", "kl_small", "kl_ragged", "kl_many_rows"])
 def test_distill_kl_rest_bucket_matches_oracle(name):
     """The second reading of the truncated teacher: recorded tokens + one rest outcome."""
     cfg = synth.KL_CONFIGS[name]
