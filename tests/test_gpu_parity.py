@@ -610,3 +610,27 @@ def test_attention_varlen_rejects_what_it_cannot_run():
                                 c["cu"], 50)
     with pytest.raises(cb.CartridgeError):      # max_seqlen above the row count
         cb.cart_attn_varlen_fwd(c["q"], c["k"], c["v"], c["zk"], c["zv"], c["cu"], 91)
+
+
+# (B, Hq, Hkv, P, max own length): one request, one query head per KV head, 32 of them, a prefix
+# shorter than / just past one key tile, a prefix whose splits end in a ragged tile, own caches
+# much longer than the prefix, more stacked rows than one prefix workgroup holds
+DECODE_EDGE_SHAPES = [(1, 4, 1, 1, 1), (1, 8, 8, 31, 40), (2, 32, 1, 33, 70), (3, 4, 2, 4100, 5), (150, 8, 2, 700, 33),
+                      (2, 4, 4, 0, 5000), (5, 8, 2, 64, 9000)]
+
+
+@pytest.mark.parametrize("shape", DECODE_EDGE_SHAPES, ids=lambda t: "B%d_Hq%d_Hkv%d_P%d_L%d" % t)
+def test_decode_edge_shapes(shape):
+    B, Hq, Hkv, P, max_len = shape
+    print("case", shape, flush=True)
+    c = _composed_case(900 + B + P, B, Hq, Hkv, [P] if P else [], 0, 0, max_len)
+    f = to_np
+    zk, zv = (c["shared"][0] if P else (torch.zeros(Hkv, 0, 128), torch.zeros(Hkv, 0, 128)))
+    o_ref, lse_ref = orc.decode(f(c["q"]), f(zk), f(zv), f(c["k_own"]), f(c["v_own"]), c["cu"].numpy())
+    d = lambda t: t.to(DEV)
+    o, lse = cb.cart_decode(d(c["q"]), d(zk) if P else None, d(zv) if P else None, d(c["k_own"]), d(c["v_own"]),
+                            d(c["cu"]), max_len, impl=cb.IMPL_MFMA)
+    torch.cuda.synchronize()
+    e = {"o": rel_err(to_np(o), o_ref), "lse": rel_err(to_np(lse), lse_ref)}
+    print(shape, e, flush=True)
+    assert e["o"] <= TOL["bf16"] and e["lse"] <= TOL["bf16"]
