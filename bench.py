@@ -176,6 +176,15 @@ def main() -> int:
     pool_bytes = 2 * pool_k.numel() * 2 + 2 * own_tokens * dcfg.Hkv * dcfg.D * 2 + 2 * dcfg.B * dcfg.Hq * dcfg.D * 2
     del pool_k, pool_v
 
+    # the serving comparison run: no cartridge, 8 requests that each carry a 131072-token KV cache
+    lcfg = synth.DECODE_CONFIGS["cfg5_long"]
+    lg = synth.decode_inputs(lcfg, dev)
+    lg_o, lg_lse = cb.cart_decode(lg["q"], None, None, lg["k_own"], lg["v_own"], lg["cu_lens"], lcfg.max_len)
+    long_ms = timed(lambda: cb.cart_decode(lg["q"], None, None, lg["k_own"], lg["v_own"], lg["cu_lens"], lcfg.max_len,
+                                           o=lg_o, lse=lg_lse))
+    long_bytes = 2 * lg["k_own"].numel() * 2
+    del lg, lg_o, lg_lse
+
     # one packed global batch of 64 ragged conversations (<= 1024 tokens) at the same layer shape
     pcfg = synth.PACKED_CONFIGS["cfg3_packed"]
     pk = synth.attn_packed_inputs(pcfg, dev)
@@ -248,6 +257,8 @@ def main() -> int:
                       "decode_4_shared_segments_ms": round(seg_ms, 4),
                       "decode_cartridge_per_request_ms": round(pool_ms, 4),
                       "decode_cartridge_per_request_gbs": round(pool_bytes / pool_ms / 1e6, 1),
+                      "decode_no_cartridge_8x131072_ms": round(long_ms, 4),
+                      "decode_no_cartridge_8x131072_gbs": round(long_bytes / long_ms / 1e6, 1),
                       "attn_packed_64_conversations_fwd_bwd_ms": round(packed_ms, 4),
                       "attn_packed_64_conversations_tflops": round(packed_tflops, 1)},
     }
