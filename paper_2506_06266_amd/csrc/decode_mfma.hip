@@ -385,8 +385,14 @@ __global__ __launch_bounds__(256, 2) void decode_fused_kernel(
     const int both = min(n_pre_wg, n_own_wg);
     bool pre;
     int idx;
-    if (i < 2 * both) { pre = !(i & 1); idx = i >> 1; }
-    else              { pre = n_pre_wg > n_own_wg; idx = i - both; }
+    // The roles alternate in runs of 8 workgroups (consecutive workgroups go to the 8 XCDs in
+    // turn): every XCD hosts both roles, and with 8 KV heads a prefix workgroup's head
+    // (idx % Hkv) is its XCD, whose L2 then holds that one head's cartridge.
+    const int both8 = both & ~7;
+    if (i < 2 * both8) { pre = !((i >> 3) & 1); idx = ((i >> 4) << 3) | (i & 7); }
+    else               { const int r = i - 2 * both8, left = both - both8;
+                         if (r < 2 * left) { pre = !(r & 1); idx = both8 + (r >> 1); }
+                         else              { pre = n_pre_wg > n_own_wg; idx = i - both; } }
     if (pre) decode_prefix_role(sm, q, tab, part_o, part_l, B, Hq, Hkv, c, n_rb, idx);
     else     decode_own_role(sm, q, k, v, cu, pool_k, pool_v, cart_id, pool_p, part_o, part_l, B, Hq, Hkv, c, chunk,
                              n_cc, n_oc, n_ps, idx);
