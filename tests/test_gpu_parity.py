@@ -522,6 +522,8 @@ VARLEN_CASES = [
     # the ragged prefix tile
     ("short_prefix", [100, 1, 300, 30, 30, 30, 200], 4, 2, 5, None),
     ("tile_aligned_sequences", [256, 512, 64, 192], 2, 1, 64, None),
+    # hundreds of very short sequences: every tile of packed rows spans many of them
+    ("many_tiny_sequences", [1 + (7 * i) % 19 for i in range(300)], 2, 1, 64, None),
     # more than 2048 packed rows: the prefix gradient is gathered over two chunks of rows, the
     # boundary falling inside a sequence
     ("two_chunks_of_rows", [1500, 700, 301], 2, 1, 65, None),
