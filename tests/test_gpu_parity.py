@@ -574,6 +574,45 @@ def test_attention_varlen_workload_distributions():
         assert e <= TOL["bf16"], (cfg.name, kk, e)
 
 
+def test_attention_varlen_score_far_above_first_keys():
+    """The flagged recomputation of the forward pass on a packed batch: in two of the three
+    sequences one own key outscores the cartridge's first keys by 200 nats, which overflows the
+    fixed softmax reference of the rows that see it."""
+    lens, Hq, Hkv, D, P = [200, 90, 310], 4, 2, 128, 96
+    gap = 200.0
+    g = torch.Generator().manual_seed(200)
+    u = torch.randn(D, generator=g)
+    u /= u.norm()
+    amp = math.sqrt(gap * math.sqrt(D))
+    T = sum(lens)
+    q = (amp * u + 0.05 * torch.randn(T, Hq, D, generator=g)).to(torch.bfloat16)
+    k = 0.05 * torch.randn(T, Hkv, D, generator=g)
+    k[50] += amp * u            # row 50 of sequence 0
+    k[290 + 120] += amp * u     # row 120 of sequence 2
+    k = k.to(torch.bfloat16)
+    v = torch.randn(T, Hkv, D, generator=g).to(torch.bfloat16)
+    zk = (0.05 * torch.randn(Hkv, P, D, generator=g)).to(torch.bfloat16)
+    zv = torch.randn(Hkv, P, D, generator=g).to(torch.bfloat16)
+    do = torch.randn(T, Hq, D, generator=g).to(torch.bfloat16)
+    cu = torch.tensor([0, 200, 290, 600], dtype=torch.int32)
+    f = to_np
+    o_ref, lse_ref = orc.attn_varlen_fwd(f(q), f(k), f(v), f(zk), f(zv), cu.numpy())
+    g_ref = orc.attn_varlen_bwd(f(q), f(k), f(v), f(zk), f(zv), f(do), cu.numpy())
+    # sequence 1 has no such key and keeps ordinary attention; the rows after a planted key copy its value
+    assert np.abs(o_ref[51:200] - f(v)[50:51].repeat(Hq // Hkv, axis=1)).max() < 1e-6
+    d = [x.to(DEV) for x in (q, k, v, zk, zv, cu)]
+    o, lse = cb.cart_attn_varlen_fwd(*d, max(lens))
+    grads = cb.cart_attn_varlen_bwd(*d, max(lens), o, lse, do.to(DEV))
+    torch.cuda.synchronize()
+    errs = {"o": rel_err(to_np(o), o_ref), "lse": rel_err(to_np(lse), lse_ref),
+            "d_v_own": rel_err(to_np(grads[2]), g_ref[2]), "d_z_v": rel_err(to_np(grads[4]), g_ref[4])}
+    print("packed gap", errs, flush=True)
+    for kk, e in errs.items():
+        assert e <= TOL["bf16"], (kk, e)
+    for x in grads:
+        assert torch.isfinite(x.float()).all()
+
+
 def test_attention_varlen_equal_lengths_is_the_batched_call():
     """Same problem through both layouts.  The packed path cuts its query tiles from the packed
     rows and sums the prefix gradient per chunk of rows, so the sums run in another order: equal
