@@ -176,6 +176,21 @@ def main() -> int:
     pool_bytes = 2 * pool_k.numel() * 2 + 2 * own_tokens * dcfg.Hkv * dcfg.D * 2 + 2 * dcfg.B * dcfg.Hq * dcfg.D * 2
     del pool_k, pool_v
 
+    # the decode call as a serving loop would issue it: captured once into a HIP graph (the library
+    # neither allocates nor synchronises), ten calls per replay
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        dec_step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    dec_graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(dec_graph):
+        for _ in range(10):
+            dec_step()
+    graph_ms = timed(dec_graph.replay) / 10
+    del dec_graph
+
     # the serving comparison run: no cartridge, 8 requests that each carry a 131072-token KV cache
     lcfg = synth.DECODE_CONFIGS["cfg5_long"]
     lg = synth.decode_inputs(lcfg, dev)
@@ -257,6 +272,7 @@ def main() -> int:
                       "decode_4_shared_segments_ms": round(seg_ms, 4),
                       "decode_cartridge_per_request_ms": round(pool_ms, 4),
                       "decode_cartridge_per_request_gbs": round(pool_bytes / pool_ms / 1e6, 1),
+                      "decode_graph_replay_ms": round(graph_ms, 4),
                       "decode_no_cartridge_8x131072_ms": round(long_ms, 4),
                       "decode_no_cartridge_8x131072_gbs": round(long_bytes / long_ms / 1e6, 1),
                       "attn_packed_64_conversations_fwd_bwd_ms": round(packed_ms, 4),
