@@ -128,10 +128,10 @@ def main() -> int:
 
     part_ms = {name: sum(ev[s][i].elapsed_time(ev[s][i + 1]) for s in range(args.steps)) / args.steps
                for i, (name, _) in enumerate(parts)}
-    bwd_kernels = ["prep", "dq", "dk", "dv", "dz_reduce"]
+    bwd_kernels = ["dq", "dk", "dv", "dz_reduce"]
     k_ms = {n: 0.0 for n in bwd_kernels}
     for tr in traces:
-        iv = tr.intervals_ms(6)
+        iv = tr.intervals_ms(5)
         for n, v in zip(bwd_kernels, iv):
             k_ms[n] += v / args.steps
         tr.close()

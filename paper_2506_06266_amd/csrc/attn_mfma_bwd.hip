@@ -31,40 +31,6 @@ constexpr int BWD_NBUF = 3;
 constexpr int BWD_WG_ROWS = 256;                  // stationary rows per workgroup (4 x 64)
 constexpr int BWD_PACK_CHUNK = 2048;              // packed layout: tokens per prefix-gradient partial
 
-// ---- -delta = -rowsum(dO * O), -lse2 = -lse * log2(e) (negated: they enter the products as
-// init values); 16 lanes per row, 8 elements per lane ----
-__global__ __launch_bounds__(256) void attn_bwd_prep_kernel(const bf16_t* __restrict__ o,
-                                                            const bf16_t* __restrict__ d_o,
-                                                            const float* __restrict__ lse,
-                                                            float* __restrict__ ndelta,
-                                                            float* __restrict__ nlse2, long tokens,
-                                                            int S, int Hq, int packed) {
-    // rows of o / d_o are (token, head) pairs in both layouts; the statistics are [B,Hq,S]
-    // (batched, tokens = B S) or [Hq,tokens] (packed)
-    const long row = static_cast<long>(blockIdx.x) * 16 + (threadIdx.x >> 4);
-    const long rows = tokens * Hq;
-    if (row >= rows) return;
-    const int sub = threadIdx.x & 15;
-    const u32x4 a = *reinterpret_cast<const u32x4*>(o + row * HD + sub * 8);
-    const u32x4 g = *reinterpret_cast<const u32x4*>(d_o + row * HD + sub * 8);
-    float s = 0.f;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        s = fmaf(__uint_as_float(a[e] << 16), __uint_as_float(g[e] << 16), s);
-        s = fmaf(__uint_as_float(a[e] & 0xffff0000u), __uint_as_float(g[e] & 0xffff0000u), s);
-    }
-#pragma unroll
-    for (int off = 8; off > 0; off >>= 1) s += __shfl_xor(s, off, 16);
-    if (sub == 0) {
-        const int h = row % Hq;
-        const long t = row / Hq;
-        const size_t st = packed ? static_cast<size_t>(h) * tokens + t
-                                 : (static_cast<size_t>(t / S) * Hq + h) * S + t % S;
-        ndelta[st] = -s;
-        nlse2[st] = -lse[st] * CART_LOG2E;
-    }
-}
-
 // store a transposed accumulator block set: lane owns output row `row_ptr` (nullptr: skip),
 // register r of block db holds column 32 db + 8 (r/4) + 4 g + r%4
 __device__ __forceinline__ void store_rows_bf16(const f32x16 (&acc)[4], bf16_t* row_ptr, int lg, float mul) {
@@ -111,10 +77,10 @@ struct DqSmem {
 
 __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
-    const bf16_t* __restrict__ zk, const bf16_t* __restrict__ zv, const bf16_t* __restrict__ d_o,
-    const float* __restrict__ nlse2, const float* __restrict__ ndelta, bf16_t* __restrict__ dq,
-    const int32_t* __restrict__ cu, const int32_t* __restrict__ row_lo, int n_tok, int B, int Smax, int Hq,
-    int Hkv, int P, float c, float scale) {
+    const bf16_t* __restrict__ zk, const bf16_t* __restrict__ zv, const bf16_t* __restrict__ o,
+    const bf16_t* __restrict__ d_o, const float* __restrict__ lse, float* __restrict__ nlse2,
+    float* __restrict__ ndelta, bf16_t* __restrict__ dq, const int32_t* __restrict__ cu,
+    const int32_t* __restrict__ row_lo, int n_tok, int B, int Smax, int Hq, int Hkv, int P, float c, float scale) {
     constexpr int NBUF = DQ_NBUF;
     constexpr int BUF_B = 2 * BWD_TILE_B;
     constexpr int V_OFF = BWD_TILE_B;
@@ -138,13 +104,17 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
     const size_t t0 = sp.t0;
     if (q0 >= S) return;
 
+    // The row statistics of the backward pass are formed here, where O and dO of every query row
+    // pass through registers anyway: -delta = -rowsum(dO * O) and -lse2 = -lse * log2(e)
+    // (negated: they enter the products as init values).  They are also written out for the dK
+    // and dV kernels, which run after this one.
     u32x4 qf[2][8], gf[2][8];     // B operands: column = query, k = head element
     float nl2[2], ndl[2];         // -lse2, -delta of the lane's queries
     int lo_q[2] = {0, 0};         // first own key the lane's queries see
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb) {
-        int qi = wrow0 + 32 * cb + lc;
-        qi = qi < S ? qi : S - 1;
+        const int qi_raw = wrow0 + 32 * cb + lc;
+        const int qi = qi_raw < S ? qi_raw : S - 1;
         if (row_lo) lo_q[cb] = row_lo[qi];
         const size_t row = (t0 + qi) * Hq + h;
 #pragma unroll
@@ -159,9 +129,24 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
 #endif
             gf[cb][t] = *reinterpret_cast<const u32x4*>(d_o + row * HD + 8 * lg + 16 * t);
         }
+        float ds = 0.f;       // the lane's half of the row's head elements, the partner lane's added below
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const u32x4 ow = *reinterpret_cast<const u32x4*>(o + row * HD + 8 * lg + 16 * t);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                ds = fmaf(__uint_as_float(ow[i] << 16), __uint_as_float(gf[cb][t][i] << 16), ds);
+                ds = fmaf(__uint_as_float(ow[i] & 0xffff0000u), __uint_as_float(gf[cb][t][i] & 0xffff0000u), ds);
+            }
+        }
+        ds += partner(ds);
         const size_t st = sp.stat_b + h * sp.stat_h + qi;
-        nl2[cb] = nlse2[st];
-        ndl[cb] = ndelta[st];
+        nl2[cb] = -lse[st] * CART_LOG2E;
+        ndl[cb] = -ds;
+        if (lg == 0 && qi_raw < S) {
+            nlse2[st] = nl2[cb];
+            ndelta[st] = ndl[cb];
+        }
     }
     f32x16 acc[4][2];   // dQ^T: [head-element block][query block]
 #pragma unroll
@@ -952,21 +937,18 @@ int launch_attn_bwd_mfma(const cart_attn_desc& d, float scale, const void* q, co
                  *V = static_cast<const bf16_t*>(v), *ZK = static_cast<const bf16_t*>(zk),
                  *ZV = static_cast<const bf16_t*>(zv), *DO = static_cast<const bf16_t*>(d_o);
     const float c = scale * CART_LOG2E;
-    const long rows = tokens * d.Hq;
-    trace_begin(st);   // kernel order: prep, dq, dk, dv, dz reduce (k, v)
-    hipLaunchKernelGGL(attn_bwd_prep_kernel, dim3(static_cast<unsigned>((rows + 15) / 16)), dim3(256), 0, st,
-                       static_cast<const bf16_t*>(o), DO, lse, delta, lse2, tokens, d.S, d.Hq, cu ? 1 : 0);
-    trace_mark(st);
+    const bf16_t* O = static_cast<const bf16_t*>(o);
+    trace_begin(st);   // kernel order: dq (+ row statistics), dk, dv, dz reduce (k, v)
     if (row_lo) {
         const long nQt = (T + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
         hipLaunchKernelGGL(attn_bwd_dq_kernel, dim3(static_cast<unsigned>(nQt * d.Hq)), dim3(256), 0, st, Q, K, V, ZK,
-                           ZV, DO, lse2, delta, static_cast<bf16_t*>(dq), nullptr, row_lo, T, 1, T, d.Hq, d.Hkv, d.P,
-                           c, scale);
+                           ZV, O, DO, lse, lse2, delta, static_cast<bf16_t*>(dq), nullptr, row_lo, T, 1, T, d.Hq,
+                           d.Hkv, d.P, c, scale);
     } else {
         const long nQt = (d.S + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
         hipLaunchKernelGGL(attn_bwd_dq_kernel, dim3(static_cast<unsigned>(nQt * d.B * d.Hq)), dim3(256), 0, st, Q, K, V,
-                           ZK, ZV, DO, lse2, delta, static_cast<bf16_t*>(dq), cu, nullptr, T, d.B, d.S, d.Hq, d.Hkv,
-                           d.P, c, scale);
+                           ZK, ZV, O, DO, lse, lse2, delta, static_cast<bf16_t*>(dq), cu, nullptr, T, d.B, d.S,
+                           d.Hq, d.Hkv, d.P, c, scale);
     }
     trace_mark(st);
     const long nPb = (d.P + BWD_WG_ROWS - 1) / BWD_WG_ROWS, nOb = (d.S + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
