@@ -10,9 +10,9 @@
 //   dk kernel   (keys stationary):    S = Q K^T,  dP = dO V^T,   dK^T += Q^T dS
 //   dv kernel   (keys stationary):    S = Q K^T,                 dV^T += dO^T P
 // with P = exp(scale S - lse), dS = P (dP - delta), delta_i = dO_i . O_i.  Nothing uses atomics:
-// a key-stationary workgroup owns its keys' gradients for one sequence; prefix-slot gradients
-// are written per sequence as fp32 partials and summed over the batch by dz_reduce_kernel in a
-// fixed order, so results are bit-reproducible.
+// a key-stationary workgroup owns its keys' gradients over the token rows it streams; prefix-slot
+// gradients are written as fp32 partials, one per chunk of token rows, and summed by
+// dz_reduce_kernel in a fixed order, so results are bit-reproducible.
 #include "attn_mfma.h"
 
 namespace cart {
@@ -29,7 +29,13 @@ constexpr int BWD_TILE = 64;                      // rows per LDS tile
 constexpr int BWD_TILE_B = BWD_TILE * ROW_B;
 constexpr int BWD_NBUF = 3;
 constexpr int BWD_WG_ROWS = 256;                  // stationary rows per workgroup (4 x 64)
-constexpr int BWD_PACK_CHUNK = 2048;              // packed layout: tokens per prefix-gradient partial
+// Prefix-slot gradients: the token rows are streamed in chunks, one fp32 partial per chunk.  The
+// chunk is sized to give about this many prefix workgroups (few, long streams and few partials,
+// yet enough workgroups to balance the chip), but never below 2048 rows.
+#ifndef BWD_PREFIX_WGS
+#define BWD_PREFIX_WGS 512
+#endif
+constexpr int BWD_MIN_CHUNK = 2048;
 
 // store a transposed accumulator block set: lane owns output row `row_ptr` (nullptr: skip),
 // register r of block db holds column 32 db + 8 (r/4) + 4 g + r%4
@@ -140,10 +146,10 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
             }
         }
         ds += partner(ds);
-        const size_t st = sp.stat_b + h * sp.stat_h + qi;
-        nl2[cb] = -lse[st] * CART_LOG2E;
+        nl2[cb] = -lse[sp.stat_b + h * sp.stat_h + qi] * CART_LOG2E;
         ndl[cb] = -ds;
-        if (lg == 0 && qi_raw < S) {
+        if (lg == 0 && qi_raw < S) {      // internal layout [Hq][all token rows], both input layouts
+            const size_t st = static_cast<size_t>(h) * n_tok + t0 + qi;
             nlse2[st] = nl2[cb];
             ndelta[st] = ndl[cb];
         }
@@ -409,8 +415,8 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
     const bf16_t* __restrict__ zk, const bf16_t* __restrict__ zv, const bf16_t* __restrict__ d_o,
     const float* __restrict__ nlse2, const float* __restrict__ ndelta, bf16_t* __restrict__ out_own,
-    float* __restrict__ part, const int32_t* __restrict__ cu, int n_tok, int B, int Smax, int Hq, int Hkv,
-    int P, float c, float scale) {
+    float* __restrict__ part, const int32_t* __restrict__ cu, int n_tok, int chunk, int B, int Smax, int Hq,
+    int Hkv, int P, float c, float scale) {
     // dV fetches every fragment a whole iteration ahead: a tile is read in two consecutive tile
     // iterations, three buffers.  dK fetches the transposed fragments of the previous sub-tile a
     // few groups ahead of their use, i.e. one tile iteration later: four buffers.
@@ -421,36 +427,29 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
     const int G = Hq / Hkv;
     const int nPb = (P + BWD_WG_ROWS - 1) / BWD_WG_ROWS, nOb = (Smax + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
     const int nKb = nPb + nOb;
-    // workgroup -> (sequence, key block, KV head): KV head fastest (one head per XCD with 8 KV
-    // heads); the key blocks of one sequence run together and share its Q / dO stream in L2.
-    // Packed layout: a prefix key sees every token whatever sequence it belongs to, so the prefix
-    // blocks stream the packed rows in chunks of BWD_PACK_CHUNK tokens (one partial dZ per chunk,
-    // not per sequence) and come first; the own-key blocks of the sequences follow.
+    // workgroup -> (KV head, key block, chunk of token rows | sequence): KV head fastest (one head
+    // per XCD with 8 KV heads).  A prefix key sees every token whatever sequence it belongs to, so
+    // the prefix blocks stream all token rows (n_tok of them, [B,S] or packed alike) in chunks,
+    // one partial dZ per chunk; the blocks of one chunk run together and share its Q / dO stream
+    // in L2.  They come first (the long ones); the own-key blocks of the sequences follow.
     int id = blockIdx.x;
     const int hk = id % Hkv; id /= Hkv;
     int kb_, b_;
     SeqSpan sp;
-    if (cu) {
-        const int nChunk = (n_tok + BWD_PACK_CHUNK - 1) / BWD_PACK_CHUNK;
-        if (id < nPb * nChunk) {
-            kb_ = id % nPb;
-            b_ = id / nPb;
-            sp.t0 = static_cast<size_t>(b_) * BWD_PACK_CHUNK;
-            sp.len = min(BWD_PACK_CHUNK, n_tok - b_ * BWD_PACK_CHUNK);
-            sp.stat_b = sp.t0;
-            sp.stat_h = static_cast<size_t>(n_tok);
-        } else {
-            id -= nPb * nChunk;
-            kb_ = nPb + id % nOb;
-            b_ = id / nOb;
-            sp = seq_span(cu, b_, n_tok, Smax, Hq);
-        }
+    const int nChunk = (n_tok + chunk - 1) / chunk;
+    if (id < nPb * nChunk) {
+        kb_ = id % nPb;
+        b_ = id / nPb;
+        sp.t0 = static_cast<size_t>(b_) * chunk;
+        sp.len = min(chunk, n_tok - b_ * chunk);
+        sp.stat_b = sp.stat_h = 0;      // (not used here: the statistics are indexed by token row)
     } else {
-        kb_ = id % nKb;
-        b_ = id / nKb;
+        id -= nPb * nChunk;
+        kb_ = nPb + id % nOb;
+        b_ = id / nOb;
         sp = seq_span(cu, b_, n_tok, Smax, Hq);
     }
-    const int kb = kb_, b = b_;      // for a prefix block of the packed layout b is the chunk
+    const int kb = kb_, b = b_;      // for a prefix block b is the chunk
     const bool pre = kb < nPb;
     const int key0 = (pre ? kb : kb - nPb) * BWD_WG_ROWS;
     const int S = sp.len;
@@ -537,7 +536,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
         ts.gb = g_c + base;
         ts.lim = S - 1 - ts.i0;
         // wavefronts 0 / 2 fetch the rows' -lse2, 1 / 3 their -delta (twice each: no branch)
-        ts.rb = reinterpret_cast<const char*>(((wv & 1) ? ndelta : nlse2) + sp.stat_b + h * sp.stat_h + ts.i0);
+        ts.rb = reinterpret_cast<const char*>(((wv & 1) ? ndelta : nlse2) + static_cast<size_t>(h) * n_tok + t0 + ts.i0);
         ts.lds_q = lds_addr(sm.t[buf].q);
         ts.lds_g = lds_addr(sm.t[buf].g);
         ts.lds_r = lds_addr((wv & 1) ? sm.ndl[buf] : sm.nl2[buf]);
@@ -901,13 +900,24 @@ bool attn_mfma_bwd_supported(const cart_attn_desc& d) { return d.dtype == CART_B
 
 static size_t r256(size_t n) { return (n + 255) & ~static_cast<size_t>(255); }
 
+// token rows per prefix-gradient partial, and the number of partials
+static int bwd_chunk(const cart_attn_desc& d, long tokens, int* n_part) {
+    const long nPb = (d.P + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
+    long n = nPb > 0 ? (BWD_PREFIX_WGS + nPb * d.Hkv - 1) / (nPb * d.Hkv) : 1;
+    const long most = (tokens + BWD_MIN_CHUNK - 1) / BWD_MIN_CHUNK;
+    n = n < 1 ? 1 : (n > most ? most : n);
+    const long chunk = (((tokens + n - 1) / n) + BWD_TILE - 1) / BWD_TILE * BWD_TILE;
+    *n_part = static_cast<int>((tokens + chunk - 1) / chunk);
+    return static_cast<int>(chunk);
+}
+
 // beyond the delta array: lse2 (one value per token and head) and the two dZ partial buffers
-// [n_part,Hkv,P,128].  Batched layout (tokens < 0): one partial per sequence.  Packed layout:
-// tokens = the packed row count, one partial per BWD_PACK_CHUNK rows, + the row_lo array.
+// [n_part,Hkv,P,128]; packed layout (tokens >= 0 = the packed row count): + the row_lo array.
 size_t attn_mfma_bwd_workspace(const cart_attn_desc& d, long tokens) {
     const bool packed = tokens >= 0;
-    const long n_part = packed ? (tokens + BWD_PACK_CHUNK - 1) / BWD_PACK_CHUNK : d.B;
     if (!packed) tokens = static_cast<long>(d.B) * d.S;
+    int n_part;
+    bwd_chunk(d, tokens, &n_part);
     const size_t rows = r256(static_cast<size_t>(tokens) * d.Hq * sizeof(float));
     const size_t part = r256(static_cast<size_t>(n_part) * d.Hkv * d.P * HD * sizeof(float));
     return rows + 2 * part + (packed ? r256(static_cast<size_t>(tokens) * sizeof(int32_t)) : 0);
@@ -919,7 +929,9 @@ int launch_attn_bwd_mfma(const cart_attn_desc& d, float scale, const void* q, co
                          float* dzk, float* dzv, void* ws, hipStream_t st, const int32_t* cu, int T) {
     const long tokens = cu ? T : static_cast<long>(d.B) * d.S;
     const size_t rows_b = r256(static_cast<size_t>(tokens) * d.Hq * sizeof(float));
-    const int n_part = cu ? static_cast<int>((tokens + BWD_PACK_CHUNK - 1) / BWD_PACK_CHUNK) : d.B;
+    int n_part;
+    const int chunk = bwd_chunk(d, tokens, &n_part);
+    const int n_tok = static_cast<int>(tokens);
     const size_t part_b = r256(static_cast<size_t>(n_part) * d.Hkv * d.P * HD * sizeof(float));
     char* w = static_cast<char*>(ws);
     float* delta = reinterpret_cast<float*>(w);
@@ -942,22 +954,22 @@ int launch_attn_bwd_mfma(const cart_attn_desc& d, float scale, const void* q, co
     if (row_lo) {
         const long nQt = (T + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
         hipLaunchKernelGGL(attn_bwd_dq_kernel, dim3(static_cast<unsigned>(nQt * d.Hq)), dim3(256), 0, st, Q, K, V, ZK,
-                           ZV, O, DO, lse, lse2, delta, static_cast<bf16_t*>(dq), nullptr, row_lo, T, 1, T, d.Hq,
-                           d.Hkv, d.P, c, scale);
+                           ZV, O, DO, lse, lse2, delta, static_cast<bf16_t*>(dq), nullptr, row_lo, n_tok, 1, n_tok,
+                           d.Hq, d.Hkv, d.P, c, scale);
     } else {
         const long nQt = (d.S + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
         hipLaunchKernelGGL(attn_bwd_dq_kernel, dim3(static_cast<unsigned>(nQt * d.B * d.Hq)), dim3(256), 0, st, Q, K, V,
-                           ZK, ZV, O, DO, lse, lse2, delta, static_cast<bf16_t*>(dq), cu, nullptr, T, d.B, d.S,
+                           ZK, ZV, O, DO, lse, lse2, delta, static_cast<bf16_t*>(dq), cu, nullptr, n_tok, d.B, d.S,
                            d.Hq, d.Hkv, d.P, c, scale);
     }
     trace_mark(st);
     const long nPb = (d.P + BWD_WG_ROWS - 1) / BWD_WG_ROWS, nOb = (d.S + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
     const unsigned kgrid = static_cast<unsigned>((nPb * n_part + nOb * d.B) * d.Hkv);
     hipLaunchKernelGGL(attn_bwd_kstat_kernel<true>, dim3(kgrid), dim3(256), 0, st, Q, K, V, ZK, ZV, DO, lse2,
-                       delta, static_cast<bf16_t*>(dk), part_k, cu, T, d.B, d.S, d.Hq, d.Hkv, d.P, c, scale);
+                       delta, static_cast<bf16_t*>(dk), part_k, cu, n_tok, chunk, d.B, d.S, d.Hq, d.Hkv, d.P, c, scale);
     trace_mark(st);
     hipLaunchKernelGGL(attn_bwd_kstat_kernel<false>, dim3(kgrid), dim3(256), 0, st, Q, K, V, ZK, ZV, DO, lse2,
-                       delta, static_cast<bf16_t*>(dv), part_v, cu, T, d.B, d.S, d.Hq, d.Hkv, d.P, c, scale);
+                       delta, static_cast<bf16_t*>(dv), part_v, cu, n_tok, chunk, d.B, d.S, d.Hq, d.Hkv, d.P, c, scale);
     trace_mark(st);
     if (d.P > 0) {
         const long n4 = static_cast<long>(d.Hkv) * d.P * HD / 4;
