@@ -400,9 +400,10 @@ __global__ __launch_bounds__(256, 2) void decode_fused_kernel(
 
 // o[b,h,:] = sum_i w_i part_o[i] / sum_i w_i, w_i = exp(lse_i - max lse), over the partial slots
 // that exist for the request: the n_ps prefix parts, the chunks of its private cartridge (when it
-// has one), the chunks of its own rows (own_chunk_keys(len) keys each).  One wavefront per (b, h): lane i holds
-// slot i's lse and weight (up to 64 slots, else a serial loop), then every lane accumulates its
-// two head elements over the slots with the loads of four slots in flight.
+// has one), the chunks of its own rows (own_chunk_keys(len) keys each).  One wavefront per
+// (b, h), the slots in groups of 64: lane i holds the lse and the weight of the group's slot i,
+// then every lane accumulates its two head elements over the group's slots with the loads of
+// eight slots in flight.
 __global__ __launch_bounds__(256) void decode_merge_kernel(const float* __restrict__ part_o,
                                                            const float* __restrict__ part_l,
                                                            const int32_t* __restrict__ cu,
@@ -421,47 +422,44 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(const float* __restri
     const int n = n_ps + n_cc + n_oc;
     auto valid = [&](int i) { return i < n_ps || (i < n_ps + n_cc ? i - n_ps < priv : i - n_ps - n_cc < own); };
     const size_t stride = static_cast<size_t>(B) * Hq;
-    float wsum = 0.f, a0 = 0.f, a1 = 0.f, m;
-    if (n <= 64) {
-        const float li = (lane < n && valid(lane)) ? part_l[lane * stride + row] : -3.0e38f;
-        m = wave_max(li);
-        const float wi = (lane < n && valid(lane)) ? __expf(li - m) : 0.f;
-        wsum = wave_sum(wi);
+    // slots in groups of 64: lane i holds the lse and the weight of slot g0 + i
+    float m = -3.0e38f;
+    for (int g0 = 0; g0 < n; g0 += 64) {
+        const int i = g0 + lane;
+        if (i < n && valid(i)) m = fmaxf(m, part_l[i * stride + row]);
+    }
+    m = wave_max(m);
+    float wsum = 0.f, a0 = 0.f, a1 = 0.f;
+    for (int g0 = 0; g0 < n; g0 += 64) {
+        const int cnt = min(64, n - g0);
+        const bool mine = lane < cnt && valid(g0 + lane);
+        const float wi = mine ? __expf(part_l[(g0 + lane) * stride + row] - m) : 0.f;
+        wsum += wi;
         int i = 0;
-        for (; i + 4 <= n; i += 4) {
-            float2 x[4];
+        for (; i + 8 <= cnt; i += 8) {
+            float2 x[8];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < 8; ++j) {
                 x[j] = float2{0.f, 0.f};
-                if (valid(i + j)) x[j] = *reinterpret_cast<const float2*>(part_o + ((i + j) * stride + row) * HD + 2 * lane);
+                if (valid(g0 + i + j))
+                    x[j] = *reinterpret_cast<const float2*>(part_o + ((g0 + i + j) * stride + row) * HD + 2 * lane);
             }
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < 8; ++j) {
                 const float w = __shfl(wi, i + j);
                 a0 = fmaf(w, x[j].x, a0);
                 a1 = fmaf(w, x[j].y, a1);
             }
         }
-        for (; i < n; ++i) {
-            if (!valid(i)) continue;
+        for (; i < cnt; ++i) {
+            if (!valid(g0 + i)) continue;
             const float w = __shfl(wi, i);
-            const float2 x = *reinterpret_cast<const float2*>(part_o + (i * stride + row) * HD + 2 * lane);
-            a0 = fmaf(w, x.x, a0);
-            a1 = fmaf(w, x.y, a1);
-        }
-    } else {
-        m = -3.0e38f;
-        for (int i = 0; i < n; ++i)
-            if (valid(i)) m = fmaxf(m, part_l[i * stride + row]);
-        for (int i = 0; i < n; ++i) {
-            if (!valid(i)) continue;
-            const float w = __expf(part_l[i * stride + row] - m);
-            const float2 x = *reinterpret_cast<const float2*>(part_o + (i * stride + row) * HD + 2 * lane);
-            wsum += w;
+            const float2 x = *reinterpret_cast<const float2*>(part_o + ((g0 + i) * stride + row) * HD + 2 * lane);
             a0 = fmaf(w, x.x, a0);
             a1 = fmaf(w, x.y, a1);
         }
     }
+    wsum = wave_sum(wsum);
     const float inv = 1.f / wsum;
     *reinterpret_cast<uint32_t*>(o + row * HD + 2 * lane) = pack_bf16x2(a0 * inv, a1 * inv);
     if (lane == 0 && lse) lse[row] = m + __logf(wsum);
