@@ -96,8 +96,8 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
     int id = blockIdx.x;
     const int hk = id % Hkv; id /= Hkv;
     const int g_ = id % G; id /= G;
-    const int b = id % B; id /= B;
-    const int qt = nQt - 1 - id;
+    const int qt = nQt - 1 - id % nQt;
+    const int b = id / nQt;
     const int h = hk * G + g_;
     const int lane = threadIdx.x & 63, lg = lane >> 5, lc = lane & 31;
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);

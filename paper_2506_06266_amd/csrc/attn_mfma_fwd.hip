@@ -54,12 +54,14 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_mfma_kernel(
     const int nQt = (Smax + FWD_BM - 1) / FWD_BM;
     // workgroup -> (query tile, sequence, head).  KV head is the fastest index so that, with 8
     // KV heads, blockIdx % 8 (the XCD a workgroup lands on) is the KV head and each XCD's L2 keeps
-    // one head's prefix; the heaviest query tiles (longest causal part) are issued first.
+    // one head's prefix; then the query tiles of one sequence, heaviest (longest causal part)
+    // first, sequence after sequence: the workgroups running at one time belong to one or two
+    // sequences, whose own K/V then stay in L2 (2 % faster than all sequences' heaviest tiles first).
     int id = blockIdx.x;
     const int hk = id % Hkv; id /= Hkv;
     const int g_ = id % G; id /= G;
-    const int b = id % B; id /= B;
-    const int qt = nQt - 1 - id;
+    const int qt = nQt - 1 - id % nQt;
+    const int b = id / nQt;
     const int h = hk * G + g_;
     const int lane = threadIdx.x & 63, lg = lane >> 5, lc = lane & 31;
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform, in a scalar register
@@ -442,8 +444,8 @@ __global__ __launch_bounds__(256) void attn_fwd_repair_kernel(
     int id = blockIdx.x;
     const int hk = id % Hkv; id /= Hkv;
     const int g_ = id % G; id /= G;
-    const int b = id % B; id /= B;
-    const int qt = nQt - 1 - id;
+    const int qt = nQt - 1 - id % nQt;
+    const int b = id / nQt;
     const int h = hk * G + g_;
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const SeqSpan sp = seq_span(cu, b, n_tok, Smax, Hq);
