@@ -29,6 +29,33 @@ __device__ __forceinline__ void static_for(F&& f) {
     static_for_impl(static_cast<F&&>(f), std::make_integer_sequence<int, N>{});
 }
 
+// Masking without compares: entry r of a score block (D row 8 (r/4) + r%4 + 4 g, g folded into
+// thr by the caller) is hidden when its row exceeds thr (mask_above) or lies below it
+// (mask_below).  bound_r = (thr - row + 1/2) * 1e30 is far above every score where the entry is
+// visible and far below where it is hidden, so x = min(x, bound_r) does the job in two plain
+// vector instructions per entry, with no condition registers between them (the compare / select
+// form goes through scalar registers and costs several times more).  A hidden entry ends up at
+// -5e29 or below: its exponential is an exact 0.
+__device__ __forceinline__ float vmin_raw(float a, float b) {
+    float r;
+    asm("v_min_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+template <typename V16>
+__device__ __forceinline__ void mask_above(V16& x, int thr) {
+    const int t = min(max(thr, -64), 64);
+    const float tf = fmaf(static_cast<float>(t), 1.0e30f, 0.5e30f);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) x[r] = vmin_raw(x[r], tf - static_cast<float>(8 * (r >> 2) + (r & 3)) * 1.0e30f);
+}
+template <typename V16>
+__device__ __forceinline__ void mask_below(V16& x, int thr) {
+    const int t = min(max(thr, -64), 64);
+    const float tf = fmaf(static_cast<float>(-t), 1.0e30f, 0.5e30f);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) x[r] = vmin_raw(x[r], tf + static_cast<float>(8 * (r >> 2) + (r & 3)) * 1.0e30f);
+}
+
 // Rows of sequence b, and where the per-row statistics (lse, delta) of its heads live: the value
 // of token i of head h is at stat_b + h * stat_h + i.
 //   batched layout (cu == nullptr): rows b*S .. b*S+S-1 of [B,S,...]; statistics [B,Hq,S]

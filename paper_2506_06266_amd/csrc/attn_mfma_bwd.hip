@@ -219,16 +219,8 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
     };
     // hidden entries of query block cb in the scores of the sub-tile whose first key is j0
     auto mask1 = [&](f32x16& x, int cb, bool pre, int j0) __attribute__((always_inline)) {
-        const int thr = (pre ? P - 1 : wrow0 + 32 * cb + lc) - j0 - 4 * lg;
-#pragma unroll
-        for (int r = 0; r < 16; ++r)
-            if (8 * (r >> 2) + (r & 3) > thr) x[r] = NEG_BIG;
-        if (row_lo && !pre) {
-            const int tlo = lo_q[cb] - j0 - 4 * lg;
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-                if (8 * (r >> 2) + (r & 3) < tlo) x[r] = NEG_BIG;
-        }
+        mask_above(x, (pre ? P - 1 : wrow0 + 32 * cb + lc) - j0 - 4 * lg);
+        if (row_lo && !pre) mask_below(x, lo_q[cb] - j0 - 4 * lg);
     };
 
     // per-lane LDS addresses: row-wise K fragments (V: + V_OFF) of the tile of sub-tile u+1,
@@ -565,13 +557,8 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
     // a query row of the sub-tile starting at token i0 is hidden from a key when it precedes it
     // (own keys) or lies past the end of the sequence (clamped tile rows)
     auto mask1 = [&](f32x16& x, int kc, int i0) __attribute__((always_inline)) {
-        const int lo = (pre ? 0 : wkey0 + 32 * kc + lc) - i0 - 4 * lg;
-        const int hi = S - i0 - 4 * lg;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int rr = 8 * (r >> 2) + (r & 3);
-            if (rr < lo || rr >= hi) x[r] = NEG_BIG;
-        }
+        mask_below(x, (pre ? 0 : wkey0 + 32 * kc + lc) - i0 - 4 * lg);
+        mask_above(x, S - 1 - i0 - 4 * lg);
     };
 
     // Per-lane LDS addresses of the fragments, complete except for compile-time offsets; they

@@ -179,21 +179,14 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_mfma_kernel(
         if (n < 4) dma16(ts.kb, voff, ts.lds_k + r0 * ROW_B);
         else       dma16(ts.vb, voff, ts.lds_v + r0 * ROW_B);
     };
-    // hidden entries of the scores of the sub-tile whose first key is j0 (prefix or own) -> NEG_BIG
+    // hidden entries of the scores of the sub-tile whose first key is j0 (prefix or own) -> very negative
     auto mask = [&](f32x16 (&x)[2], bool pre, int j0) __attribute__((always_inline)) {
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb) {
             // key j0 + d_row(r, lg) is hidden when it exceeds the lane's last visible key
-            const int thr = (pre ? P - 1 : wrow0 + 32 * cb + lc) - j0 - 4 * lg;
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-                if (8 * (r >> 2) + (r & 3) > thr) x[cb][r] = NEG_BIG;
-            if (row_lo && !pre) {           // ... or precedes the first key of the query's sequence
-                const int tlo = lo_q[cb] - j0 - 4 * lg;
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    if (8 * (r >> 2) + (r & 3) < tlo) x[cb][r] = NEG_BIG;
-            }
+            mask_above(x[cb], (pre ? P - 1 : wrow0 + 32 * cb + lc) - j0 - 4 * lg);
+            // ... or precedes the first key of the query's sequence
+            if (row_lo && !pre) mask_below(x[cb], lo_q[cb] - j0 - 4 * lg);
         }
     };
 
