@@ -33,7 +33,7 @@ constexpr int BWD_WG_ROWS = 256;                  // stationary rows per workgro
 // chunk is sized to give about this many prefix workgroups (few, long streams and few partials,
 // yet enough workgroups to balance the chip), but never below 2048 rows.
 #ifndef BWD_PREFIX_WGS
-#define BWD_PREFIX_WGS 512
+#define BWD_PREFIX_WGS 256
 #endif
 constexpr int BWD_MIN_CHUNK = 2048;
 
