@@ -154,6 +154,13 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
             ndelta[st] = ndl[cb];
         }
     }
+    // -delta of the lane's queries in all 16 registers of a set: the dP^T products start from it
+    // (their init value), so that dP^T - delta needs no instruction of its own
+    f32x16 ndi[2];
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) ndi[cb][r] = ndl[cb];
     f32x16 acc[4][2];   // dQ^T: [head-element block][query block]
 #pragma unroll
     for (int db = 0; db < 4; ++db)
@@ -277,9 +284,9 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
             } else {
                 const int j = g - 16, t8 = j >> 2, which = j & 3;   // block 1 first: its results are read first
                 if (which == 0)      { if (t8 == 0) mma_vd_zero(x1, ka[0], qf[1][0]); else mma_vd(x1, ka[t8], qf[1][t8]); }
-                else if (which == 1) { if (t8 == 0) mma_vd_zero(y1, va[0], gf[1][0]); else mma_vd(y1, va[t8], gf[1][t8]); }
+                else if (which == 1) { if (t8 == 0) mma_vd_first(y1, va[0], gf[1][0], ndi[1]); else mma_vd(y1, va[t8], gf[1][t8]); }
                 else if (which == 2) { if (t8 == 0) mma_vd_zero(x0out, ka[0], qf[0][0]); else mma_vd(x0out, ka[t8], qf[0][t8]); }
-                else                 { if (t8 == 0) mma_vd_zero(y0out, va[0], gf[0][0]); else mma_vd(y0out, va[t8], gf[0][t8]); }
+                else                 { if (t8 == 0) mma_vd_first(y0out, va[0], gf[0][0], ndi[0]); else mma_vd(y0out, va[t8], gf[0][t8]); }
             }
             __builtin_amdgcn_sched_barrier(0);
             if (hb == 0 && g >= 16 && g < 24) dma_piece(ts, g - 16);
@@ -295,12 +302,12 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
             if (g >= 8 && g <= 36 && ((g - 8) & 3) == 0) va[(g - 8) >> 2] = ld_v((g - 8) >> 2, hb ? 0 : 1);
             // vector ALU: block 1 element g (groups 0-15), block 0 element (g-16)/2 (even groups after)
             if (g < 16) {
-                w1[g] = fast_exp2(CART_PRESCALE ? x1[g] + nl2[1] : fmaf(x1[g], c, nl2[1])) * (y1[g] + ndl[1]);
+                w1[g] = fast_exp2(CART_PRESCALE ? x1[g] + nl2[1] : fmaf(x1[g], c, nl2[1])) * y1[g];
                 if (g >= 2 && !(g & 1)) dn[1][(g - 2) >> 3][((g - 2) & 7) >> 1] = pack_bf16x2(w1[g - 2], w1[g - 1]);
             } else if (!(g & 1)) {
                 const int r = (g - 16) >> 1;
                 if (r == 0) dn[1][1][3] = pack_bf16x2(w1[14], w1[15]);
-                w0[r] = fast_exp2(CART_PRESCALE ? x0in[r] + nl2[0] : fmaf(x0in[r], c, nl2[0])) * (y0in[r] + ndl[0]);
+                w0[r] = fast_exp2(CART_PRESCALE ? x0in[r] + nl2[0] : fmaf(x0in[r], c, nl2[0])) * y0in[r];
                 if (r >= 2 && !(r & 1)) dn[0][(r - 2) >> 3][((r - 2) & 7) >> 1] = pack_bf16x2(w0[r - 2], w0[r - 1]);
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -328,7 +335,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
 #pragma unroll
         for (int t8 = 0; t8 < 8; ++t8) {
             if (t8 == 0) { mma_vd_zero(x0a, ka[0], qf[0][0]); mma_vd_zero(x1, ka[0], qf[1][0]);
-                           mma_vd_zero(y0a, va[0], gf[0][0]); mma_vd_zero(y1, va[0], gf[1][0]); }
+                           mma_vd_first(y0a, va[0], gf[0][0], ndi[0]); mma_vd_first(y1, va[0], gf[1][0], ndi[1]); }
             else         { mma_vd(x0a, ka[t8], qf[0][t8]); mma_vd(x1, ka[t8], qf[1][t8]);
                            mma_vd(y0a, va[t8], gf[0][t8]); mma_vd(y1, va[t8], gf[1][t8]); }
         }
