@@ -236,7 +236,7 @@ def main() -> int:
     # HBM bytes per launch of these kernels at this workload, from the rocprofv3 --pmc runs of
     # this command (FETCH_SIZE x 2.0, its calibration factor against a plain copy, + WRITE_SIZE);
     # the counters cannot be read from inside the process, so the figures are carried here
-    hbm_bytes = {"dq": 1.250e9 + 0.277e9, "dk": 2.629e9 + 0.138e9, "dv": 2.525e9 + 0.136e9}
+    hbm_bytes = {"dq": 1.250e9 + 0.277e9, "dk": 2.623e9 + 0.102e9, "dv": 2.521e9 + 0.101e9}
     dom = max(("dq", "dk", "dv"), key=lambda n: k_ms[n])
     per_pair = {"dq": 6, "dk": 6, "dv": 4}[dom] * acfg.D
     dom_tflops = pairs * per_pair / (k_ms[dom] * 1e-3) / 1e12
