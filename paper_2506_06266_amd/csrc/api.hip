@@ -312,6 +312,6 @@ const char* cart_status_str(cart_status s) {
     return "unknown status";
 }
 
-int cart_version(void) { return 100; }
+int cart_version(void) { return 140; }   // 1.4: + composed decode, teacher top-k, loss modes, packed batches
 
 }  // extern "C"
