@@ -102,7 +102,7 @@ typedef struct {
 #define CART_MAX_SEGMENTS 8
 
 /* Decode step over composed cartridges (Sec. 5.4) and / or one cartridge per request (the
- * serving protocol of App. B's throughput measurement). */
+ * serving protocol of App. A.3, "Throughput measurement details"). */
 typedef struct {
     int32_t B;                  /* requests, >= 1 */
     int32_t Hq, Hkv, D;         /* as in cart_attn_desc */
@@ -115,8 +115,10 @@ typedef struct {
     float softmax_scale;        /* 0 selects 1/sqrt(D) */
 } cart_decode_composed_desc;
 
-/* A packed batch of sequences of different lengths for cart_attn_varlen_fwd / _bwd (App. A.1:
- * Self-Study conversations are short and ragged; they are trained on concatenated, not padded). */
+/* A packed batch of sequences of different lengths for cart_attn_varlen_fwd / _bwd (the
+ * training batches of Fig. "Scaling Self-Study compute" hold 64 conversations of at most 1024
+ * tokens; the paper does not say how they are laid out -- concatenating them instead of padding
+ * is this library's choice). */
 typedef struct {
     int32_t T;              /* packed rows = sum of the sequence lengths, >= 1 */
     int32_t B;              /* sequences, >= 1 */

@@ -15,7 +15,9 @@ What each function follows (arxiv 2506.06266):
   trains Z by back-propagating into the key and value vectors with the model
   frozen, so dZ sums every query of every sequence in the batch.
   attn_varlen_fwd / attn_varlen_bwd -- the same over a packed batch of
-  sequences of different lengths (the ragged Self-Study batches of App. A.1).
+  sequences of different lengths (Fig. "Scaling Self-Study compute" trains on batches
+  of 64 conversations of at most 1024 tokens; the paper does not say how they are
+  laid out: packing instead of padding is this build's choice).
 * distill_kl -- Eq. 3 (Sec. 4.2), the KL divergence from the teacher's to the
   student's next-token distribution, restricted to the teacher entries that
   were recorded (App. A.2 "Training Objective": top output probabilities are
@@ -31,7 +33,7 @@ What each function follows (arxiv 2506.06266):
   cache of Sec. 3.3 (a cartridge is served as a cached prefix of length p).
   decode_composed -- the same over several cartridges concatenated (Sec. 5.4,
   composition without retraining) and / or a different cartridge per request
-  (the serving protocol of App. B's throughput measurement).
+  (the serving protocol of App. A.3, "Throughput measurement details").
 
 Readings where the paper is silent (listed in the design notes as well):
 scale is 1/sqrt(head_dim) per head unless given; query head h reads KV head
@@ -269,7 +271,7 @@ def decode(q, z_k, z_v, k_own, v_own, cu_lens, scale: Optional[float] = None):
 
 def decode_composed(q, shared, pool_k, pool_v, cart_id, k_own, v_own, cu_lens, scale: Optional[float] = None):
     """Decode step over composed cartridges (Sec. 5.4: independently trained cartridges are
-    concatenated without retraining; App. B's throughput protocol serves a different cartridge
+    concatenated without retraining; App. A.3's throughput protocol serves a different cartridge
     per request).
 
     Request b attends over, in cache order: every shared segment (z_k, z_v) of `shared`, each
@@ -326,8 +328,9 @@ def teacher_topk(logits, k: int):
 
 
 def attn_varlen_fwd(q, k_own, v_own, z_k, z_v, cu_seqlens, scale: Optional[float] = None):
-    """attn_fwd over a packed batch of sequences of different lengths (App. A.1: Self-Study
-    conversations are short and ragged; a training batch is their concatenation).
+    """attn_fwd over a packed batch of sequences of different lengths (the training batches of
+    Fig. "Scaling Self-Study compute": 64 conversations of at most 1024 tokens; the paper is silent on
+    their layout, concatenating them instead of padding is this build's choice).
 
     q [T,Hq,d]; k_own, v_own [T,Hkv,d]; sequence b owns rows cu_seqlens[b] .. cu_seqlens[b+1]-1 and
     attends over [Z ; its own rows, causally] exactly as a batch of one in attn_fwd.

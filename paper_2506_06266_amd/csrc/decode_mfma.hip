@@ -13,7 +13,7 @@
 // decode_merge_kernel combines them by their log-sum-exps.
 //
 // Composition (Sec. 5.4: cartridges trained apart are concatenated without retraining) and the
-// per-request cartridges of App. B's serving protocol use the same two kernels: the shared
+// per-request cartridges of App. A.3's serving protocol use the same two kernels: the shared
 // prefix is a list of segments, each split and run like a single cartridge (a segment is never
 // copied next to another), and a request's private cartridge is streamed like its own KV.
 #include "attn_mfma.h"
