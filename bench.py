@@ -23,6 +23,29 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "bench_step_hbm_traffic.md")
+
+
+def profiled_traffic(kernel: str, lib_version: int):
+    """HBM bytes per launch of `kernel` at the bench workload, from the committed rocprofv3 --pmc
+    summary (FETCH_SIZE and WRITE_SIZE runs of this command, scaled as the summary states), or
+    None when the summary is missing or was taken with another version of the library."""
+    try:
+        text = open(TRAFFIC_FILE).read()
+    except OSError:
+        return None
+    import re
+    m = re.search(r"library version (\d+)", text)
+    if not m or int(m.group(1)) != lib_version:
+        return None
+    for line in text.splitlines():
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) >= 5 and cells[0].startswith(kernel + " (cfg3"):
+            try:
+                return round((float(cells[3]) + float(cells[4])) * 1e9)
+            except ValueError:
+                return None
+    return None
 
 
 def attn_pairs(cfg) -> int:
@@ -200,6 +223,52 @@ def main() -> int:
     long_bytes = 2 * lg["k_own"].numel() * 2
     del lg, lg_o, lg_lse
 
+    # the same decode call with the last-level cache cold: 512 MiB written between the calls
+    flush = torch.empty(512 << 20, dtype=torch.uint8, device=dev)
+    cold = []
+    for i in range(6):
+        flush.fill_(i)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        dec_step()
+        e1.record()
+        torch.cuda.synchronize()
+        cold.append(e0.elapsed_time(e1))
+    decode_cold_ms = sorted(cold[1:])[len(cold[1:]) // 2]
+    del flush
+
+    # the Llama-3B-shaped layer (cfg2), forward and backward
+    c2 = synth.ATTN_CONFIGS["cfg2"]
+    a2 = synth.attn_inputs(c2, dev)
+    o2, lse2 = cb.cart_attn_fwd(a2["q"], a2["k_own"], a2["v_own"], a2["z_k"], a2["z_v"])
+    g2 = cb.cart_attn_bwd(a2["q"], a2["k_own"], a2["v_own"], a2["z_k"], a2["z_v"], o2, lse2, a2["d_o"])
+    ad2 = cb.attn_desc(a2["q"], a2["k_own"], c2.P)
+    ws2 = torch.empty(max(lib.cart_attn_bwd_workspace(C.byref(ad2)), lib.cart_attn_fwd_workspace(C.byref(ad2)), 16),
+                      dtype=torch.uint8, device=dev)
+    c2_fwd_ms = timed(lambda: cb.cart_attn_fwd(a2["q"], a2["k_own"], a2["v_own"], a2["z_k"], a2["z_v"], o=o2,
+                                               lse=lse2, workspace=ws2), n=10)
+    c2_bwd_ms = timed(lambda: cb.cart_attn_bwd(a2["q"], a2["k_own"], a2["v_own"], a2["z_k"], a2["z_v"], o2, lse2,
+                                               a2["d_o"], d_q=g2[0], d_k_own=g2[1], d_v_own=g2[2], d_z_k=g2[3],
+                                               d_z_v=g2[4], workspace=ws2), n=10)
+    c2_pairs = attn_pairs(c2) * c2.B * c2.Hq
+    del a2, o2, lse2, g2, ws2
+
+    # what this machine gives a kernel with nothing else to do, measured in this run: a matrix-core-only
+    # loop of the attention kernels' instruction, a 4 GiB device copy and a 4 GiB device read
+    sink = torch.zeros(64, dtype=torch.float32, device=dev)
+    peak_fl = [0.0]
+    def mfma_loop():
+        peak_fl[0] = cb.cart_calib_mfma(sink, 20000, 1)
+    mfma_ms = timed(mfma_loop, n=3)
+    peak_mfma_tflops = peak_fl[0] / mfma_ms / 1e9
+    big_a = torch.empty(4 << 30, dtype=torch.uint8, device=dev).fill_(1)
+    big_b = torch.empty_like(big_a)
+    copy_ms = timed(lambda: cb.cart_calib_copy(big_b, big_a), n=3)
+    read_ms = timed(lambda: cb.cart_calib_read(big_a, sink), n=3)
+    peak_copy_gbs = 2 * big_a.numel() / copy_ms / 1e6
+    peak_read_gbs = big_a.numel() / read_ms / 1e6
+    del big_a, big_b
+
     # one packed global batch of 64 ragged conversations (<= 1024 tokens) at the same layer shape
     pcfg = synth.PACKED_CONFIGS["cfg3_packed"]
     pk = synth.attn_packed_inputs(pcfg, dev)
@@ -230,21 +299,26 @@ def main() -> int:
     kl_gbs = kl_bytes / (part_ms["kl"] * 1e-3) / 1e9
     dec_gbs = dec_bytes / (part_ms["decode"] * 1e-3) / 1e9
 
-    # dominant kernel of the step = the slowest of the three backward kernels, priced on the
-    # contractions it must perform over every visible pair: dq and dk kernels 3 (S, dP, and dQ
-    # or dK) = 6*D flops per pair, dv kernel 2 (S, dV) = 4*D.
-    # HBM bytes per launch of these kernels at this workload, from the rocprofv3 --pmc runs of
-    # this command (FETCH_SIZE x 2.0, its calibration factor against a plain copy, + WRITE_SIZE);
-    # the counters cannot be read from inside the process, so the figures are carried here
-    hbm_bytes = {"dq": 1.250e9 + 0.277e9, "dk": 2.623e9 + 0.102e9, "dv": 2.521e9 + 0.101e9}
-    dom = max(("dq", "dk", "dv"), key=lambda n: k_ms[n])
-    per_pair = {"dq": 6, "dk": 6, "dv": 4}[dom] * acfg.D
-    dom_tflops = pairs * per_pair / (k_ms[dom] * 1e-3) / 1e12
-    roofline = {"kernel": {"dq": "attn_bwd_dq_kernel", "dk": "attn_bwd_kstat_kernel<true>",
-                           "dv": "attn_bwd_kstat_kernel<false>"}[dom],
-                "bound": "mfma", "achieved": round(dom_tflops, 1), "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(dom_tflops / PEAK_BF16_TFLOPS, 4), "traffic": hbm_bytes[dom],
-                "avg_launch_ms": round(k_ms[dom], 4)}
+    # Roofline of the step's dominant kernel, the slowest kernel of the backward call.  The
+    # call's kernels share the algorithmic work of the gradient (10*D flops per visible pair:
+    # recomputing S, then dP, dV, dQ, dK), whatever they recompute between them, so `achieved`
+    # prices the call: algorithmic flops of the backward / time of its kernels.  What the dominant
+    # kernel itself executes per second is reported beside it.
+    units = {"dq": 3, "dk": 3, "dv": 2}          # contractions each kernel performs per pair
+    dom = max(units, key=lambda n: k_ms[n])
+    bwd_kernel_ms = sum(k_ms.values())
+    bwd_alg_tflops = bwd_flop / (bwd_kernel_ms * 1e-3) / 1e12
+    dom_exec_tflops = pairs * units[dom] * 2 * acfg.D / (k_ms[dom] * 1e-3) / 1e12
+    dom_name = {"dq": "attn_bwd_dq_kernel", "dk": "attn_bwd_kstat_kernel<true>", "dv": "attn_bwd_kstat_kernel<false>"}[dom]
+    roofline = {"kernel": dom_name, "bound": "mfma", "achieved": round(bwd_alg_tflops, 1),
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(bwd_alg_tflops / PEAK_BF16_TFLOPS, 4),
+                "traffic": profiled_traffic(dom_name, lib.cart_version()),
+                "basis": "algorithmic flops of the backward call (10*D per visible pair) / time of its kernels",
+                "call_kernel_ms": round(bwd_kernel_ms, 4), "avg_launch_ms": round(k_ms[dom], 4),
+                "executed_units_per_pair": sum(units.values()), "algorithmic_units_per_pair": 5,
+                "kernel_executed_tflops": round(dom_exec_tflops, 1),
+                "kernel_executed_frac": round(dom_exec_tflops / PEAK_BF16_TFLOPS, 4),
+                "frac_of_measured_peak": round(bwd_alg_tflops / peak_mfma_tflops, 4)}
 
     out = {
         "metric": "cartridge attn fwd+bwd TFLOP/s (MFMA util) @Llama-8B shape; KL loss HBM GB/s",
@@ -257,11 +331,29 @@ def main() -> int:
                   "attn_fwd_tflops": round(fwd_flop / part_ms["attn_fwd"] / 1e9, 1),
                   "attn_bwd_tflops": round(bwd_flop / part_ms["attn_bwd"] / 1e9, 1),
                   "attn_mfma_frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4),
+                  "attn_fwd_frac": round(fwd_flop / part_ms["attn_fwd"] / 1e9 / PEAK_BF16_TFLOPS, 4),
+                  "attn_bwd_frac": round(bwd_flop / part_ms["attn_bwd"] / 1e9 / PEAK_BF16_TFLOPS, 4),
+                  "attn_frac_of_measured_peak": round(attn_tflops / peak_mfma_tflops, 4),
                   "bwd_kernel_ms": {n: round(v, 4) for n, v in k_ms.items()},
                   "kl_ms": round(part_ms["kl"], 4), "kl_gbs": round(kl_gbs, 1),
                   "kl_hbm_frac": round(kl_gbs / PEAK_HBM_GBS, 4),
                   "decode_ms": round(part_ms["decode"], 4), "decode_gbs": round(dec_gbs, 1),
-                  "decode_hbm_frac": round(dec_gbs / PEAK_HBM_GBS, 4)},
+                  "decode_hbm_frac": round(dec_gbs / PEAK_HBM_GBS, 4),
+                  "decode_cold_ms": round(decode_cold_ms, 4),
+                  "decode_cold_gbs": round(dec_bytes / decode_cold_ms / 1e6, 1),
+                  "kl_frac_of_measured_copy": round(kl_gbs / peak_copy_gbs, 4),
+                  "decode_frac_of_measured_read": round(dec_gbs / peak_read_gbs, 4),
+                  "cfg2": {"workload": "Llama-3B-shaped layer B32 S1024 Hq24 Hkv8 D128 P2048",
+                           "attn_fwd_ms": round(c2_fwd_ms, 4), "attn_bwd_ms": round(c2_bwd_ms, 4),
+                           "attn_fwd_tflops": round(c2_pairs * 4 * c2.D / c2_fwd_ms / 1e9, 1),
+                           "attn_bwd_tflops": round(c2_pairs * 10 * c2.D / c2_bwd_ms / 1e9, 1),
+                           "attn_fwd_bwd_tflops": round(c2_pairs * 14 * c2.D / (c2_fwd_ms + c2_bwd_ms) / 1e9, 1),
+                           "attn_mfma_frac": round(c2_pairs * 14 * c2.D / (c2_fwd_ms + c2_bwd_ms) / 1e9
+                                                   / PEAK_BF16_TFLOPS, 4)}},
+        "measured_peaks": {"mfma_bf16_tflops": round(peak_mfma_tflops, 1), "copy_4GiB_gbs": round(peak_copy_gbs, 1),
+                           "read_4GiB_gbs": round(peak_read_gbs, 1),
+                           "note": "plain kernels of this library timed in this run (matrix-core-only loop; "
+                                   "16-byte-per-lane copy and read of 4 GiB)"},
         "roofline": roofline,
         "next_rows": {"kl_rest_bucket_ms": round(rest_ms, 4),
                       "kl_rest_bucket_gbs": round((2 * kcfg.N * kcfg.V * 2 + kcfg.N * kcfg.K * 8) / rest_ms / 1e6, 1),
@@ -290,10 +382,15 @@ def cpu_baseline(a, acfg):
     import numpy as np
     from oracle import cartridge_oracle as orc
     try:
+        allowed = len(os.sched_getaffinity(0))
+    except AttributeError:
+        allowed = os.cpu_count() or 1
+    try:
         from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
-        cores = os.cpu_count() or 1
+        threads = allowed
+    cores = min(threads, allowed)      # the BLAS pool's threads, no more than the CPUs this process may use
     G = acfg.Hq // acfg.Hkv
     f64 = lambda t: t.detach().to("cpu").double().numpy()
     NB, NK = 4, 4                      # sequences x KV groups in the sample
@@ -306,6 +403,7 @@ def cpu_baseline(a, acfg):
     dt = time.perf_counter() - t0
     flop = attn_pairs(acfg) * NB * NK * G * 14 * acfg.D
     return {"value": round(flop / dt / 1e12, 5), "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "blas_threads": int(threads), "affinity_cpus": int(allowed),
             "sample": "cfg3 shape, 4 of 16 sequences x 16 of 32 query heads (4 KV groups), fwd+bwd, "
                       "%.1f s" % dt}
 

@@ -277,6 +277,22 @@ cart_status cart_attn_varlen_bwd(const cart_attn_varlen_desc *desc, const void *
  */
 cart_status cart_trace_events(void *const *events, int32_t count);
 
+/*
+ * cart_calib_* -- benchmark hooks (not part of the paper): plain kernels that measure what this
+ * machine gives a kernel with nothing else to do, so that a benchmark can put a rate of the hot
+ * path next to a peak measured in the same run.  The caller times them with events on `stream`.
+ *   cart_calib_mfma  a matrix-core-only loop of the bf16 instruction the attention kernels use
+ *                    (register operands, pseudo-random values), wgs_per_cu (1..8) workgroups of
+ *                    four wavefronts per CU, `iters` x 8 instructions per wavefront.  Returns the
+ *                    floating-point operations the launch performs (0 on a bad argument or a
+ *                    refused launch).  sink: 4 bytes of device memory, never written in practice.
+ *   cart_calib_copy  dst[0..bytes) = src[0..bytes), 16 bytes per lane per step (bytes % 16 == 0).
+ *   cart_calib_read  reads src[0..bytes) the same way; sink as above.
+ */
+double cart_calib_mfma(void *sink, int32_t iters, int32_t wgs_per_cu, void *stream);
+cart_status cart_calib_copy(void *dst, const void *src, size_t bytes, void *stream);
+cart_status cart_calib_read(const void *src, size_t bytes, void *sink, void *stream);
+
 const char *cart_status_str(cart_status status);
 int cart_version(void);
 

@@ -24,7 +24,8 @@ EXPORTS = ["cart_attn_fwd_workspace", "cart_attn_bwd_workspace", "cart_kl_worksp
            "cart_decode_workspace", "cart_attn_fwd", "cart_attn_bwd", "cart_distill_kl_fwd_bwd",
            "cart_decode", "cart_decode_composed_workspace", "cart_decode_composed", "cart_teacher_topk",
            "cart_attn_varlen_fwd_workspace", "cart_attn_varlen_bwd_workspace", "cart_attn_varlen_fwd",
-           "cart_attn_varlen_bwd", "cart_trace_events",
+           "cart_attn_varlen_bwd", "cart_trace_events", "cart_calib_mfma", "cart_calib_copy",
+           "cart_calib_read",
            "cart_status_str", "cart_version"]
 
 
@@ -112,6 +113,12 @@ def load() -> C.CDLL:
     lib.cart_decode_composed.argtypes = [C.POINTER(DecodeComposedDesc), vp, C.POINTER(Segment)] + [vp] * 9 + [sz, vp]
     lib.cart_trace_events.restype = C.c_int
     lib.cart_trace_events.argtypes = [C.POINTER(C.c_void_p), C.c_int32]
+    lib.cart_calib_mfma.restype = C.c_double
+    lib.cart_calib_mfma.argtypes = [vp, C.c_int32, C.c_int32, vp]
+    lib.cart_calib_copy.restype = C.c_int
+    lib.cart_calib_copy.argtypes = [vp, vp, sz, vp]
+    lib.cart_calib_read.restype = C.c_int
+    lib.cart_calib_read.argtypes = [vp, sz, vp, vp]
     lib.cart_status_str.restype, lib.cart_status_str.argtypes = C.c_char_p, [C.c_int]
     lib.cart_version.restype, lib.cart_version.argtypes = C.c_int, []
     _lib = lib
@@ -333,6 +340,24 @@ def cart_decode_composed(q, shared, pool_k, pool_v, cart_id, k_own, v_own, cu_le
 
 
 # ------------------------------------------------------------------------------------------------
+def cart_calib_mfma(sink: torch.Tensor, iters: int, wgs_per_cu: int = 1, stream=None) -> float:
+    """Enqueues the matrix-core-only loop; returns the flops the launch performs."""
+    fl = load().cart_calib_mfma(_ptr(sink), iters, wgs_per_cu, _stream(stream))
+    if fl <= 0.0:
+        raise CartridgeError(5, "cart_calib_mfma")
+    return fl
+
+
+def cart_calib_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
+    _check(load().cart_calib_copy(_ptr(dst), _ptr(src), src.numel() * src.element_size(), _stream(stream)),
+           "cart_calib_copy")
+
+
+def cart_calib_read(src: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
+    _check(load().cart_calib_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream(stream)),
+           "cart_calib_read")
+
+
 class KernelTrace:
     """HIP events recorded by the library at kernel boundaries (cart_trace_events).
 
