@@ -209,6 +209,25 @@ cart_status cart_decode(const cart_decode_desc *desc, const void *q, const void 
                         size_t workspace_bytes, void *stream);
 
 /*
+ * cart_decode_static -- cart_decode for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, same kernels and bit-identical results, but the partial results of the call live
+ * in an array inside the library (32 MiB of device memory per GPU the library runs on, held until
+ * the process ends) instead of a caller-supplied workspace; the call allocates nothing.
+ *   - bf16 with D = 128 only (the matrix-core decode kernels): CART_ERR_UNSUPPORTED otherwise.
+ *   - A problem whose cart_decode_workspace() exceeds cart_decode_static_capacity() is refused
+ *     with CART_ERR_WORKSPACE before anything is launched (the 128-request, 8192-slot serving
+ *     shape needs 16.9 MB).
+ *   - Every call on a GPU uses that GPU's one array: calls that overlap in time on the same GPU
+ *     (two streams, two threads) race; calls on one stream do not.  Nothing in it has to be
+ *     cleared between calls: every partial result is written before it is read.
+ */
+cart_status cart_decode_static(const cart_decode_desc *desc, const void *q, const void *z_k,
+                               const void *z_v, const void *k_own, const void *v_own,
+                               const int32_t *cu_lens, void *o, float *lse, void *stream);
+size_t cart_decode_static_capacity(void);
+
+/*
  * cart_teacher_topk -- the producer of cart_distill_kl_fwd_bwd's teacher inputs (App. A.2: the
  * teacher's top output probabilities are collected while it generates).  Per position n:
  *   teacher_idx[n,0..K)  the K tokens with the largest logits, by descending logit, the lower

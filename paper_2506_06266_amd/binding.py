@@ -25,7 +25,7 @@ EXPORTS = ["cart_attn_fwd_workspace", "cart_attn_bwd_workspace", "cart_kl_worksp
            "cart_decode", "cart_decode_composed_workspace", "cart_decode_composed", "cart_teacher_topk",
            "cart_attn_varlen_fwd_workspace", "cart_attn_varlen_bwd_workspace", "cart_attn_varlen_fwd",
            "cart_attn_varlen_bwd", "cart_trace_events", "cart_calib_mfma", "cart_calib_copy",
-           "cart_calib_read",
+           "cart_calib_read", "cart_decode_static", "cart_decode_static_capacity",
            "cart_status_str", "cart_version"]
 
 
@@ -105,6 +105,9 @@ def load() -> C.CDLL:
     lib.cart_distill_kl_fwd_bwd.argtypes = [C.POINTER(KlDesc)] + [vp] * 7 + [sz, vp]
     lib.cart_decode.restype = C.c_int
     lib.cart_decode.argtypes = [C.POINTER(DecodeDesc)] + [vp] * 9 + [sz, vp]
+    lib.cart_decode_static.restype = C.c_int
+    lib.cart_decode_static.argtypes = [C.POINTER(DecodeDesc)] + [vp] * 9
+    lib.cart_decode_static_capacity.restype, lib.cart_decode_static_capacity.argtypes = sz, []
     lib.cart_teacher_topk.restype = C.c_int
     lib.cart_teacher_topk.argtypes = [C.POINTER(TopkDesc), vp, vp, vp, vp]
     lib.cart_decode_composed_workspace.restype = sz
@@ -300,6 +303,22 @@ def cart_decode(q, z_k, z_v, k_own, v_own, cu_lens, max_own_len: int, *, scale: 
                          _ptr(cu_lens), _ptr(o), _ptr(lse), _ptr(ws),
                          0 if ws is None else ws.numel(), _stream(stream))
     _check(st, "cart_decode")
+    return o, lse
+
+
+def cart_decode_static(q, z_k, z_v, k_own, v_own, cu_lens, max_own_len: int, *, scale: float = 0.0,
+                       o=None, lse=None, stream=None):
+    """cart_decode without a workspace: the library's own per-GPU scratch array holds the partial
+    results (nothing is allocated by the call itself when o and lse are passed in)."""
+    lib = load()
+    B, Hq, D = q.shape
+    p = 0 if z_k is None else z_k.shape[1]
+    d = DecodeDesc(B, Hq, k_own.shape[1], D, p, k_own.shape[0], max_own_len, _dtype_code(q), scale, IMPL_AUTO)
+    o = torch.empty_like(q) if o is None else o
+    lse = torch.empty(B, Hq, dtype=torch.float32, device=q.device) if lse is None else lse
+    st = lib.cart_decode_static(C.byref(d), _ptr(q), _ptr(z_k), _ptr(z_v), _ptr(k_own), _ptr(v_own),
+                                _ptr(cu_lens), _ptr(o), _ptr(lse), _stream(stream))
+    _check(st, "cart_decode_static")
     return o, lse
 
 

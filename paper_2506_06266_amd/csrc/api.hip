@@ -290,6 +290,26 @@ cart_status cart_decode(const cart_decode_desc* d, const void* q, const void* z_
     return e == 0 ? CART_OK : CART_ERR_LAUNCH;
 }
 
+size_t cart_decode_static_capacity(void) { return cart::decode_static_capacity(); }
+
+cart_status cart_decode_static(const cart_decode_desc* d, const void* q, const void* z_k, const void* z_v,
+                               const void* k_own, const void* v_own, const int32_t* cu_lens, void* o,
+                               float* lse, void* stream) {
+    cart_status s = check_decode(d);
+    if (s != CART_OK) return s;
+    if (!cart::decode_mfma_supported(*d) || d->impl == CART_IMPL_VECTOR) return CART_ERR_UNSUPPORTED;
+    REQUIRE(q); REQUIRE(k_own); REQUIRE(v_own); REQUIRE(cu_lens); REQUIRE(o);
+    if (d->P > 0) { REQUIRE(z_k); REQUIRE(z_v); }
+    ALIGNED(q); ALIGNED(z_k); ALIGNED(z_v); ALIGNED(k_own); ALIGNED(v_own); ALIGNED(o);
+    if (cart::decode_mfma_workspace(*d) > cart::decode_static_capacity()) return CART_ERR_WORKSPACE;
+    void* ws = cart::decode_static_scratch();
+    if (!ws) return CART_ERR_LAUNCH;
+    const float scale = attn_scale(d->softmax_scale, d->D);
+    int e = cart::launch_decode_mfma(*d, scale, q, z_k, z_v, k_own, v_own, cu_lens, o, lse, ws,
+                                     static_cast<hipStream_t>(stream));
+    return e == 0 ? CART_OK : CART_ERR_LAUNCH;
+}
+
 cart_status cart_trace_events(void* const* events, int32_t count) {
     if (events && count < 1) return CART_ERR_SHAPE;
     cart::Trace& t = cart::trace();

@@ -117,6 +117,8 @@ int launch_decode_composed(const cart_decode_composed_desc& d, float scale, cons
                            float* lse, void* ws, hipStream_t st);
 bool decode_mfma_supported(const cart_decode_desc& d);
 size_t decode_mfma_workspace(const cart_decode_desc& d);
+size_t decode_static_capacity();      // bytes of the library's own per-GPU decode scratch array
+void* decode_static_scratch();        // its address on the current device (nullptr on failure)
 int launch_decode_mfma(const cart_decode_desc& d, float scale, const void* q, const void* zk,
                        const void* zv, const void* k, const void* v, const int32_t* cu, void* o,
                        float* lse, void* ws, hipStream_t st);

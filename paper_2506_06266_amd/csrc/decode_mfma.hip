@@ -525,6 +525,29 @@ int launch_decode_mfma(const cart_decode_desc& d, float scale, const void* q, co
     return run_decode(p, d.B, d.Hq, d.Hkv, scale, q, nullptr, nullptr, nullptr, 0, k, v, cu, o, lse, ws, st);
 }
 
+// ---- the decode step for callers that cannot allocate ---------------------------------------------
+// The partial results of one call live in a file-scope device array instead of a caller-supplied
+// workspace.  Each GPU holds its own copy of the array at its own address, looked up once per
+// device; host code only ever uses that looked-up address, never the array's name.
+constexpr size_t DEC_STATIC_BYTES = static_cast<size_t>(32) << 20;
+static __device__ __align__(256) unsigned char scratch[DEC_STATIC_BYTES];
+constexpr int DEC_MAX_DEVICES = 64;
+static void* g_scratch_ptr[DEC_MAX_DEVICES];      // per device, nullptr until looked up
+
+size_t decode_static_capacity() { return DEC_STATIC_BYTES; }
+
+// the current device's copy of the array (nullptr when the runtime refuses the lookup)
+void* decode_static_scratch() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= DEC_MAX_DEVICES) return nullptr;
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return nullptr;
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
+
 int launch_decode_composed(const cart_decode_composed_desc& d, float scale, const void* q,
                            const cart_segment* shared, const void* pool_k, const void* pool_v,
                            const int32_t* cart_id, const void* k, const void* v, const int32_t* cu, void* o,
