@@ -1,10 +1,14 @@
 """Parity at the benchmark's full sizes, in the launch configuration bench.py times.
 
-The GPU runs the whole problem; the oracle recomputes a sample that is complete for the outputs
-it checks: for attention one whole KV group (every sequence, its G query heads), which fixes
-O / LSE / dQ for those heads, dK_own / dV_own for that KV head and -- because the sum over the
-whole batch is inside the sample -- dZ_k / dZ_v of that head, every element.
+The GPU runs the whole problem.  Attention: the oracle recomputes the forward pass of every KV
+group (every element of O and LSE), and the backward pass of two whole KV groups on different
+residues of the workgroup-to-XCD rotation (every sequence, their G query heads), which fixes dQ
+for those heads, dK_own / dV_own for those KV heads and -- because the sum over the whole batch
+is inside the sample -- dZ_k / dZ_v of those heads, every element.  Loss: every row's value and
+the scalar against the oracle run in row chunks, the gradient on sampled rows.
 """
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 import pytest
 import torch
@@ -25,39 +29,53 @@ def rel_err(x, ref) -> float:
     return float(np.abs(x - ref).max() / np.abs(ref).max())
 
 
+def elem_err(x, ref, floor=1e-3) -> float:
+    """Element-wise relative error with an absolute floor of `floor` x max |ref| in the denominator."""
+    x = np.asarray(x, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    return float((np.abs(x - ref) / np.maximum(np.abs(ref), floor * np.abs(ref).max())).max())
+
+
 def f64(t):
     return t.detach().to("cpu", torch.float64).numpy()
 
 
-@pytest.mark.parametrize("name,hk", [("cfg2", 5), ("cfg3", 2)])
-def test_attention_full_shape_one_kv_group(name, hk):
+@pytest.mark.parametrize("name,grad_heads", [("cfg2", (5, 0)), ("cfg3", (2, 7))])
+def test_attention_full_shape_every_kv_group(name, grad_heads):
     cfg = synth.ATTN_CONFIGS[name]
-    print("case", name, "kv head", hk, flush=True)
+    print("case", name, "gradients of kv heads", grad_heads, flush=True)
     g = synth.attn_inputs(cfg, DEV)
     o, lse = cb.cart_attn_fwd(g["q"], g["k_own"], g["v_own"], g["z_k"], g["z_v"])
     dq, dk, dv, dzk, dzv = cb.cart_attn_bwd(g["q"], g["k_own"], g["v_own"], g["z_k"], g["z_v"], o, lse, g["d_o"])
     torch.cuda.synchronize()
     G = cfg.Hq // cfg.Hkv
-    hs = slice(hk * G, (hk + 1) * G)
-    q, do = f64(g["q"][:, :, hs]), f64(g["d_o"][:, :, hs])
-    k, v = f64(g["k_own"][:, :, hk:hk + 1]), f64(g["v_own"][:, :, hk:hk + 1])
-    zk, zv = f64(g["z_k"][hk:hk + 1]), f64(g["z_v"][hk:hk + 1])
-    o_ref, lse_ref = orc.attn_fwd(q, k, v, zk, zv)
-    r = orc.attn_bwd(q, k, v, zk, zv, do)
-    errs = {
-        "o": rel_err(f64(o[:, :, hs]), o_ref), "lse": rel_err(f64(lse[:, hs]), lse_ref),
-        "dq": rel_err(f64(dq[:, :, hs]), r[0]), "dk": rel_err(f64(dk[:, :, hk:hk + 1]), r[1]),
-        "dv": rel_err(f64(dv[:, :, hk:hk + 1]), r[2]), "dzk": rel_err(f64(dzk[hk:hk + 1]), r[3]),
-        "dzv": rel_err(f64(dzv[hk:hk + 1]), r[4]),
-    }
-    print(name, errs, flush=True)
-    for kk, e in errs.items():
-        assert e <= TOL, (name, kk, e)
+    for hk in range(cfg.Hkv):
+        hs = slice(hk * G, (hk + 1) * G)
+        q, do = f64(g["q"][:, :, hs]), f64(g["d_o"][:, :, hs])
+        k, v = f64(g["k_own"][:, :, hk:hk + 1]), f64(g["v_own"][:, :, hk:hk + 1])
+        zk, zv = f64(g["z_k"][hk:hk + 1]), f64(g["z_v"][hk:hk + 1])
+        o_ref, lse_ref = orc.attn_fwd(q, k, v, zk, zv)
+        pairs = {"o": (f64(o[:, :, hs]), o_ref), "lse": (f64(lse[:, hs]), lse_ref)}
+        if hk in grad_heads:
+            r = orc.attn_bwd(q, k, v, zk, zv, do)
+            pairs.update({"dq": (f64(dq[:, :, hs]), r[0]), "dk": (f64(dk[:, :, hk:hk + 1]), r[1]),
+                          "dv": (f64(dv[:, :, hk:hk + 1]), r[2]), "dzk": (f64(dzk[hk:hk + 1]), r[3]),
+                          "dzv": (f64(dzv[hk:hk + 1]), r[4])})
+        errs = {kk: rel_err(x, rr) for kk, (x, rr) in pairs.items()}
+        print(name, "kv head", hk, "max|x-ref|/max|ref|", {kk: "%.2e" % e for kk, e in errs.items()},
+              "element-wise (floor 1e-3 max|ref|)", {kk: "%.2e" % elem_err(x, rr) for kk, (x, rr) in pairs.items()},
+              flush=True)
+        for kk, e in errs.items():
+            assert e <= TOL, (name, hk, kk, e)
     # the backward pass is bit-reproducible (no atomics): a second run gives the same bits
     again = cb.cart_attn_bwd(g["q"], g["k_own"], g["v_own"], g["z_k"], g["z_v"], o, lse, g["d_o"])
     torch.cuda.synchronize()
     for a, b in zip((dq, dk, dv, dzk, dzv), again):
         assert torch.equal(a, b)
+    # and so is the forward pass
+    o2, lse2 = cb.cart_attn_fwd(g["q"], g["k_own"], g["v_own"], g["z_k"], g["z_v"])
+    torch.cuda.synchronize()
+    assert torch.equal(o, o2) and torch.equal(lse, lse2)
 
 
 @pytest.mark.parametrize("mode", [cb.KL_TOPK, cb.KL_REST], ids=["topk", "rest"])
@@ -82,6 +100,28 @@ def test_distill_kl_full_size_sampled_rows(mode):
     # the recorded tokens carry the only negative gradients of a row, exactly at teacher_idx
     neg = (dl[rows].float() < 0).cpu()
     assert torch.equal(neg, torch.tensor(dl_ref < 0))
+    # every row's value and the scalar against the oracle, run in chunks of rows (a stripe of
+    # 2048 rows for the rest-bucket reading, whose oracle is several times slower)
+    n_rows = cfg.N if mode == cb.KL_TOPK else 2048
+    fn = orc.distill_kl if mode == cb.KL_TOPK else orc.distill_kl_rest_bucket
+    idx_all = g["teacher_idx"].cpu().numpy()
+    lp_all = f64(g["teacher_logp"])
+    chunk = 256
+
+    def rows_of(c0):
+        zc = f64(g["logits"][c0:c0 + chunk])
+        return fn(zc, idx_all[c0:c0 + chunk], lp_all[c0:c0 + chunk], 1.0)[2]
+
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        parts = list(ex.map(rows_of, range(0, n_rows, chunk)))
+    row_all = np.concatenate(parts)
+    print("cfg4 oracle rows done:", n_rows, flush=True)
+    e_rows = rel_err(f64(row_kl[:n_rows]), row_all)
+    assert e_rows <= 1e-4, e_rows
+    if n_rows == cfg.N:
+        loss_ref = cfg.scale * float(row_all.sum())
+        print("cfg4 loss", loss.item(), "oracle", loss_ref, "row_kl err", e_rows, flush=True)
+        assert abs(loss.item() - loss_ref) <= 1e-4 * abs(loss_ref)
     # scalar = scale * sum of the per-row values (fixed-order fp64 reduce in the library)
     expect = cfg.scale * float(row_kl.double().sum().item())
     assert abs(loss.item() - expect) <= 1e-6 * abs(expect)
