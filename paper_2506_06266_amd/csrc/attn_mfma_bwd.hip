@@ -274,7 +274,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
             mask1(x1, 1, pre, j0 + 32 * hb);
         }
         pin();
-        float w0[16], w1[16];
+        float w0[16], w1[16], e0[16], e1[16];
         u32x4 dn[2][2];
         static_for<48>([&](auto gc) __attribute__((always_inline)) {
             constexpr int g = decltype(gc)::value;
@@ -300,18 +300,26 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
             // row-wise fragments of sub-tile u+1
             if (g >= 6 && g <= 34 && ((g - 6) & 3) == 0) ka[(g - 6) >> 2] = ld_k((g - 6) >> 2, hb ? 0 : 1);
             if (g >= 8 && g <= 36 && ((g - 8) & 3) == 0) va[(g - 8) >> 2] = ld_v((g - 8) >> 2, hb ? 0 : 1);
+            // The LDS reads go out right behind the matrix-core instruction, the vector ALU work
+            // follows; its exponential and the product that consumes it sit a group apart (a
+            // transcendental's consumer right behind it costs a wait state).
+            __builtin_amdgcn_sched_barrier(0);
             // vector ALU: block 1 element g (groups 0-15), block 0 element (g-16)/2 (even groups after)
             if (g < 16) {
-                w1[g] = fast_exp2(CART_PRESCALE ? x1[g] + nl2[1] : fmaf(x1[g], c, nl2[1])) * y1[g];
-                if (g >= 2 && !(g & 1)) dn[1][(g - 2) >> 3][((g - 2) & 7) >> 1] = pack_bf16x2(w1[g - 2], w1[g - 1]);
+                e1[g] = fast_exp2(CART_PRESCALE ? x1[g] + nl2[1] : fmaf(x1[g], c, nl2[1]));
+                if (g >= 1) w1[g - 1] = e1[g - 1] * y1[g - 1];
+                if (g >= 3 && (g & 1)) dn[1][(g - 3) >> 3][((g - 3) & 7) >> 1] = pack_bf16x2(w1[g - 3], w1[g - 2]);
             } else if (!(g & 1)) {
                 const int r = (g - 16) >> 1;
-                if (r == 0) dn[1][1][3] = pack_bf16x2(w1[14], w1[15]);
-                w0[r] = fast_exp2(CART_PRESCALE ? x0in[r] + nl2[0] : fmaf(x0in[r], c, nl2[0])) * y0in[r];
-                if (r >= 2 && !(r & 1)) dn[0][(r - 2) >> 3][((r - 2) & 7) >> 1] = pack_bf16x2(w0[r - 2], w0[r - 1]);
+                if (r == 0) w1[15] = e1[15] * y1[15];
+                if (r == 1) dn[1][1][3] = pack_bf16x2(w1[14], w1[15]);
+                e0[r] = fast_exp2(CART_PRESCALE ? x0in[r] + nl2[0] : fmaf(x0in[r], c, nl2[0]));
+                if (r >= 1) w0[r - 1] = e0[r - 1] * y0in[r - 1];
+                if (r >= 3 && (r & 1)) dn[0][(r - 3) >> 3][((r - 3) & 7) >> 1] = pack_bf16x2(w0[r - 3], w0[r - 2]);
             }
             __builtin_amdgcn_sched_barrier(0);
         });
+        w0[15] = e0[15] * y0in[15];
         dn[0][1][3] = pack_bf16x2(w0[14], w0[15]);
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb)
@@ -653,6 +661,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
             if (!CART_PRESCALE && g == 20) ld_rows_at(nl_n, hb ? rofs : rofs_c, 0, 1 - hb);   // of sub-tile u+1
             if (g >= 2 && g <= 16 && !(g & 1)) qa[(g - 2) >> 1] = ld_q((g - 2) >> 1, hb);
             if (g >= 18 && !(g & 1)) ta[(g - 18) >> 1] = ld_t((g - 18) >> 1, hb);
+            __builtin_amdgcn_sched_barrier(0);   // LDS reads first, then the vector ALU work
             {
                 const int kc = g >> 4, r = g & 15;
                 pe[g] = fast_exp2(CART_PRESCALE ? xin[kc][r] : fmaf(xin[kc][r], c, nl[r]));

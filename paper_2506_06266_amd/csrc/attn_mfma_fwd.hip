@@ -278,6 +278,8 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_mfma_kernel(
                 const int i = g - 18;
                 va[i >> 3][(i >> 1) & 3] = ld_v(i >> 3, (i >> 1) & 3, hb);
             }
+            // the LDS reads go out right behind the matrix-core instruction, ahead of the vector ALU work
+            __builtin_amdgcn_sched_barrier(0);
             {   // softmax element g; the pair before it is rounded, packed and summed
                 const int cb = g >> 4, r = g & 15;
 #if CART_PRESCALE
