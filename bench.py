@@ -151,10 +151,10 @@ def main() -> int:
 
     part_ms = {name: sum(ev[s][i].elapsed_time(ev[s][i + 1]) for s in range(args.steps)) / args.steps
                for i, (name, _) in enumerate(parts)}
-    bwd_kernels = ["dq", "dk", "dv", "dz_reduce"]
+    bwd_kernels = ["dq", "dkv", "dz_reduce"]
     k_ms = {n: 0.0 for n in bwd_kernels}
     for tr in traces:
-        iv = tr.intervals_ms(5)
+        iv = tr.intervals_ms(4)
         for n, v in zip(bwd_kernels, iv):
             k_ms[n] += v / args.steps
         tr.close()
@@ -304,12 +304,12 @@ def main() -> int:
     # recomputing S, then dP, dV, dQ, dK), whatever they recompute between them, so `achieved`
     # prices the call: algorithmic flops of the backward / time of its kernels.  What the dominant
     # kernel itself executes per second is reported beside it.
-    units = {"dq": 3, "dk": 3, "dv": 2}          # contractions each kernel performs per pair
+    units = {"dq": 3, "dkv": 4}                  # contractions each kernel performs per pair
     dom = max(units, key=lambda n: k_ms[n])
     bwd_kernel_ms = sum(k_ms.values())
     bwd_alg_tflops = bwd_flop / (bwd_kernel_ms * 1e-3) / 1e12
     dom_exec_tflops = pairs * units[dom] * 2 * acfg.D / (k_ms[dom] * 1e-3) / 1e12
-    dom_name = {"dq": "attn_bwd_dq_kernel", "dk": "attn_bwd_kstat_kernel<true>", "dv": "attn_bwd_kstat_kernel<false>"}[dom]
+    dom_name = {"dq": "attn_bwd_dq_kernel", "dkv": "attn_bwd_kv_kernel"}[dom]
     roofline = {"kernel": dom_name, "bound": "mfma", "achieved": round(bwd_alg_tflops, 1),
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(bwd_alg_tflops / PEAK_BF16_TFLOPS, 4),
                 "traffic": profiled_traffic(dom_name, lib.cart_version()),

@@ -289,7 +289,7 @@ cart_status cart_attn_varlen_bwd(const cart_attn_varlen_desc *desc, const void *
  * variants) / cart_distill_kl_fwd_bwd / cart_decode call records events[0] on its stream before
  * its first kernel and events[i] after its i-th kernel (as many as `count` allows).  Kernel
  * order, bf16 / head_dim 128: attention forward = forward, overflow repair; backward = dQ
- * (which also forms the row statistics), dK, dV, the two dZ reductions (one event); loss = row kernel, scalar
+ * (which also forms the row statistics), dK + dV (one kernel), the two dZ reductions (one event); loss = row kernel, scalar
  * reduction; decode = prefix + own-KV (one launch), merge.  The array must stay valid while the
  * hook is set.  Process-global, not thread-safe; the caller owns the events and reads them after
  * synchronising the stream.

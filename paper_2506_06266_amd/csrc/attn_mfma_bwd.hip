@@ -909,10 +909,22 @@ __global__ __launch_bounds__(256) void dz_reduce_kernel(const float* __restrict_
 
 bool attn_mfma_bwd_supported(const cart_attn_desc& d) { return d.dtype == CART_BF16 && d.D == 128; }
 
+// 1: the split dK and dV kernels (5 contractions per pair between them); 0: the fused kernel of
+// attn_mfma_bwd_kv.hip (4)
+#ifndef CART_BWD_SPLIT
+#define CART_BWD_SPLIT 0
+#endif
+int bwd_kv_chunk(const cart_attn_desc& d, long tokens, int* n_part);
+void launch_attn_bwd_kv(const cart_attn_desc& d, float scale, const bf16_t* Q, const bf16_t* K, const bf16_t* V,
+                        const bf16_t* ZK, const bf16_t* ZV, const bf16_t* DO, const float* lse2, const float* delta,
+                        bf16_t* dk, bf16_t* dv, float* part_k, float* part_v, const int32_t* cu, int n_tok, int chunk,
+                        int n_part, hipStream_t st);
+
 static size_t r256(size_t n) { return (n + 255) & ~static_cast<size_t>(255); }
 
 // token rows per prefix-gradient partial, and the number of partials
 static int bwd_chunk(const cart_attn_desc& d, long tokens, int* n_part) {
+    if (!CART_BWD_SPLIT) return bwd_kv_chunk(d, tokens, n_part);
     const long nPb = (d.P + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
     long n = nPb > 0 ? (BWD_PREFIX_WGS + nPb * d.Hkv - 1) / (nPb * d.Hkv) : 1;
     const long most = (tokens + BWD_MIN_CHUNK - 1) / BWD_MIN_CHUNK;
@@ -961,7 +973,7 @@ int launch_attn_bwd_mfma(const cart_attn_desc& d, float scale, const void* q, co
                  *ZV = static_cast<const bf16_t*>(zv), *DO = static_cast<const bf16_t*>(d_o);
     const float c = scale * CART_LOG2E;
     const bf16_t* O = static_cast<const bf16_t*>(o);
-    trace_begin(st);   // kernel order: dq (+ row statistics), dk, dv, dz reduce (k, v)
+    trace_begin(st);   // kernel order: dq (+ row statistics), dk + dv (one kernel), dz reduce (k, v)
     if (row_lo) {
         const long nQt = (T + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
         hipLaunchKernelGGL(attn_bwd_dq_kernel, dim3(static_cast<unsigned>(nQt * d.Hq)), dim3(256), 0, st, Q, K, V, ZK,
@@ -974,6 +986,7 @@ int launch_attn_bwd_mfma(const cart_attn_desc& d, float scale, const void* q, co
                            d.Hq, d.Hkv, d.P, c, scale);
     }
     trace_mark(st);
+#if CART_BWD_SPLIT
     const long nPb = (d.P + BWD_WG_ROWS - 1) / BWD_WG_ROWS, nOb = (d.S + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
     const unsigned kgrid = static_cast<unsigned>((nPb * n_part + nOb * d.B) * d.Hkv);
     hipLaunchKernelGGL(attn_bwd_kstat_kernel<true>, dim3(kgrid), dim3(256), 0, st, Q, K, V, ZK, ZV, DO, lse2,
@@ -982,6 +995,11 @@ int launch_attn_bwd_mfma(const cart_attn_desc& d, float scale, const void* q, co
     hipLaunchKernelGGL(attn_bwd_kstat_kernel<false>, dim3(kgrid), dim3(256), 0, st, Q, K, V, ZK, ZV, DO, lse2,
                        delta, static_cast<bf16_t*>(dv), part_v, cu, n_tok, chunk, d.B, d.S, d.Hq, d.Hkv, d.P, c, scale);
     trace_mark(st);
+#else
+    launch_attn_bwd_kv(d, scale, Q, K, V, ZK, ZV, DO, lse2, delta, static_cast<bf16_t*>(dk), static_cast<bf16_t*>(dv),
+                       part_k, part_v, cu, n_tok, chunk, n_part, st);
+    trace_mark(st);
+#endif
     if (d.P > 0) {
         const long n4 = static_cast<long>(d.Hkv) * d.P * HD / 4;
         const unsigned rg = static_cast<unsigned>((n4 + 255) / 256);
