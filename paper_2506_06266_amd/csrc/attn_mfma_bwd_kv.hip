@@ -47,6 +47,13 @@ struct KvSmem {
 // functions, each with a register allocation of its own, that address the same memory.
 __shared__ KvSmem kv_sm;
 
+// The workgroup barrier without the wait for every outstanding LDS and memory operation that
+// __syncthreads() puts in front of it: in the hot loop a wavefront only has to have finished what
+// the OTHER wavefronts are about to depend on (A: its direct-to-LDS loads and its P-slot writes;
+// B: nothing), and fragment loads for later iterations stay in flight across the barrier.
+__device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
+__device__ __forceinline__ void lds_wait0() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
 __device__ __forceinline__ void kv_store_f32(const f32x16 (&acc)[4], float* row_ptr, int lg, float mul) {
     if (!row_ptr) return;
 #pragma unroll
@@ -191,11 +198,10 @@ __device__ __attribute__((noinline)) void kv_role(const KvArgs* args_generic) {
         ts.qb = q_c + base;
         ts.gb = g_c + base;
         ts.lim = S - 1 - ts.i0;
-        // wavefronts 0 / 2 fetch the rows' -lse2, 1 / 3 their -delta (twice each: no branch)
-        ts.rb = reinterpret_cast<const char*>(((wv & 1) ? ndelta : nlse2) + static_cast<size_t>(h) * n_tok + t0 + ts.i0);
+        ts.rb = reinterpret_cast<const char*>((pair ? ndelta : nlse2) + static_cast<size_t>(h) * n_tok + t0 + ts.i0);
         ts.lds_q = lds_addr(sm.t[buf].q);
         ts.lds_g = lds_addr(sm.t[buf].g);
-        ts.lds_r = lds_addr((wv & 1) ? sm.ndl[buf] : sm.nl2[buf]);
+        ts.lds_r = lds_addr(pair ? sm.ndl[buf] : sm.nl2[buf]);
         if (it_cnt < nT - 1) {     // past the end the last tile is fetched again, into a retired buffer
             ++it_cnt;
             ++it_n;
@@ -206,18 +212,21 @@ __device__ __attribute__((noinline)) void kv_role(const KvArgs* args_generic) {
         }
         return ts;
     };
-    // direct-to-LDS loads of a tile, nine per wavefront: 4 x Q rows, 4 x dO rows, 1 x row values
+    // Direct-to-LDS loads of a tile, all issued by the two A wavefronts (B is the busier role):
+    // seventeen each -- 8 x 4 Q rows, 8 x 4 dO rows of the wavefront's half of the tile, and one
+    // of the two row-value arrays (pair 0: -lse2, pair 1: -delta).
     auto dma_piece = [&](const TileSrc& ts, int n) __attribute__((always_inline)) {
-        if (n == 8) {
+        if (n == 16) {
             dma4(ts.rb, static_cast<uint32_t>(min(lane, ts.lim)) * 4u, ts.lds_r);
             return;
         }
-        const int i = n & 3;
-        const int r0 = (4 * wv + i) * 4;
-        const uint32_t voff = __umul24(min(r0 + (lane >> 4), ts.lim), q_pitch) + ((dma_c0 ^ i) << 4);
-        if (n < 4) dma16(ts.qb, voff, ts.lds_q + r0 * ROW_B);
+        const int i = n & 7;
+        const int r0 = (8 * pair + i) * 4;
+        const uint32_t voff = __umul24(min(r0 + (lane >> 4), ts.lim), q_pitch) + ((dma_c0 ^ (i & 3)) << 4);
+        if (n < 8) dma16(ts.qb, voff, ts.lds_q + r0 * ROW_B);
         else       dma16(ts.gb, voff, ts.lds_g + r0 * ROW_B);
     };
+    constexpr int KV_DMA = 17, KV_DMA0 = 9;      // pieces per tile; how many of them ride in the first half
 
     const uint32_t fwd = static_cast<uint32_t>(KV_BUF_B), back = static_cast<uint32_t>(-(KV_NBUF - 1) * KV_BUF_B);
     const uint32_t rfwd = static_cast<uint32_t>(KV_TILE * 4), rback = static_cast<uint32_t>(-(KV_NBUF - 1) * KV_TILE * 4);
@@ -268,10 +277,15 @@ __device__ __attribute__((noinline)) void kv_role(const KvArgs* args_generic) {
         for (int kc = 0; kc < 2; ++kc)
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) xf[kc][ks] = u32x4{0u, 0u, 0u, 0u};
-        bf16x8 qa[8], ta[8];
+        bf16x8 qa[8], ta[6];
         f32x16 nl, nl_n;
         f32x16 xa[2], xb[2];
 
+        // The last two transposed fragments have a spare register set each (tb6 / tb7, indexed by
+        // the parity of the iteration that USES them), so that the next iteration's copies can be
+        // requested before this iteration's last use: nothing is issued to LDS in the last
+        // groups, and the wait in front of the barrier finds (almost) nothing outstanding.
+        bf16x8 tb6[2], tb7[2];
         auto stage = [&](auto hb_tag, auto masked_tag, int i0, f32x16 (&xin)[2], f32x16 (&xout)[2], const TileSrc& ts,
                          uint32_t wslot) __attribute__((always_inline)) {
             constexpr int hb = decltype(hb_tag)::value;
@@ -280,6 +294,15 @@ __device__ __attribute__((noinline)) void kv_role(const KvArgs* args_generic) {
             pin();
             float pe[32];
             u32x4 xn[2][2];
+            auto elem = [&](int e) __attribute__((always_inline)) {
+                pe[e] = fast_exp2(fmaf(xin[e >> 4][e & 15], c, nl[e & 15]));
+            };
+            auto pack2 = [&](int e) __attribute__((always_inline)) {     // elements e, e+1 -> their word of P(u)
+                xn[e >> 4][(e & 15) >> 3][(e & 7) >> 1] = pack_bf16x2(pe[e], pe[e + 1]);
+            };
+            auto put = [&](int f) __attribute__((always_inline)) {       // fragment f of P(u) -> the pair's slot
+                *(u32x4 __attribute__((address_space(3)))*)(wslot + f * 1024) = xn[f >> 1][f & 1];
+            };
             static_for<32>([&](auto gc) __attribute__((always_inline)) {
                 constexpr int g = decltype(gc)::value;
                 if (g < 16) {
@@ -287,35 +310,39 @@ __device__ __attribute__((noinline)) void kv_role(const KvArgs* args_generic) {
                     if (t8 == 0) mma_vd_zero(xout[kc], qa[0], sf[kc][0]);
                     else         mma_vd(xout[kc], qa[t8], sf[kc][t8]);
                 } else {
-                    const int i = g - 16, ks = i >> 3, db = (i >> 1) & 3, kc = i & 1;
-                    acc[db][kc] = mma(ta[4 * ks + db], __builtin_bit_cast(bf16x8, xf[kc][ks]), acc[db][kc]);
+                    const int i = g - 16, ks = i >> 3, db = (i >> 1) & 3, kc = i & 1, pf = 4 * ks + db;
+                    const bf16x8 tf = pf == 6 ? tb6[hb] : pf == 7 ? tb7[hb] : ta[pf];
+                    acc[db][kc] = mma(tf, __builtin_bit_cast(bf16x8, xf[kc][ks]), acc[db][kc]);
                 }
                 __builtin_amdgcn_sched_barrier(0);   // the matrix-core instruction leads its group
-                if (hb == 0 && g < 9) dma_piece(ts, g);
+                if (hb == 0 && g < KV_DMA0) dma_piece(ts, g);
+                if (hb == 1 && g < KV_DMA - KV_DMA0) dma_piece(ts, KV_DMA0 + g);
                 if (g == 20) ld_rows_at(nl_n, hb ? rofs : rofs_c, 1 - hb);                 // -lse2 of sub-tile u+1
                 if (g >= 2 && g <= 16 && !(g & 1)) qa[(g - 2) >> 1] = ld_q((g - 2) >> 1, hb);   // of sub-tile u+2
-                if (g >= 18 && !(g & 1)) ta[(g - 18) >> 1] = ld_t((g - 18) >> 1, hb);           // of sub-tile u
-                __builtin_amdgcn_sched_barrier(0);   // LDS reads first, then the vector ALU work
-                {
-                    const int kc = g >> 4, r = g & 15;
-                    pe[g] = fast_exp2(fmaf(xin[kc][r], c, nl[r]));
-                    if (g >= 2 && !(g & 1)) {
-                        const int e = g - 2;
-                        xn[e >> 4][(e & 15) >> 3][(e & 7) >> 1] = pack_bf16x2(pe[e], pe[e + 1]);
-                    }
-                }
+                if (g >= 18 && g <= 28 && !(g & 1)) ta[(g - 18) >> 1] = ld_t((g - 18) >> 1, hb);   // of sub-tile u
+                if (g == 25) tb6[1 - hb] = ld_t(6, hb);
+                if (g == 27) tb7[1 - hb] = ld_t(7, hb);
+                // P(u) leaves for the pair's slot fragment by fragment, as soon as each is complete
+                if (g == 9) put(0);
+                if (g == 17) put(1);
+                if (g == 21) put(2);
+                if (g == 29) put(3);
+                __builtin_amdgcn_sched_barrier(0);   // LDS traffic first, then the vector ALU work
+                // P(u): one element per group, two in groups 16-19, so that the last fragment is
+                // complete four groups before the iteration ends
+                if (g < 16) elem(g);
+                else if (g < 20) { elem(2 * g - 16); elem(2 * g - 15); }
+                else if (g < 28) elem(g + 4);
+                if (g >= 2 && g <= 16 && !(g & 1)) pack2(g - 2);
+                if (g >= 17 && g <= 20) pack2(2 * g - 18);
+                if (g >= 22 && g <= 28 && !(g & 1)) pack2(g + 2);
                 __builtin_amdgcn_sched_barrier(0);
             });
-            ta[7] = ld_t(7, hb);
             nl = nl_n;
-            xn[1][1][3] = pack_bf16x2(pe[30], pe[31]);
 #pragma unroll
             for (int kc = 0; kc < 2; ++kc)
 #pragma unroll
-                for (int ks = 0; ks < 2; ++ks) {
-                    xf[kc][ks] = xn[kc][ks];
-                    *(u32x4 __attribute__((address_space(3)))*)(wslot + (2 * kc + ks) * 1024) = xn[kc][ks];
-                }
+                for (int ks = 0; ks < 2; ++ks) xf[kc][ks] = xn[kc][ks];
             __builtin_amdgcn_sched_barrier(0);
         };
         auto settle = [&]() __attribute__((always_inline)) { asm volatile("s_nop 15\n\ts_nop 7" ::: "memory"); };
@@ -325,13 +352,13 @@ __device__ __attribute__((noinline)) void kv_role(const KvArgs* args_generic) {
             const TileSrc t0s = next_tile(0);
             i0_cur = t0s.i0;
 #pragma unroll
-            for (int n = 0; n < 9; ++n) dma_piece(t0s, n);
+            for (int n = 0; n < KV_DMA; ++n) dma_piece(t0s, n);
             dma_wait();
             __syncthreads();
             const TileSrc t1s = next_tile(1);
             i0_nx = t1s.i0;
 #pragma unroll
-            for (int n = 0; n < 9; ++n) dma_piece(t1s, n);
+            for (int n = 0; n < KV_DMA; ++n) dma_piece(t1s, n);
 #pragma unroll
             for (int t8 = 0; t8 < 8; ++t8) qa[t8] = lds_ld_frag(qofs[t8] - KV_BUF_B);        // sub-tile 0
             ld_rows_at(nl, rofs_c, 0);
@@ -344,17 +371,21 @@ __device__ __attribute__((noinline)) void kv_role(const KvArgs* args_generic) {
 #pragma unroll
             for (int t8 = 0; t8 < 8; ++t8) qa[t8] = lds_ld_frag(qofs[t8] - KV_BUF_B + 32 * ROW_B);   // sub-tile 1
 #pragma unroll
-            for (int p = 0; p < 8; ++p) ta[p] = ld_t(p, 0);     // placeholder: multiplied by P = 0
+            for (int p = 0; p < 6; ++p) ta[p] = ld_t(p, 0);     // placeholder: multiplied by P = 0
+            tb6[0] = ld_t(6, 0);
+            tb7[0] = ld_t(7, 0);
         }
         int buf = 0;
         auto tile_iter = [&](auto masked_tag) __attribute__((always_inline)) {
             const int nbuf = buf + 1 == KV_NBUF ? 0 : buf + 1;
             const int nnbuf = nbuf + 1 == KV_NBUF ? 0 : nbuf + 1;
             const TileSrc ts = next_tile(nnbuf);
-            dma_wait();
-            __syncthreads();
+            dma_wait();       // tile T+1 has landed,
+            lds_wait0();      // the last P went into its slot,
+            wg_barrier();     // and everybody knows
             stage(std::integral_constant<int, 0>{}, masked_tag, i0_cur, xa, xb, ts, slot0);
-            __syncthreads();
+            lds_wait0();
+            wg_barrier();
             stage(std::integral_constant<int, 1>{}, masked_tag, i0_cur, xb, xa, ts, slot0 + KV_SLOT_B);
 #pragma unroll
             for (int db = 0; db < 4; ++db) {                 // tile T -> T+1
@@ -378,8 +409,10 @@ __device__ __attribute__((noinline)) void kv_role(const KvArgs* args_generic) {
             for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
                 for (int db = 0; db < 4; ++db) {
-                    acc[db][0] = mma(ta[4 * ks + db], __builtin_bit_cast(bf16x8, xf[0][ks]), acc[db][0]);
-                    acc[db][1] = mma(ta[4 * ks + db], __builtin_bit_cast(bf16x8, xf[1][ks]), acc[db][1]);
+                    const int pf = 4 * ks + db;
+                    const bf16x8 tf = pf == 6 ? tb6[0] : pf == 7 ? tb7[0] : ta[pf];
+                    acc[db][0] = mma(tf, __builtin_bit_cast(bf16x8, xf[0][ks]), acc[db][0]);
+                    acc[db][1] = mma(tf, __builtin_bit_cast(bf16x8, xf[1][ks]), acc[db][1]);
                 }
         }
 #pragma unroll
@@ -451,8 +484,7 @@ __device__ __attribute__((noinline)) void kv_role(const KvArgs* args_generic) {
         };
         // stage: `half` of the row-wise / row-value reads (sub-tile u+1) and `thalf` of the
         // transposed reads (sub-tile u-1) are fixed per call site
-        auto stage = [&](auto hb_tag, f32x16 (&yin)[2], f32x16 (&yout)[2], const TileSrc& ts, uint32_t rslot)
-                         __attribute__((always_inline)) {
+        auto stage = [&](auto hb_tag, f32x16 (&yin)[2], f32x16 (&yout)[2], uint32_t rslot) __attribute__((always_inline)) {
             constexpr int hb = decltype(hb_tag)::value;
             constexpr int half = 1 - hb;        // sub-tile u+1 is half 1 of tile T (hb 0) or half 0 of tile T+1 (hb 1)
             constexpr int thalf = 1 - hb;       // sub-tile u-1 is half 1 of tile T-1 (hb 0) or half 0 of tile T (hb 1)
@@ -473,7 +505,6 @@ __device__ __attribute__((noinline)) void kv_role(const KvArgs* args_generic) {
                     acc[db][kc] = mma(ta[4 * ks + db], __builtin_bit_cast(bf16x8, xf[kc][ks]), acc[db][kc]);
                 }
                 __builtin_amdgcn_sched_barrier(0);
-                if (hb == 0 && g < 9) dma_piece(ts, g);
                 if (g == 20) ld_rows(nd, half);                                                   // -delta of sub-tile u+1
                 if (g >= 2 && g <= 16 && !(g & 1)) ga[(g - 2) >> 1] = ld_g((g - 2) >> 1, half);   // of sub-tile u+1
                 if (g >= 18 && !(g & 1)) ta[(g - 18) >> 1] = ld_t((g - 18) >> 1, thalf);          // of sub-tile u-1
@@ -499,15 +530,8 @@ __device__ __attribute__((noinline)) void kv_role(const KvArgs* args_generic) {
             __builtin_amdgcn_sched_barrier(0);
         };
 
-        {   // prologue: the same loads and barriers as A; fragments and row values of sub-tile 0
-            const TileSrc t0s = next_tile(0);
-#pragma unroll
-            for (int n = 0; n < 9; ++n) dma_piece(t0s, n);
-            dma_wait();
+        {   // prologue: A's barrier publishes tile 0; fragments and row values of sub-tile 0
             __syncthreads();
-            const TileSrc t1s = next_tile(1);
-#pragma unroll
-            for (int n = 0; n < 9; ++n) dma_piece(t1s, n);
 #pragma unroll
             for (int t8 = 0; t8 < 8; ++t8) ga[t8] = ld_g(t8, 0);
             ld_rows(nd, 0);
@@ -519,11 +543,9 @@ __device__ __attribute__((noinline)) void kv_role(const KvArgs* args_generic) {
         auto tile_iter = [&]() __attribute__((always_inline)) {
             const int nbuf = buf + 1 == KV_NBUF ? 0 : buf + 1;
             const int nnbuf = nbuf + 1 == KV_NBUF ? 0 : nbuf + 1;
-            const TileSrc ts = next_tile(nnbuf);
-            dma_wait();
-            __syncthreads();
+            wg_barrier();
             // first half: reads P of the previous tile's second sub-tile (parity 1)
-            stage(std::integral_constant<int, 0>{}, ya, yb, ts, slot0 + KV_SLOT_B);
+            stage(std::integral_constant<int, 0>{}, ya, yb, slot0 + KV_SLOT_B);
             // between the halves the row-wise reads move on to tile T+1 and the transposed reads
             // to tile T (the first tile has no predecessor: they already sit on tile 0)
 #pragma unroll
@@ -536,8 +558,8 @@ __device__ __attribute__((noinline)) void kv_role(const KvArgs* args_generic) {
                     tofs[db][1] += buf == 0 ? back : fwd;
                 }
             }
-            __syncthreads();
-            stage(std::integral_constant<int, 1>{}, yb, ya, ts, slot0);
+            wg_barrier();
+            stage(std::integral_constant<int, 1>{}, yb, ya, slot0);
             first = false;
             buf = nbuf;
         };
