@@ -296,7 +296,9 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
                 tofs[g - 5][0] += tbump;
                 tofs[g - 5][1] += tbump;
             }
-            if (g >= 38 && !(g & 1)) ta[(g - 38) >> 1] = ld_t((g - 38) >> 1, hb);
+            // (in the odd groups 17-25, which carry no other LDS read and no vector ALU work: every LDS
+            // read of an iteration is out by group 36, and the wait in front of the tile barrier finds none)
+            if (g >= 17 && g <= 25 && (g & 1)) ta[(g - 17) >> 1] = ld_t((g - 17) >> 1, hb);
             // row-wise fragments of sub-tile u+1
             if (g >= 6 && g <= 34 && ((g - 6) & 3) == 0) ka[(g - 6) >> 2] = ld_k((g - 6) >> 2, hb ? 0 : 1);
             if (g >= 8 && g <= 36 && ((g - 8) & 3) == 0) va[(g - 8) >> 2] = ld_v((g - 8) >> 2, hb ? 0 : 1);

@@ -239,6 +239,11 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_mfma_kernel(
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) pf[cb][ks] = u32x4{0u, 0u, 0u, 0u};
     bf16x8 ka[8], va[2][4];   // K fragments of sub-tile u+1, V fragments of sub-tile u-1
+    // The last two V fragments have a spare register set each (indexed by the parity of the
+    // iteration that USES them): the next iteration's copies are requested before this
+    // iteration's last use, so no LDS read is issued in the last groups and the wait in front of
+    // the tile barrier finds nothing outstanding.
+    bf16x8 vb6[2], vb7[2];
 
     // Iteration u (sub-tile hb of a tile; MASKED: it may hold hidden keys).  On entry: x = S(u),
     // ka = K fragments of sub-tile u+1, va = V fragments of sub-tile u-1, pf = P(u-1); on exit
@@ -267,17 +272,20 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_mfma_kernel(
 #endif
                 else         mma_vd(y[cb], ka[t8], qraw[cb][t8]);
             } else {
-                const int i = g - 16, ks = i >> 3, db = (i >> 1) & 3, cb = i & 1;
-                acc[db][cb] = mma(va[ks][db], __builtin_bit_cast(bf16x8, pf[cb][ks]), acc[db][cb]);
+                const int i = g - 16, ks = i >> 3, db = (i >> 1) & 3, cb = i & 1, p = 4 * ks + db;
+                const bf16x8 vf_ = p == 6 ? vb6[hb] : p == 7 ? vb7[hb] : va[ks][db];
+                acc[db][cb] = mma(vf_, __builtin_bit_cast(bf16x8, pf[cb][ks]), acc[db][cb]);
             }
             __builtin_amdgcn_sched_barrier(0);   // the matrix-core instruction leads its group
             if (hb == 0 && g < 8) dma_piece(ts, g);
             // refill the fragment register the previous two groups used last
             if (g >= 2 && g <= 16 && !(g & 1)) ka[(g - 2) >> 1] = ld_k((g - 2) >> 1, hb);
-            if (g >= 18 && !(g & 1)) {
+            if (g >= 18 && g <= 28 && !(g & 1)) {
                 const int i = g - 18;
                 va[i >> 3][(i >> 1) & 3] = ld_v(i >> 3, (i >> 1) & 3, hb);
             }
+            if (g == 25) vb6[1 - hb] = ld_v(1, 2, hb);
+            if (g == 27) vb7[1 - hb] = ld_v(1, 3, hb);
             // the LDS reads go out right behind the matrix-core instruction, ahead of the vector ALU work
             __builtin_amdgcn_sched_barrier(0);
             {   // softmax element g; the pair before it is rounded, packed and summed
@@ -295,7 +303,6 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_mfma_kernel(
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-        va[1][3] = ld_v(1, 3, hb);
         pn[1][1][3] = pack_bf16x2(pe[30], pe[31]);
         l_run[1] += pe[30] + pe[31];
 #pragma unroll
@@ -349,6 +356,8 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_mfma_kernel(
         for (int ks = 0; ks < 2; ++ks)     // placeholder for "V of sub-tile -1": multiplied by P = 0
 #pragma unroll
             for (int db = 0; db < 4; ++db) va[ks][db] = lds_frag_t(sm.v[0], 16 * ks, 32 * db, lane);
+        vb6[0] = va[1][2];
+        vb7[0] = va[1][3];
     }
     // Four LDS buffers, tile t in buffer t % 4.  The one barrier per tile opens the iteration of
     // the tile's first sub-tile: it publishes tile t+1 (read from this iteration on; its loads
@@ -384,8 +393,10 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_mfma_kernel(
         for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
             for (int db = 0; db < 4; ++db) {
-                acc[db][0] = mma(va[ks][db], __builtin_bit_cast(bf16x8, pf[0][ks]), acc[db][0]);
-                acc[db][1] = mma(va[ks][db], __builtin_bit_cast(bf16x8, pf[1][ks]), acc[db][1]);
+                const int p = 4 * ks + db;
+                const bf16x8 vf_ = p == 6 ? vb6[0] : p == 7 ? vb7[0] : va[ks][db];
+                acc[db][0] = mma(vf_, __builtin_bit_cast(bf16x8, pf[0][ks]), acc[db][0]);
+                acc[db][1] = mma(vf_, __builtin_bit_cast(bf16x8, pf[1][ks]), acc[db][1]);
             }
     }
 #if CART_PRESCALE
