@@ -2,17 +2,13 @@
 // the gradient of Eq. 1 over the cache of Sec. 3.2 with respect to Q, the own K/V and the
 // trainable prefix Z (Sec. 3.2 trains Z by back-propagation with the model frozen).
 //
-// Three kernels, each with one 64-wide operand block held stationary in registers per wavefront
-// and the other side streamed through LDS in tiles of 64 rows (sub-tiles of 32), in the same
-// software pipeline as the forward kernel; the probabilities are recomputed from the saved
-// log-sum-exp, so there is no running max and no rescale:
-//   dq kernel   (queries stationary): S^T = K Q^T, dP^T = V dO^T, dQ^T += K^T dS^T
-//   dk kernel   (keys stationary):    S = Q K^T,  dP = dO V^T,   dK^T += Q^T dS
-//   dv kernel   (keys stationary):    S = Q K^T,                 dV^T += dO^T P
-// with P = exp(scale S - lse), dS = P (dP - delta), delta_i = dO_i . O_i.  Nothing uses atomics:
-// a key-stationary workgroup owns its keys' gradients over the token rows it streams; prefix-slot
-// gradients are written as fp32 partials, one per chunk of token rows, and summed by
-// dz_reduce_kernel in a fixed order, so results are bit-reproducible.
+// This file: the dQ kernel (queries stationary: S^T = K Q^T, dP^T = V dO^T, dQ^T += K^T dS^T, with
+// P = exp(scale S - lse), dS = P (dP - delta), delta_i = dO_i . O_i formed in its prologue and
+// written out for the key-side kernel), the fixed-order reduction of the prefix-gradient partials,
+// and the launcher of the whole backward call.  dK, dV and the partials of dZ come from the
+// key-stationary kernel of attn_mfma_bwd_kv.hip.  The probabilities are recomputed from the saved
+// log-sum-exp, so there is no running max and no rescale; nothing uses atomics, so results are
+// bit-reproducible.
 #include "attn_mfma.h"
 
 namespace cart {
@@ -27,16 +23,7 @@ using namespace mfma;
 
 constexpr int BWD_TILE = 64;                      // rows per LDS tile
 constexpr int BWD_TILE_B = BWD_TILE * ROW_B;
-constexpr int BWD_NBUF = 3;
 constexpr int BWD_WG_ROWS = 256;                  // stationary rows per workgroup (4 x 64)
-// Prefix-slot gradients: the token rows are streamed in chunks, one fp32 partial per chunk.  The
-// chunk is sized to give about this many prefix workgroups (few, long streams and few partials,
-// yet enough workgroups to balance the chip), but never below 2048 rows.
-#ifndef BWD_PREFIX_WGS
-#define BWD_PREFIX_WGS 256
-#endif
-constexpr int BWD_MIN_CHUNK = 2048;
-
 // store a transposed accumulator block set: lane owns output row `row_ptr` (nullptr: skip),
 // register r of block db holds column 32 db + 8 (r/4) + 4 g + r%4
 __device__ __forceinline__ void store_rows_bf16(const f32x16 (&acc)[4], bf16_t* row_ptr, int lg, float mul) {
@@ -48,17 +35,6 @@ __device__ __forceinline__ void store_rows_bf16(const f32x16 (&acc)[4], bf16_t* 
             u32x2 w = {pack_bf16x2(acc[db][4 * r4] * mul, acc[db][4 * r4 + 1] * mul),
                        pack_bf16x2(acc[db][4 * r4 + 2] * mul, acc[db][4 * r4 + 3] * mul)};
             *reinterpret_cast<u32x2*>(row_ptr + 32 * db + 8 * r4 + 4 * lg) = w;
-        }
-}
-__device__ __forceinline__ void store_rows_f32(const f32x16 (&acc)[4], float* row_ptr, int lg, float mul) {
-    if (!row_ptr) return;
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-            f32x4 w = {acc[db][4 * r4] * mul, acc[db][4 * r4 + 1] * mul, acc[db][4 * r4 + 2] * mul,
-                       acc[db][4 * r4 + 3] * mul};
-            *reinterpret_cast<f32x4*>(row_ptr + 32 * db + 8 * r4 + 4 * lg) = w;
         }
 }
 
@@ -397,501 +373,6 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dq_kernel(
     }
 }
 
-// =================================================================================================
-// dK / dV: keys stationary
-// =================================================================================================
-// One workgroup = 256 keys of one (sequence, KV head): a block of prefix slots, or a block of the
-// sequence's own tokens; each wavefront keeps 64 of them as B-operand fragments in accumulation
-// registers (K scaled by c = softmax_scale * log2(e), so scores come out in log2 units).  It
-// streams the queries that see those keys (all tokens of all heads of the group for prefix slots,
-// tokens at or after the block for own keys) through LDS in tiles of 64 rows of Q and dO plus the
-// rows' -lse2 and -delta, which start the score and dP products as their init values:
-//   S = Q K^T - lse2 -> P = 2^S,   dP = dO V^T - delta,   dS = P dP,
-//   dV^T += dO^T P   (dV kernel),   dK^T += Q^T dS   (dK kernel).
-// Tiles all of whose (query, key) pairs are visible come first, through a loop without masking
-// code; the tiles on the diagonal and the ragged last tile of each head follow through a copy of
-// the loop that masks.  Every iteration is laid out as fenced groups of one matrix-core
-// instruction plus its share of the vector-ALU work, LDS fragment loads and direct-to-LDS loads.
-template <int NBUF>
-struct KsSmem {
-    struct { char q[BWD_TILE_B]; char g[BWD_TILE_B]; } t[NBUF];
-    float nl2[NBUF][BWD_TILE];
-    float ndl[NBUF][BWD_TILE];
-};
-
-template <bool IS_DK>
-__global__ __launch_bounds__(256, 1) void attn_bwd_kstat_kernel(
-    const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
-    const bf16_t* __restrict__ zk, const bf16_t* __restrict__ zv, const bf16_t* __restrict__ d_o,
-    const float* __restrict__ nlse2, const float* __restrict__ ndelta, bf16_t* __restrict__ out_own,
-    float* __restrict__ part, const int32_t* __restrict__ cu, int n_tok, int chunk, int B, int Smax, int Hq,
-    int Hkv, int P, float c, float scale) {
-    // dV fetches every fragment a whole iteration ahead: a tile is read in two consecutive tile
-    // iterations, three buffers.  dK fetches the transposed fragments of the previous sub-tile a
-    // few groups ahead of their use, i.e. one tile iteration later: four buffers.
-    constexpr int NBUF = IS_DK ? 4 : 3;
-    constexpr int BUF_B = 2 * BWD_TILE_B;     // one buffer: Q tile, dO tile
-    constexpr int G_OFF = BWD_TILE_B;         // dO tile inside a buffer
-    __shared__ KsSmem<NBUF> sm;
-    const int G = Hq / Hkv;
-    const int nPb = (P + BWD_WG_ROWS - 1) / BWD_WG_ROWS, nOb = (Smax + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
-    const int nKb = nPb + nOb;
-    // workgroup -> (KV head, key block, chunk of token rows | sequence): KV head fastest (one head
-    // per XCD with 8 KV heads).  A prefix key sees every token whatever sequence it belongs to, so
-    // the prefix blocks stream all token rows (n_tok of them, [B,S] or packed alike) in chunks,
-    // one partial dZ per chunk; the blocks of one chunk run together and share its Q / dO stream
-    // in L2.  They come first (the long ones); the own-key blocks of the sequences follow.
-    int id = blockIdx.x;
-    const int hk = id % Hkv; id /= Hkv;
-    int kb_, b_;
-    SeqSpan sp;
-    const int nChunk = (n_tok + chunk - 1) / chunk;
-    if (id < nPb * nChunk) {
-        kb_ = id % nPb;
-        b_ = id / nPb;
-        sp.t0 = static_cast<size_t>(b_) * chunk;
-        sp.len = min(chunk, n_tok - b_ * chunk);
-        sp.stat_b = sp.stat_h = 0;      // (not used here: the statistics are indexed by token row)
-    } else {
-        id -= nPb * nChunk;
-        kb_ = nPb + id % nOb;
-        b_ = id / nOb;
-        sp = seq_span(cu, b_, n_tok, Smax, Hq);
-    }
-    const int kb = kb_, b = b_;      // for a prefix block b is the chunk
-    const bool pre = kb < nPb;
-    const int key0 = (pre ? kb : kb - nPb) * BWD_WG_ROWS;
-    const int S = sp.len;
-    const size_t t0 = sp.t0;
-    const int nkeys = pre ? P : S;
-    const int lane = threadIdx.x & 63, lg = lane >> 5, lc = lane & 31;
-    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int wkey0 = key0 + 64 * wv;
-    // packed layout: the grid covers the longest sequence; an own-key block past the end of its
-    // sequence has nothing to do
-    if (!pre && key0 >= S) return;
-
-    // this wavefront's 64 keys as B operands: column = key, k = head element
-    u32x4 kf[2][8], vf[2][8];
-#pragma unroll
-    for (int kc = 0; kc < 2; ++kc) {
-        const int key = min(wkey0 + 32 * kc + lc, nkeys - 1);
-        const size_t row = pre ? static_cast<size_t>(hk) * P + key
-                               : (t0 + key) * Hkv + hk;
-        const bf16_t* kp = (pre ? zk : k) + row * HD + 8 * lg;
-        const bf16_t* vp = (pre ? zv : v) + row * HD + 8 * lg;
-#pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            const u32x4 w = *reinterpret_cast<const u32x4*>(kp + 16 * t);
-#if CART_PRESCALE
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                kf[kc][t][i] = pack_bf16x2(__uint_as_float(w[i] << 16) * c, __uint_as_float(w[i] & 0xffff0000u) * c);
-#else
-            kf[kc][t] = w;
-#endif
-            if (IS_DK) vf[kc][t] = *reinterpret_cast<const u32x4*>(vp + 16 * t);
-        }
-    }
-    f32x16 acc[4][2];   // dK^T or dV^T: [head-element block][key block]
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int kc = 0; kc < 2; ++kc)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[db][kc][r] = 0.f;
-    // the stationary fragments and the accumulators live in accumulation registers
-    auto pin = [&]() __attribute__((always_inline)) {
-#pragma unroll
-        for (int kc = 0; kc < 2; ++kc)
-#pragma unroll
-            for (int t = 0; t < 8; ++t) {
-                asm volatile("" : "+a"(kf[kc][t]));
-                if (IS_DK) asm volatile("" : "+a"(vf[kc][t]));
-            }
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-            for (int kc = 0; kc < 2; ++kc) asm volatile("" : "+a"(acc[db][kc]));
-    };
-    pin();
-
-    // The stream of query tiles (64 token rows of one head).  Per head: whole tiles entirely
-    // after the block's last key [qtF0, nFullEnd) need no mask; the tiles on the diagonal
-    // [qt0, qtF0) and the ragged last tile do.  Order: the unmasked tiles of every head, then the
-    // masked tiles of every head.
-    const int nQtAll = (S + BWD_TILE - 1) / BWD_TILE, nFullEnd = S / BWD_TILE;
-    const int qt0 = pre ? 0 : key0 / BWD_TILE;
-    const int qtF0 = pre ? 0 : qt0 + BWD_WG_ROWS / BWD_TILE;
-    const int nFull = max(0, nFullEnd - qtF0);
-    const int nM1 = min(qtF0, nQtAll) - qt0;
-    const int nM = nM1 + ((nFullEnd < nQtAll && nFullEnd >= qtF0) ? 1 : 0);
-    const int nMain = G * nFull, nT = G * (nFull + nM);
-    const char* q_c = reinterpret_cast<const char*>(q);
-    const char* g_c = reinterpret_cast<const char*>(d_o);
-    const uint32_t q_pitch = static_cast<uint32_t>(Hq) * ROW_B;
-    // iterator over that order (all scalar): phase 0 = unmasked, 1 = masked
-    int it_ph = nFull > 0 ? 0 : 1, it_g = 0, it_n = 0, it_cnt = 0;
-    struct TileSrc { const char* qb; const char* gb; const char* rb; int lim; int i0; uint32_t lds_q, lds_g, lds_r; };
-    const uint32_t dma_c0 = (lane & 15) ^ (((lane >> 4) & 3) << 2);
-    // describes the iterator's tile as the source of a load into buffer buf, then advances
-    auto next_tile = [&](int buf) __attribute__((always_inline)) {
-        const int qt = it_ph == 0 ? qtF0 + it_n : (it_n < nM1 ? qt0 + it_n : nFullEnd);
-        const int h = hk * G + it_g;
-        TileSrc ts;
-        ts.i0 = qt * BWD_TILE;
-        const size_t base = (t0 * Hq + h) * ROW_B + static_cast<size_t>(ts.i0) * q_pitch;
-        ts.qb = q_c + base;
-        ts.gb = g_c + base;
-        ts.lim = S - 1 - ts.i0;
-        // wavefronts 0 / 2 fetch the rows' -lse2, 1 / 3 their -delta (twice each: no branch)
-        ts.rb = reinterpret_cast<const char*>(((wv & 1) ? ndelta : nlse2) + static_cast<size_t>(h) * n_tok + t0 + ts.i0);
-        ts.lds_q = lds_addr(sm.t[buf].q);
-        ts.lds_g = lds_addr(sm.t[buf].g);
-        ts.lds_r = lds_addr((wv & 1) ? sm.ndl[buf] : sm.nl2[buf]);
-        if (it_cnt < nT - 1) {     // past the end the last tile is fetched again, into a retired buffer
-            ++it_cnt;
-            ++it_n;
-            if (it_n == (it_ph == 0 ? nFull : nM)) {
-                it_n = 0;
-                if (++it_g == G) { it_g = 0; ++it_ph; }
-            }
-        }
-        return ts;
-    };
-    // direct-to-LDS loads of a tile, nine per wavefront: 4 x Q rows, 4 x dO rows, 1 x row values
-    auto dma_piece = [&](const TileSrc& ts, int n) __attribute__((always_inline)) {
-        if (n == 8) {
-            dma4(ts.rb, static_cast<uint32_t>(min(lane, ts.lim)) * 4u, ts.lds_r);
-            return;
-        }
-        const int i = n & 3;
-        const int r0 = (4 * wv + i) * 4;
-        const uint32_t voff = __umul24(min(r0 + (lane >> 4), ts.lim), q_pitch) + ((dma_c0 ^ i) << 4);
-        if (n < 4) dma16(ts.qb, voff, ts.lds_q + r0 * ROW_B);
-        else       dma16(ts.gb, voff, ts.lds_g + r0 * ROW_B);
-    };
-    // a query row of the sub-tile starting at token i0 is hidden from a key when it precedes it
-    // (own keys) or lies past the end of the sequence (clamped tile rows)
-    auto mask1 = [&](f32x16& x, int kc, int i0) __attribute__((always_inline)) {
-        mask_below(x, (pre ? 0 : wkey0 + 32 * kc + lc) - i0 - 4 * lg);
-        mask_above(x, S - 1 - i0 - 4 * lg);
-    };
-
-    // Per-lane LDS addresses of the fragments, complete except for compile-time offsets; they
-    // move from buffer to buffer once per tile.
-    // dV reads row-wise fragments and row values a whole iteration ahead (tile T+1 throughout tile
-    // iteration T) and transposed fragments of the current sub-tile (tile T); dK reads row-wise
-    // fragments a few groups ahead (tile T in the first half of iteration T, T+1 in the second)
-    // and transposed fragments of the previous sub-tile (tile T-1, then T).
-    uint32_t qofs[8];      // row-wise Q fragment t8 (dO: + G_OFF)
-    uint32_t tofs[4][2];   // transposed fragment of head-element block db: of dO (dV), of Q (dK)
-    uint32_t rofs;         // -lse2 of rows 4 lg .. +3 (-delta: + R_OFF)
-    {
-        const uint32_t t1 = lds_addr(IS_DK ? sm.t[0].q : sm.t[1].q), t0 = lds_addr(IS_DK ? sm.t[0].q : sm.t[0].g);
-#pragma unroll
-        for (int t8 = 0; t8 < 8; ++t8) qofs[t8] = t1 + frag_n_ofs(lane, t8);
-#pragma unroll
-        for (int db = 0; db < 4; ++db) {
-            frag_t_ofs(lane, db, tofs[db][0], tofs[db][1]);
-            tofs[db][0] += t0;
-            tofs[db][1] += t0;
-        }
-        rofs = lds_addr(&sm.nl2[IS_DK ? 0 : 1][4 * lg]);
-    }
-    uint32_t rofs_c = lds_addr(&sm.nl2[0][4 * lg]);   // dV, exact mode: the same rows of tile T
-    constexpr int R_OFF = NBUF * BWD_TILE * 4;     // -delta rows behind the -lse2 rows
-    // fragment loads; hb = which 32-row half of the tile
-    auto ld_q = [&](int t8, int hb) __attribute__((always_inline)) { return lds_ld_frag(qofs[t8] + hb * 32 * ROW_B); };
-    auto ld_g = [&](int t8, int hb) __attribute__((always_inline)) { return lds_ld_frag(qofs[t8] + G_OFF + hb * 32 * ROW_B); };
-    auto ld_t = [&](int p, int hb) __attribute__((always_inline)) {
-        const int ks = p >> 2, db = p & 3;
-        return lds_ld_frag_t(tofs[db][0] + (32 * hb + 16 * ks) * ROW_B, tofs[db][1] + (32 * hb + 16 * ks) * ROW_B);
-    };
-    // init values of the score (dP) products of a sub-tile: register r <-> row 8 (r/4) + 4 lg + r%4
-    auto ld_rows_at = [&](f32x16& d, uint32_t base, int ofs, int hb) __attribute__((always_inline)) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const f32x4 w = lds_ld_f32x4(base + ofs + (32 * hb + 8 * j) * 4);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) d[4 * j + e] = w[e];
-        }
-    };
-    auto ld_rows = [&](f32x16& d, int ofs, int hb) __attribute__((always_inline)) { ld_rows_at(d, rofs, ofs, hb); };
-
-    u32x4 xf[2][2];       // P or dS of sub-tile u-1 as B-operand fragments [key block][k-step]
-#pragma unroll
-    for (int kc = 0; kc < 2; ++kc)
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) xf[kc][ks] = u32x4{0u, 0u, 0u, 0u};
-    bf16x8 qa[8], ga[8], ta[8];   // row-wise Q, dO fragments; transposed fragments [2 ks + ... ]
-    // -lse2 / -delta of a sub-tile's rows: nd is the init value of the next dP products; nl is the
-    // init value of the next score products (pre-scaled mode) or the addend of the current
-    // sub-tile's exponents, with the next sub-tile's values arriving in nl_n (exact mode)
-    f32x16 nl, nd, nl_n;
-    f32x16 xa[2], xb[2];          // dV: scores, two sets used alternately
-    f32x16 x1, y1, x0a, x0b, y0a, y0b;   // dK: key block 1 single, key block 0 two sets
-
-    // ---------------------------------------------------------------------------------------------
-    // dV iteration u (half hb of tile T): 32 groups.  On entry xin = S(u), qa = Q fragments of
-    // sub-tile u+1, nl = its init values, ta = transposed dO fragments of sub-tile u-1, xf = P(u-1).
-    // Matrix cores: S(u+1) (groups 0-15), dV^T += dO^T P(u-1) (groups 16-31); vector ALU: P(u).
-    // ---------------------------------------------------------------------------------------------
-    auto stage_dv = [&](auto hb_tag, auto masked_tag, int i0, f32x16 (&xin)[2], f32x16 (&xout)[2],
-                        const TileSrc& ts) __attribute__((always_inline)) {
-        constexpr int hb = decltype(hb_tag)::value;
-        constexpr bool MASKED = decltype(masked_tag)::value;
-        if (MASKED) { mask1(xin[0], 0, i0 + 32 * hb); mask1(xin[1], 1, i0 + 32 * hb); }
-        pin();
-        float pe[32];
-        u32x4 xn[2][2];
-        static_for<32>([&](auto gc) __attribute__((always_inline)) {
-            constexpr int g = decltype(gc)::value;
-            if (g < 16) {
-                const int t8 = g >> 1, kc = g & 1;
-                if (t8 == 0 && CART_PRESCALE) mma_vd_first(xout[kc], qa[0], kf[kc][0], nl);
-                else if (t8 == 0)             mma_vd_zero(xout[kc], qa[0], kf[kc][0]);
-                else                          mma_vd(xout[kc], qa[t8], kf[kc][t8]);
-            } else {
-                const int i = g - 16, ks = i >> 3, db = (i >> 1) & 3, kc = i & 1;
-                acc[db][kc] = mma(ta[4 * ks + db], __builtin_bit_cast(bf16x8, xf[kc][ks]), acc[db][kc]);
-            }
-            __builtin_amdgcn_sched_barrier(0);   // the matrix-core instruction leads its group
-            if (hb == 0 && g < 9) dma_piece(ts, g);
-            // refill what the previous two groups used last: for sub-tile u+2 / of sub-tile u
-            if (CART_PRESCALE && g == 2) ld_rows(nl, 0, hb);                 // of sub-tile u+2
-            if (!CART_PRESCALE && g == 20) ld_rows_at(nl_n, hb ? rofs : rofs_c, 0, 1 - hb);   // of sub-tile u+1
-            if (g >= 2 && g <= 16 && !(g & 1)) qa[(g - 2) >> 1] = ld_q((g - 2) >> 1, hb);
-            if (g >= 18 && !(g & 1)) ta[(g - 18) >> 1] = ld_t((g - 18) >> 1, hb);
-            __builtin_amdgcn_sched_barrier(0);   // LDS reads first, then the vector ALU work
-            {
-                const int kc = g >> 4, r = g & 15;
-                pe[g] = fast_exp2(CART_PRESCALE ? xin[kc][r] : fmaf(xin[kc][r], c, nl[r]));
-                if (g >= 2 && !(g & 1)) {
-                    const int e = g - 2;
-                    xn[e >> 4][(e & 15) >> 3][(e & 7) >> 1] = pack_bf16x2(pe[e], pe[e + 1]);
-                }
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        });
-        ta[7] = ld_t(7, hb);
-        if (!CART_PRESCALE) nl = nl_n;
-        xn[1][1][3] = pack_bf16x2(pe[30], pe[31]);
-#pragma unroll
-        for (int kc = 0; kc < 2; ++kc)
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks) xf[kc][ks] = xn[kc][ks];
-        __builtin_amdgcn_sched_barrier(0);
-    };
-
-    // ---------------------------------------------------------------------------------------------
-    // dK iteration u: 48 groups.  Key block 1's scores / dP live in one register set, key block
-    // 0's in two used alternately.  Groups 0-15: dK^T += Q^T dS(u-1) on the matrix cores while the
-    // vector ALU turns block 1 of sub-tile u into dS; groups 16-47: S(u+1), dP(u+1) (block 1's
-    // overwrite what was just consumed) while the vector ALU does block 0.  Fragments are fetched
-    // about ten groups ahead of their use.
-    // ---------------------------------------------------------------------------------------------
-    auto stage_dk = [&](auto hb_tag, auto masked_tag, int i0, f32x16& x0in, f32x16& y0in, f32x16& x0out,
-                        f32x16& y0out, const TileSrc& ts, uint32_t tbump) __attribute__((always_inline)) {
-        constexpr int hb = decltype(hb_tag)::value;
-        constexpr bool MASKED = decltype(masked_tag)::value;
-        if (MASKED) {
-            // the last score products of the previous iteration were issued only two groups ago
-            // and the compiler does not know they are matrix-core results: let them retire
-            asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
-            mask1(x0in, 0, i0 + 32 * hb);
-            mask1(x1, 1, i0 + 32 * hb);
-        }
-        pin();
-        float w0[16], w1[16], e0[16], e1[16];
-        u32x4 xn[2][2];
-        static_for<48>([&](auto gc) __attribute__((always_inline)) {
-            constexpr int g = decltype(gc)::value;
-            if (g < 16) {
-                const int ks = g >> 3, db = (g >> 1) & 3, kc = g & 1;
-                acc[db][kc] = mma(ta[4 * ks + db], __builtin_bit_cast(bf16x8, xf[kc][ks]), acc[db][kc]);
-            } else {
-                const int j = g - 16, t8 = j >> 2, which = j & 3;   // block 1 first: its results are read first
-                if (which == 0)      { if (t8 == 0 && CART_PRESCALE) mma_vd_first(x1, qa[0], kf[1][0], nl); else if (t8 == 0) mma_vd_zero(x1, qa[0], kf[1][0]); else mma_vd(x1, qa[t8], kf[1][t8]); }
-                else if (which == 1) { if (t8 == 0) mma_vd_first(y1, ga[0], vf[1][0], nd); else mma_vd(y1, ga[t8], vf[1][t8]); }
-                else if (which == 2) { if (t8 == 0 && CART_PRESCALE) mma_vd_first(x0out, qa[0], kf[0][0], nl); else if (t8 == 0) mma_vd_zero(x0out, qa[0], kf[0][0]); else mma_vd(x0out, qa[t8], kf[0][t8]); }
-                else                 { if (t8 == 0) mma_vd_first(y0out, ga[0], vf[0][0], nd); else mma_vd(y0out, ga[t8], vf[0][t8]); }
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            if (hb == 0 && g >= 16 && g < 25) dma_piece(ts, g - 16);
-            // transposed Q fragments of sub-tile u-1 (groups 0-8) and, for the next iteration, u
-            if (g <= 4 && !(g & 1)) ta[5 + (g >> 1)] = ld_t(5 + (g >> 1), 1 - hb);
-            if (hb == 0 && g >= 5 && g < 9) {       // then the addresses move on to tile T
-                tofs[g - 5][0] += tbump;
-                tofs[g - 5][1] += tbump;
-            }
-            if (g >= 38 && !(g & 1)) ta[(g - 38) >> 1] = ld_t((g - 38) >> 1, hb);
-            // row-wise fragments and init values of sub-tile u+1
-            if (g == 3) ld_rows(CART_PRESCALE ? nl : nl_n, 0, hb ? 0 : 1);
-            if (g == 5) ld_rows(nd, R_OFF, hb ? 0 : 1);
-            if (g >= 6 && g <= 34 && ((g - 6) & 3) == 0) qa[(g - 6) >> 2] = ld_q((g - 6) >> 2, hb ? 0 : 1);
-            if (g >= 8 && g <= 36 && ((g - 8) & 3) == 0) ga[(g - 8) >> 2] = ld_g((g - 8) >> 2, hb ? 0 : 1);
-            // The LDS reads go out right behind the matrix-core instruction, the vector ALU work
-            // follows; its exponential and the product that consumes it sit a group apart (a
-            // transcendental's consumer right behind it costs a wait state).
-            __builtin_amdgcn_sched_barrier(0);
-            // vector ALU: block 1 element g (groups 0-15), block 0 element (g-16)/2 (even groups after)
-            if (g < 16) {
-                e1[g] = fast_exp2(CART_PRESCALE ? x1[g] : fmaf(x1[g], c, nl[g]));
-                if (g >= 1) w1[g - 1] = e1[g - 1] * y1[g - 1];
-                if (g >= 3 && (g & 1)) xn[1][(g - 3) >> 3][((g - 3) & 7) >> 1] = pack_bf16x2(w1[g - 3], w1[g - 2]);
-            } else if (!(g & 1)) {
-                const int r = (g - 16) >> 1;
-                if (r == 0) w1[15] = e1[15] * y1[15];
-                if (r == 1) xn[1][1][3] = pack_bf16x2(w1[14], w1[15]);
-                e0[r] = fast_exp2(CART_PRESCALE ? x0in[r] : fmaf(x0in[r], c, nl[r]));
-                if (r >= 1) w0[r - 1] = e0[r - 1] * y0in[r - 1];
-                if (r >= 3 && (r & 1)) xn[0][(r - 3) >> 3][((r - 3) & 7) >> 1] = pack_bf16x2(w0[r - 3], w0[r - 2]);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        });
-        w0[15] = e0[15] * y0in[15];
-        xn[0][1][3] = pack_bf16x2(w0[14], w0[15]);
-        if (!CART_PRESCALE) nl = nl_n;
-#pragma unroll
-        for (int kc = 0; kc < 2; ++kc)
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks) xf[kc][ks] = xn[kc][ks];
-        __builtin_amdgcn_sched_barrier(0);
-    };
-    auto settle = [&]() __attribute__((always_inline)) { asm volatile("s_nop 15\n\ts_nop 7" ::: "memory"); };
-
-    // ---- prologue: tiles 0 and 1 on their way, scores of sub-tile 0, fragments of sub-tile 1 ----
-    int i0_cur, i0_nx;
-    {
-        const TileSrc t0 = next_tile(0);
-        i0_cur = t0.i0;
-#pragma unroll
-        for (int n = 0; n < 9; ++n) dma_piece(t0, n);
-        dma_wait();
-        __syncthreads();
-        const TileSrc t1 = next_tile(1);
-        i0_nx = t1.i0;
-#pragma unroll
-        for (int n = 0; n < 9; ++n) dma_piece(t1, n);
-        // (dV's row-wise addresses point one buffer ahead: step back for tile 0)
-        constexpr int QB = IS_DK ? 0 : BUF_B, RB = IS_DK ? 0 : BWD_TILE * 4;
-#pragma unroll
-        for (int t8 = 0; t8 < 8; ++t8) {
-            qa[t8] = lds_ld_frag(qofs[t8] - QB);
-            if (IS_DK) ga[t8] = lds_ld_frag(qofs[t8] + G_OFF);
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const f32x4 a = lds_ld_f32x4(rofs - RB + 8 * j * 4);
-            const f32x4 d = lds_ld_f32x4(rofs - RB + R_OFF + 8 * j * 4);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) { nl[4 * j + e] = a[e]; nd[4 * j + e] = d[e]; }
-        }
-        f32x16 (&s0)[2] = xa;
-#pragma unroll
-        for (int t8 = 0; t8 < 8; ++t8) {
-            f32x16& sx0 = IS_DK ? x0a : s0[0];
-            f32x16& sx1 = IS_DK ? x1 : s0[1];
-            if (t8 == 0 && CART_PRESCALE) { mma_vd_first(sx0, qa[0], kf[0][0], nl); mma_vd_first(sx1, qa[0], kf[1][0], nl); }
-            else if (t8 == 0)             { mma_vd_zero(sx0, qa[0], kf[0][0]);      mma_vd_zero(sx1, qa[0], kf[1][0]); }
-            else                          { mma_vd(sx0, qa[t8], kf[0][t8]);         mma_vd(sx1, qa[t8], kf[1][t8]); }
-            if (IS_DK) {
-                if (t8 == 0) { mma_vd_first(y0a, ga[0], vf[0][0], nd); mma_vd_first(y1, ga[0], vf[1][0], nd); }
-                else         { mma_vd(y0a, ga[t8], vf[0][t8]);         mma_vd(y1, ga[t8], vf[1][t8]); }
-            }
-        }
-        settle();
-        if (IS_DK) {
-            // steady state on entry of the first iteration: fragments of sub-tile u-1 for the
-            // matrix cores (xf = 0: a placeholder tile), nothing else carried
-#pragma unroll
-            for (int p = 0; p < 5; ++p) ta[p] = ld_t(p, 0);
-        } else {
-#pragma unroll
-            for (int t8 = 0; t8 < 8; ++t8) qa[t8] = lds_ld_frag(qofs[t8] - BUF_B + 32 * ROW_B);   // sub-tile 1
-            if (CART_PRESCALE) {     // init values of sub-tile 1 (exact mode keeps sub-tile 0's rows)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const f32x4 a = lds_ld_f32x4(rofs - BWD_TILE * 4 + (32 + 8 * j) * 4);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) nl[4 * j + e] = a[e];
-                }
-            }
-#pragma unroll
-            for (int p = 0; p < 8; ++p) ta[p] = ld_t(p, 0);     // placeholder: multiplied by P = 0
-        }
-    }
-    // Tile T lives in buffer T % NBUF.  The one barrier per tile publishes tile T+1 and retires
-    // the buffer that receives tile T+2.
-    int buf = 0;
-    bool first = true;
-    auto tile_iter = [&](auto masked_tag) __attribute__((always_inline)) {
-        const int nbuf = buf + 1 == NBUF ? 0 : buf + 1;
-        const int nnbuf = nbuf + 1 == NBUF ? 0 : nbuf + 1;
-        const TileSrc ts = next_tile(nnbuf);
-        const uint32_t fwd = static_cast<uint32_t>(BUF_B), back = static_cast<uint32_t>(-(NBUF - 1) * BUF_B);
-        const uint32_t rfwd = static_cast<uint32_t>(BWD_TILE * 4), rback = static_cast<uint32_t>(-(NBUF - 1) * BWD_TILE * 4);
-        dma_wait();
-        __syncthreads();
-        if (IS_DK) {
-            // the transposed reads still address tile T-1 when the iteration starts (the very
-            // first iteration has no predecessor: its placeholder is tile 0 itself)
-            const uint32_t tb = first ? 0u : (buf == 0 ? back : fwd);
-            stage_dk(std::integral_constant<int, 0>{}, masked_tag, i0_cur, x0a, y0a, x0b, y0b, ts, tb);
-            // the row-wise reads move on to tile T+1 between the two halves
-#pragma unroll
-            for (int t8 = 0; t8 < 8; ++t8) qofs[t8] += nbuf == 0 ? back : fwd;
-            rofs += nbuf == 0 ? rback : rfwd;
-            stage_dk(std::integral_constant<int, 1>{}, masked_tag, i0_cur, x0b, y0b, x0a, y0a, ts, 0u);
-        } else {
-            stage_dv(std::integral_constant<int, 0>{}, masked_tag, i0_cur, xa, xb, ts);
-            stage_dv(std::integral_constant<int, 1>{}, masked_tag, i0_cur, xb, xa, ts);
-#pragma unroll
-            for (int db = 0; db < 4; ++db) {                 // tile T -> T+1
-                tofs[db][0] += nbuf == 0 ? back : fwd;
-                tofs[db][1] += nbuf == 0 ? back : fwd;
-            }
-#pragma unroll
-            for (int t8 = 0; t8 < 8; ++t8) qofs[t8] += nnbuf == 0 ? back : fwd;   // tile T+1 -> T+2
-            rofs += nnbuf == 0 ? rback : rfwd;
-            rofs_c += nbuf == 0 ? rback : rfwd;
-        }
-        first = false;
-        buf = nbuf;
-        i0_cur = i0_nx;
-        i0_nx = ts.i0;
-    };
-    for (int ti = 0; ti < nMain; ++ti) tile_iter(std::false_type{});
-    for (int ti = nMain; ti < nT; ++ti) tile_iter(std::true_type{});
-    {   // drain: the last sub-tile's contribution
-        pin();
-        if (IS_DK) {
-            // fragments 0-4 of the last sub-tile are in registers; the others come from the last
-            // tile's second half (the transposed-read addresses are on that tile)
-#pragma unroll
-            for (int p = 5; p < 8; ++p) ta[p] = ld_t(p, 1);
-        }
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-            for (int db = 0; db < 4; ++db) {
-                acc[db][0] = mma(ta[4 * ks + db], __builtin_bit_cast(bf16x8, xf[0][ks]), acc[db][0]);
-                acc[db][1] = mma(ta[4 * ks + db], __builtin_bit_cast(bf16x8, xf[1][ks]), acc[db][1]);
-            }
-    }
-    const float mul = IS_DK ? scale : 1.f;
-#pragma unroll
-    for (int kc = 0; kc < 2; ++kc) {
-        const int key = wkey0 + 32 * kc + lc;
-        f32x16 col[4] = {acc[0][kc], acc[1][kc], acc[2][kc], acc[3][kc]};
-        if (pre)
-            store_rows_f32(col, key < P ? part + ((static_cast<size_t>(b) * Hkv + hk) * P + key) * HD : nullptr, lg, mul);
-        else
-            store_rows_bf16(col, key < S ? out_own + ((t0 + key) * Hkv + hk) * HD : nullptr, lg, mul);
-    }
-}
-
 // dZ[hk,slot,:] = sum_b part[b,hk,slot,:] in order of b (+ the previous value when accumulating);
 // rows below n_frozen are 0 / left alone.  One 16-byte vector per thread.
 __global__ __launch_bounds__(256) void dz_reduce_kernel(const float* __restrict__ part,
@@ -911,11 +392,7 @@ __global__ __launch_bounds__(256) void dz_reduce_kernel(const float* __restrict_
 
 bool attn_mfma_bwd_supported(const cart_attn_desc& d) { return d.dtype == CART_BF16 && d.D == 128; }
 
-// 1: the split dK and dV kernels (5 contractions per pair between them); 0: the fused kernel of
-// attn_mfma_bwd_kv.hip (4)
-#ifndef CART_BWD_SPLIT
-#define CART_BWD_SPLIT 0
-#endif
+// the fused dK + dV kernel (attn_mfma_bwd_kv.hip)
 int bwd_kv_chunk(const cart_attn_desc& d, long tokens, int* n_part);
 void launch_attn_bwd_kv(const cart_attn_desc& d, float scale, const bf16_t* Q, const bf16_t* K, const bf16_t* V,
                         const bf16_t* ZK, const bf16_t* ZV, const bf16_t* DO, const float* lse2, const float* delta,
@@ -924,25 +401,13 @@ void launch_attn_bwd_kv(const cart_attn_desc& d, float scale, const bf16_t* Q, c
 
 static size_t r256(size_t n) { return (n + 255) & ~static_cast<size_t>(255); }
 
-// token rows per prefix-gradient partial, and the number of partials
-static int bwd_chunk(const cart_attn_desc& d, long tokens, int* n_part) {
-    if (!CART_BWD_SPLIT) return bwd_kv_chunk(d, tokens, n_part);
-    const long nPb = (d.P + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
-    long n = nPb > 0 ? (BWD_PREFIX_WGS + nPb * d.Hkv - 1) / (nPb * d.Hkv) : 1;
-    const long most = (tokens + BWD_MIN_CHUNK - 1) / BWD_MIN_CHUNK;
-    n = n < 1 ? 1 : (n > most ? most : n);
-    const long chunk = (((tokens + n - 1) / n) + BWD_TILE - 1) / BWD_TILE * BWD_TILE;
-    *n_part = static_cast<int>((tokens + chunk - 1) / chunk);
-    return static_cast<int>(chunk);
-}
-
 // beyond the delta array: lse2 (one value per token and head) and the two dZ partial buffers
 // [n_part,Hkv,P,128]; packed layout (tokens >= 0 = the packed row count): + the row_lo array.
 size_t attn_mfma_bwd_workspace(const cart_attn_desc& d, long tokens) {
     const bool packed = tokens >= 0;
     if (!packed) tokens = static_cast<long>(d.B) * d.S;
     int n_part;
-    bwd_chunk(d, tokens, &n_part);
+    bwd_kv_chunk(d, tokens, &n_part);
     const size_t rows = r256(static_cast<size_t>(tokens) * d.Hq * sizeof(float));
     const size_t part = r256(static_cast<size_t>(n_part) * d.Hkv * d.P * HD * sizeof(float));
     return rows + 2 * part + (packed ? r256(static_cast<size_t>(tokens) * sizeof(int32_t)) : 0);
@@ -955,7 +420,7 @@ int launch_attn_bwd_mfma(const cart_attn_desc& d, float scale, const void* q, co
     const long tokens = cu ? T : static_cast<long>(d.B) * d.S;
     const size_t rows_b = r256(static_cast<size_t>(tokens) * d.Hq * sizeof(float));
     int n_part;
-    const int chunk = bwd_chunk(d, tokens, &n_part);
+    const int chunk = bwd_kv_chunk(d, tokens, &n_part);
     const int n_tok = static_cast<int>(tokens);
     const size_t part_b = r256(static_cast<size_t>(n_part) * d.Hkv * d.P * HD * sizeof(float));
     char* w = static_cast<char*>(ws);
@@ -988,20 +453,9 @@ int launch_attn_bwd_mfma(const cart_attn_desc& d, float scale, const void* q, co
                            d.Hq, d.Hkv, d.P, c, scale);
     }
     trace_mark(st);
-#if CART_BWD_SPLIT
-    const long nPb = (d.P + BWD_WG_ROWS - 1) / BWD_WG_ROWS, nOb = (d.S + BWD_WG_ROWS - 1) / BWD_WG_ROWS;
-    const unsigned kgrid = static_cast<unsigned>((nPb * n_part + nOb * d.B) * d.Hkv);
-    hipLaunchKernelGGL(attn_bwd_kstat_kernel<true>, dim3(kgrid), dim3(256), 0, st, Q, K, V, ZK, ZV, DO, lse2,
-                       delta, static_cast<bf16_t*>(dk), part_k, cu, n_tok, chunk, d.B, d.S, d.Hq, d.Hkv, d.P, c, scale);
-    trace_mark(st);
-    hipLaunchKernelGGL(attn_bwd_kstat_kernel<false>, dim3(kgrid), dim3(256), 0, st, Q, K, V, ZK, ZV, DO, lse2,
-                       delta, static_cast<bf16_t*>(dv), part_v, cu, n_tok, chunk, d.B, d.S, d.Hq, d.Hkv, d.P, c, scale);
-    trace_mark(st);
-#else
     launch_attn_bwd_kv(d, scale, Q, K, V, ZK, ZV, DO, lse2, delta, static_cast<bf16_t*>(dk), static_cast<bf16_t*>(dv),
                        part_k, part_v, cu, n_tok, chunk, n_part, st);
     trace_mark(st);
-#endif
     if (d.P > 0) {
         const long n4 = static_cast<long>(d.Hkv) * d.P * HD / 4;
         const unsigned rg = static_cast<unsigned>((n4 + 255) / 256);
