@@ -23,7 +23,9 @@ using namespace mfma;
 
 constexpr int DEC_BM = 128;            // stacked query rows per prefix workgroup (4 x 32)
 constexpr int DEC_BN = 32;             // prefix keys per LDS tile
-constexpr int DEC_NBUF = 4;
+#ifndef DEC_NBUF
+#define DEC_NBUF 4                     // prefix tiles in LDS: one read, one ready, the rest in flight
+#endif
 // Prefix workgroups aimed at: half the CUs.  Measured on the serving shape (128 requests, 8192
 // shared slots, own caches U[1,1024]): 64 -> 131 us, 128 -> 84 us, 192 -> 90 us, 256 -> 94 us,
 // 512 -> 118 us for the whole call.
@@ -32,8 +34,8 @@ constexpr int DEC_TILE_B = DEC_BN * ROW_B;
 constexpr int DEC_SUB = 32;            // own keys per wavefront step
 constexpr int DEC_SUB_B = DEC_SUB * ROW_B;
 
-#ifndef DEC_OWN_CHUNK
-#define DEC_OWN_CHUNK 256              // most keys per own / private-cartridge chunk of short caches
+#ifndef DEC_POOL_CHUNK
+#define DEC_POOL_CHUNK 256             // most keys per chunk of a private cartridge
 #endif
 constexpr int DEC_MAX_SEG = CART_MAX_SEGMENTS;
 
@@ -51,12 +53,27 @@ struct PrefixTable {
 struct DecodePlan {
     PrefixTable tab;
     int G, n_rb, n_ps;                    // prefix: row blocks, partial slots of all segments
-    int chunk, n_cc, n_oc;                // keys per chunk; chunks of a private cartridge / own KV (worst case)
+    int chunk, n_cc;                      // private cartridge: keys per chunk, chunks
+    int share, n_oc, n_own_wg;            // own KV: token rows per range, most ranges a request reaches into, workgroups
     size_t part_o_bytes, part_l_bytes;
 };
 
-// seg_p[n_seg]: slots per shared segment; pool_p: slots of a private cartridge (0 = none)
-static DecodePlan make_plan(int B, int Hq, int Hkv, int max_own_len, const int* seg_p, int n_seg, int pool_p) {
+// workgroups of 256 threads the chip holds at two per CU (per device, looked up once)
+static int resident_wgs() {
+    static int cached[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 512;
+    if (!cached[dev]) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
+        cached[dev] = 2 * cus;
+    }
+    return cached[dev];
+}
+
+// seg_p[n_seg]: slots per shared segment; pool_p: slots of a private cartridge (0 = none);
+// T: rows of the packed own caches
+static DecodePlan make_plan(int B, int Hq, int Hkv, int max_own_len, int T, const int* seg_p, int n_seg, int pool_p) {
     DecodePlan p;
     p.G = Hq / Hkv;
     const int rows = B * p.G;
@@ -81,25 +98,31 @@ static DecodePlan make_plan(int B, int Hq, int Hkv, int max_own_len, const int* 
         p.tab.blk0[k + 1] = p.tab.blk0[k] + Hkv * p.n_rb * p.tab.n_ps[k];
         p.tab.zk[k] = p.tab.zv[k] = nullptr;                        // filled by the launcher
     }
-    p.chunk = (max_own_len > 4096 || pool_p > 4096) ? 1024 : DEC_OWN_CHUNK;
+    p.chunk = pool_p > 4096 ? 1024 : DEC_POOL_CHUNK;
     p.n_cc = (pool_p + p.chunk - 1) / p.chunk;
-    p.n_oc = (max_own_len + p.chunk - 1) / p.chunk;
+    // Own KV: the workgroups that stay resident beside the prefix workgroups, four wavefronts
+    // each, one wavefront per (range of token rows, KV head); the ranges cut T evenly, in whole
+    // steps of 32 rows.
+    const int n_pre_wg = p.n_ps > 0 ? p.tab.blk0[p.tab.n_seg] : 0;
+    long wgs = resident_wgs() - n_pre_wg;
+    if (wgs < 64) wgs = 64;
+    long ranges = 4 * wgs / Hkv;
+    if (ranges < 1) { ranges = 1; wgs = (Hkv + 3) / 4; }
+    long share = ((static_cast<long>(T) + ranges - 1) / ranges + DEC_SUB - 1) / DEC_SUB * DEC_SUB;
+    if (share < DEC_SUB) share = DEC_SUB;
+    const long used = (static_cast<long>(T) + share - 1) / share;            // ranges that hold rows
+    if (p.n_cc == 0 && (used * Hkv + 3) / 4 < wgs) wgs = (used * Hkv + 3) / 4;
+    p.share = static_cast<int>(share);
+    p.n_own_wg = static_cast<int>(wgs);
+    p.n_oc = static_cast<int>((max_own_len + share - 1) / share) + 1;
     const size_t slots = static_cast<size_t>(p.n_ps + p.n_cc + p.n_oc) * B * Hq;
     p.part_o_bytes = (slots * HD * sizeof(float) + 255) & ~static_cast<size_t>(255);
     p.part_l_bytes = (slots * sizeof(float) + 255) & ~static_cast<size_t>(255);
     return p;
 }
 
-// Own rows of a request are split evenly over the n_oc chunk slots (in steps of 32 keys), so that
-// every request keeps all its slots busy whatever its length: keys per chunk of a request.
-__host__ __device__ __forceinline__ int own_chunk_keys(int len, int n_oc) {
-    const int ck = ((len + n_oc - 1) / n_oc + DEC_SUB - 1) & ~(DEC_SUB - 1);
-    return ck < DEC_SUB ? DEC_SUB : ck;
-}
-
 // Prefix role of the fused kernel: 128 stacked query rows (32 per wavefront) against one split of
-// one segment, 32 keys per LDS tile, four tiles in rotation (tile u+1 feeds the next scores while
-// tile u feeds O, tiles u+2 and u+3 are on their way).  Small on purpose -- at most 256 registers
+// one segment, 32 keys per LDS tile, DEC_NBUF tiles in rotation.  Small on purpose -- at most 256 registers
 // per lane and 64 KB of LDS -- so that two workgroups share a CU and the bandwidth-bound own-KV
 // role runs beside it.  part_o [slot][B][Hq][128] fp32 (normalised), part_l [slot][B][Hq]
 // (natural-log lse).
@@ -155,22 +178,91 @@ __device__ __forceinline__ void decode_prefix_role(char* sm, const bf16_t* __res
 #pragma unroll
         for (int t8 = 0; t8 < 8; ++t8) s = mma(lds_frag_n(kt, lc, 16 * t8 + 8 * lg), qf[t8], s);
     };
-    // mask the ragged end of the segment, then move the running maximum when the tile's exceeds
-    // it by more than RESCALE_GAP (rare after the first tile)
-    auto prepare = [&](int t, bool live) __attribute__((always_inline)) {
+    // entries past the last slot of the segment, in the scores of tile t
+    auto mask_tail = [&](int t) __attribute__((always_inline)) {
         const int j0 = (t_lo + t) * DEC_BN;
-        if (live && j0 + DEC_BN > P) {
+        if (j0 + DEC_BN > P) {
             const int thr = P - 1 - j0 - 4 * lg;
 #pragma unroll
             for (int r = 0; r < 16; ++r)
                 if (8 * (r >> 2) + (r & 3) > thr) s[r] = NEG_BIG;
         }
+    };
+    // largest scaled score of the tile in s, over both halves of the lane's row
+    auto row_max = [&]() __attribute__((always_inline)) {
         float tm = s[0];
 #pragma unroll
         for (int r = 1; r < 16; ++r) tm = fmaxf(tm, s[r]);
-        tm = partner_max(tm) * c;
-        const float m_new = (live && tm > m_run + RESCALE_GAP) ? tm : m_run;
-        if (__any(m_new != m_run)) {
+        return partner_max(tm) * c;
+    };
+
+    // Pipeline.  Entering iteration u a wavefront holds, in registers, the masked scores of tile
+    // u, the K fragments of tile u+1 and the V fragments of tile u.  The iteration issues the 8
+    // score products of tile u+1 and the 8 O products of tile u; each fragment register is
+    // refilled from LDS right behind the product that consumed it (K of tile u+2, V of tile u+1),
+    // and the exponentials of tile u run between the score products.  Requested all together
+    // behind the barrier instead, the four wavefronts' 64 KB of fragment reads per tile keep LDS
+    // busy for as long as the products keep the matrix cores busy, one after the other.
+    //   What bounds an iteration is the number of instructions the one wavefront of a SIMD has to
+    // issue besides its 16 products (measured 0.74 us per tile against 0.25 us of products with
+    // about 250 of them), so everything that is not per-element work is kept out of the loop:
+    //   - the loop is unrolled over the DEC_NBUF buffers, which makes every LDS address of an
+    //     iteration a per-lane constant plus an immediate;
+    //   - the softmax reference m is the maximum of the FIRST tile and is not looked for again:
+    //     the exponentials are formed against it, and only if a lane's row sum for the tile
+    //     exceeds 2^12 -- some score lies more than 2^8 above m, or the sum has overflowed -- does
+    //     the wavefront take the tile's true maximum, rescale O and l, and form the tile's
+    //     exponentials again.  A false alarm costs time, not accuracy.
+    // Buffers: tiles u+1 and u+2 are read, tile u+3 is in flight, the buffer of tile u is free
+    // once every wavefront's reads of it have completed -- the wait and the barrier at the top --
+    // and takes tile u+4.  Past the end of the split the last tile is requested again and stale
+    // buffers are read; nothing formed from them is used.
+    static_assert(DEC_NBUF == 4, "the rotation below is written for four buffers");
+    constexpr float OVER = 4096.f;
+#pragma unroll
+    for (int t = 0; t < DEC_NBUF; ++t) issue(min(t, nT - 1), t);
+    dma_wait_but<4 * (DEC_NBUF - 2)>();          // tiles 0 and 1
+    __syncthreads();
+    scores(smk);
+    mask_tail(0);
+    m_run = row_max();
+    bf16x8 ka[8], va[2][4];
+#pragma unroll
+    for (int t8 = 0; t8 < 8; ++t8) ka[t8] = lds_frag_n(smk + DEC_TILE_B, lc, 16 * t8 + 8 * lg);
+#pragma unroll
+    for (int db = 0; db < 4; ++db) {
+        va[0][db] = lds_frag_t(smv, 0, 32 * db, lane);
+        va[1][db] = lds_frag_t(smv, 16, 32 * db, lane);
+    }
+    auto body = [&](auto buf_c, int u) __attribute__((always_inline)) {
+        constexpr int BUF = decltype(buf_c)::value;
+        dma_wait_but<4 * (DEC_NBUF - 3)>();       // tile u+2
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __syncthreads();
+        issue(min(u + DEC_NBUF, nT - 1), BUF);
+        const char* kn = smk + ((BUF + 2) % DEC_NBUF) * DEC_TILE_B;
+        const char* vn = smv + ((BUF + 1) % DEC_NBUF) * DEC_TILE_B;
+        f32x16 sn;
+        uint32_t pw[8];
+        float rs = 0.f;
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t8 = 0; t8 < 8; ++t8) {
+            // written out so that the product stays in this place: the compiler is free to move
+            // the builtin across the fences, and gathers all eight at the end of the iteration.
+            // sn is next read by vector instructions behind the eight O products.
+            if (t8 == 0) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(sn) : "v"(ka[0]), "v"(qf[0]));
+            else         asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(sn) : "v"(ka[t8]), "v"(qf[t8]));
+            ka[t8] = lds_frag_n(kn, lc, 16 * t8 + 8 * lg);
+            const float p0 = fast_exp2(fmaf(s[2 * t8], c, -m_run));
+            const float p1 = fast_exp2(fmaf(s[2 * t8 + 1], c, -m_run));
+            rs += p0;
+            rs += p1;
+            pw[t8] = pack_bf16x2(p0, p1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (__any(!(rs <= OVER))) {
+            const float m_new = fmaxf(m_run, row_max());
             const float alpha = fast_exp2(m_run - m_new);
             l_run *= alpha;
             m_run = m_new;
@@ -178,40 +270,36 @@ __device__ __forceinline__ void decode_prefix_role(char* sm, const bf16_t* __res
             for (int db = 0; db < 4; ++db)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[db][r] *= alpha;
-        }
-    };
-
-    issue(0, 0);
-    issue(min(1, nT - 1), 1);
-    issue(min(2, nT - 1), 2);
-    dma_wait_but<8>();          // tile 0
-    __syncthreads();
-    scores(smk);
-    prepare(0, true);
-    for (int u = 0; u < nT; ++u) {
-        const int buf = u & 3;
-        float rs = 0.f;
-        f32x16 p;
+            rs = 0.f;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            p[r] = fast_exp2(fmaf(s[r], c, -m_run));
-            rs += p[r];
+            for (int t8 = 0; t8 < 8; ++t8) {
+                const float p0 = fast_exp2(fmaf(s[2 * t8], c, -m_run));
+                const float p1 = fast_exp2(fmaf(s[2 * t8 + 1], c, -m_run));
+                rs += p0 + p1;
+                pw[t8] = pack_bf16x2(p0, p1);
+            }
         }
         l_run += rs;
-        const bf16x8 pf0 = pack_frag(p, 0), pf1 = pack_frag(p, 8);
-        // tile u+1 has landed for every wavefront and tile u-1 is no longer read: its buffer
-        // takes tile u+3 (past the end the last tile again, into a buffer nobody reads)
-        dma_wait_but<4>();
-        __syncthreads();
-        issue(min(u + 3, nT - 1), (u + 3) & 3);
-        if (u + 1 < nT) scores(smk + ((u + 1) & 3) * DEC_TILE_B);
-        const char* vt = smv + buf * DEC_TILE_B;
+        const bf16x8 pf0 = __builtin_bit_cast(bf16x8, u32x4{pw[0], pw[1], pw[2], pw[3]});
+        const bf16x8 pf1 = __builtin_bit_cast(bf16x8, u32x4{pw[4], pw[5], pw[6], pw[7]});
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int db = 0; db < 4; ++db) {
-            acc[db] = mma(lds_frag_t(vt, 0, 32 * db, lane), pf0, acc[db]);
-            acc[db] = mma(lds_frag_t(vt, 16, 32 * db, lane), pf1, acc[db]);
+            acc[db] = mma(va[0][db], pf0, acc[db]);
+            va[0][db] = lds_frag_t(vn, 0, 32 * db, lane);
+            __builtin_amdgcn_sched_barrier(0);
+            acc[db] = mma(va[1][db], pf1, acc[db]);
+            va[1][db] = lds_frag_t(vn, 16, 32 * db, lane);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        prepare(u + 1, u + 1 < nT);
+        s = sn;
+        if (u + 1 < nT) mask_tail(u + 1);
+    };
+    for (int u0 = 0; u0 < nT; u0 += DEC_NBUF) {
+        body(std::integral_constant<int, 0>{}, u0);
+        if (u0 + 1 < nT) body(std::integral_constant<int, 1>{}, u0 + 1);
+        if (u0 + 2 < nT) body(std::integral_constant<int, 2>{}, u0 + 2);
+        if (u0 + 3 < nT) body(std::integral_constant<int, 3>{}, u0 + 3);
     }
     dma_wait();
     const float l_tot = l_run + partner(l_run);
@@ -232,155 +320,246 @@ __device__ __forceinline__ void decode_prefix_role(char* sm, const bf16_t* __res
     }
 }
 
-// One wavefront per (request, KV head, chunk of keys): chunks 0 .. n_cc-1 cover the request's
-// private cartridge pool[cart_id[b]] ([Hkv,pool_p,128]; none when cart_id is null or negative),
-// chunks n_cc .. n_cc+n_oc-1 its own KV rows, split evenly over those slots.  32 keys per step through a private 16 KB LDS
-// slot; the G query rows of the group occupy columns 0..G-1 of one MFMA block.
-__device__ __forceinline__ void decode_own_role(
-    char* sm /* [wavefront][K, V][32 rows] */, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
-    const bf16_t* __restrict__ v, const int32_t* __restrict__ cu, const bf16_t* __restrict__ pool_k,
-    const bf16_t* __restrict__ pool_v, const int32_t* __restrict__ cart_id, int pool_p,
-    float* __restrict__ part_o, float* __restrict__ part_l, int B, int Hq, int Hkv, float c, int chunk, int n_cc,
-    int n_oc, int n_ps, int blk) {
-    const int G = Hq / Hkv;
-    const int lane = threadIdx.x & 63, lg = lane >> 5, lc = lane & 31;
-    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    long item = static_cast<long>(blk) * 4 + wv;
-    const int hk = item % Hkv; item /= Hkv;
-    const int cc = item % (n_cc + n_oc);
-    const int b = static_cast<int>(item / (n_cc + n_oc));
-    if (b >= B) return;
-    const bool priv = cc < n_cc;
-    int len, k0, ck = chunk;
-    uint32_t pitch;
-    const char *k_b, *v_b;
-    if (priv) {
-        const int cid = cart_id ? cart_id[b] : -1;
-        if (cid < 0) return;
-        len = pool_p;
-        k0 = cc * chunk;
-        pitch = ROW_B;
-        const size_t row0 = (static_cast<size_t>(cid) * Hkv + hk) * pool_p + k0;
-        k_b = reinterpret_cast<const char*>(pool_k) + row0 * ROW_B;
-        v_b = reinterpret_cast<const char*>(pool_v) + row0 * ROW_B;
-    } else {
-        const int t0 = cu[b];
-        len = cu[b + 1] - t0;
-        ck = own_chunk_keys(len, n_oc);
-        k0 = (cc - n_cc) * ck;
-        pitch = static_cast<uint32_t>(Hkv) * ROW_B;
-        const size_t row0 = static_cast<size_t>(t0 + k0) * Hkv + hk;
-        k_b = reinterpret_cast<const char*>(k) + row0 * ROW_B;
-        v_b = reinterpret_cast<const char*>(v) + row0 * ROW_B;
-    }
-    if (k0 >= len) return;
-    const int nk = min(ck, len - k0);
-
-    bf16x8 qf[8];
-    {
-        const bf16_t* qp = q + (static_cast<size_t>(b) * Hq + hk * G + min(lc, G - 1)) * HD + 8 * lg;
-#pragma unroll
-        for (int t = 0; t < 8; ++t) qf[t] = *reinterpret_cast<const bf16x8*>(qp + 16 * t);
-    }
-    char* kt = sm + (2 * wv) * DEC_SUB_B;
-    char* vt = kt + DEC_SUB_B;
-    // 32 rows x 256 B = 8 direct-to-LDS loads of 4 rows each, per tensor, by this wavefront alone
-    auto issue = [&](int j0) __attribute__((always_inline)) {
-        const size_t step = static_cast<size_t>(j0) * pitch;
-        const int lim = nk - 1 - j0;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int r = 4 * i + (lane >> 4);
-            const uint32_t off = static_cast<uint32_t>(min(r, lim)) * pitch + (((lane & 15) ^ swz(r)) << 4);
-            dma16(k_b + step, off, lds_addr(kt) + 4 * i * ROW_B);
-            dma16(v_b + step, off, lds_addr(vt) + 4 * i * ROW_B);
-        }
-    };
-
+// One step of the own-KV role: 32 key rows (the last ones of a run repeated past its end and
+// masked) from the wavefront's private 16 KB LDS slot against the G query rows of one request,
+// which occupy columns 0..G-1 of one MFMA block.
+struct OwnState {
     f32x16 acc[4];
+    float m_run, l_run;
+};
+__device__ __forceinline__ void own_reset(OwnState& st) {
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
-    float m_run = NEG_BIG, l_run = 0.f;
-    issue(0);
-    for (int j0 = 0; j0 < nk; j0 += DEC_SUB) {
-        // fragments of this step into registers, then the next step's loads overwrite the slot
-        // while the matrix cores work
-        bf16x8 ka[8], va[2][4];
-        dma_wait();   // this step's direct-to-LDS loads have landed
+        for (int r = 0; r < 16; ++r) st.acc[db][r] = 0.f;
+    st.m_run = NEG_BIG;
+    st.l_run = 0.f;
+}
+// nkeys: valid keys of the step (1..32)
+__device__ __forceinline__ void own_step(OwnState& st, const bf16x8 (&ka)[8], const bf16x8 (&va)[2][4],
+                                         const bf16x8 (&qf)[8], int nkeys, float c, int lg) {
+    f32x16 s;
 #pragma unroll
-        for (int t8 = 0; t8 < 8; ++t8) ka[t8] = lds_frag_n(kt, lc, 16 * t8 + 8 * lg);
+    for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
+    for (int t8 = 0; t8 < 8; ++t8) s = mma(ka[t8], qf[t8], s);
+    if (nkeys < DEC_SUB) {
+        const int thr = nkeys - 1 - 4 * lg;
 #pragma unroll
-            for (int db = 0; db < 4; ++db) va[ks][db] = lds_frag_t(vt, 16 * ks, 32 * db, lane);
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        if (j0 + DEC_SUB < nk) issue(j0 + DEC_SUB);
-        f32x16 s;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[r] = 0.f;
-#pragma unroll
-        for (int t8 = 0; t8 < 8; ++t8) s = mma(ka[t8], qf[t8], s);
-        if (j0 + DEC_SUB > nk) {
-            const int thr = nk - 1 - j0 - 4 * lg;
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-                if (8 * (r >> 2) + (r & 3) > thr) s[r] = NEG_BIG;
-        }
-        float tm = s[0];
-#pragma unroll
-        for (int r = 1; r < 16; ++r) tm = fmaxf(tm, s[r]);
-        tm = partner_max(tm) * c;
-        const float m_new = fmaxf(m_run, tm);
-        const float alpha = fast_exp2(m_run - m_new);
-        m_run = m_new;
-        float rs = 0.f;
-        f32x16 p;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            p[r] = fast_exp2(fmaf(s[r], c, -m_run));
-            rs += p[r];
-        }
-        l_run = l_run * alpha + rs;
-        const bf16x8 pf0 = pack_frag(p, 0), pf1 = pack_frag(p, 8);
-#pragma unroll
-        for (int db = 0; db < 4; ++db) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[db][r] *= alpha;
-            acc[db] = mma(va[0][db], pf0, acc[db]);
-            acc[db] = mma(va[1][db], pf1, acc[db]);
-        }
+        for (int r = 0; r < 16; ++r)
+            if (8 * (r >> 2) + (r & 3) > thr) s[r] = NEG_BIG;
     }
-    const float l_tot = l_run + partner(l_run);
+    float tm = s[0];
+#pragma unroll
+    for (int r = 1; r < 16; ++r) tm = fmaxf(tm, s[r]);
+    tm = partner_max(tm) * c;
+    // the running maximum moves only when exceeded by more than RESCALE_GAP (then O and l are
+    // rescaled; rare after a run's first step)
+    const float m_new = tm > st.m_run + RESCALE_GAP ? tm : st.m_run;
+    if (__any(m_new != st.m_run)) {
+        const float alpha = fast_exp2(st.m_run - m_new);
+        st.l_run *= alpha;
+        st.m_run = m_new;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) st.acc[db][r] *= alpha;
+    }
+    float rs = 0.f;
+    f32x16 p;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        p[r] = fast_exp2(fmaf(s[r], c, -st.m_run));
+        rs += p[r];
+    }
+    st.l_run += rs;
+    const bf16x8 pf0 = pack_frag(p, 0), pf1 = pack_frag(p, 8);
+#pragma unroll
+    for (int db = 0; db < 4; ++db) {
+        st.acc[db] = mma(va[0][db], pf0, st.acc[db]);
+        st.acc[db] = mma(va[1][db], pf1, st.acc[db]);
+    }
+}
+// normalised partial O and natural-log lse of the G rows (lanes lc < G) into partial slot `slot`
+__device__ __forceinline__ void own_store(const OwnState& st, float* __restrict__ part_o, float* __restrict__ part_l,
+                                          size_t slot_row0, int G, int lc, int lg) {
+    const float l_tot = st.l_run + partner(st.l_run);
     const float inv = 1.f / l_tot;
     if (lc < G) {
-        const size_t slot = (static_cast<size_t>(n_ps + cc) * B + b) * Hq + hk * G + lc;
+        const size_t slot = slot_row0 + lc;
         float* op = part_o + slot * HD;
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
             for (int r4 = 0; r4 < 4; ++r4) {
                 typedef float f32x4 __attribute__((ext_vector_type(4)));
-                f32x4 w = {acc[db][4 * r4] * inv, acc[db][4 * r4 + 1] * inv, acc[db][4 * r4 + 2] * inv,
-                           acc[db][4 * r4 + 3] * inv};
+                f32x4 w = {st.acc[db][4 * r4] * inv, st.acc[db][4 * r4 + 1] * inv, st.acc[db][4 * r4 + 2] * inv,
+                           st.acc[db][4 * r4 + 3] * inv};
                 *reinterpret_cast<f32x4*>(op + 32 * db + 8 * r4 + 4 * lg) = w;
             }
-        if (lg == 0) part_l[slot] = (m_run + fast_log2(l_tot)) * CART_LN2;
+        if (lg == 0) part_l[slot] = (st.m_run + fast_log2(l_tot)) * CART_LN2;
     }
+}
+// 32 rows x 256 B from row `row0` of a [rows][pitch] tensor (rows past `lim` repeat row lim) into
+// the wavefront's slot: 8 direct-to-LDS loads of 4 rows each, per tensor
+__device__ __forceinline__ void own_issue(const char* k_row0, const char* v_row0, uint32_t pitch, int lim, char* kt,
+                                          char* vt, int lane) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int r = 4 * i + (lane >> 4);
+        const uint32_t off = static_cast<uint32_t>(min(r, lim)) * pitch + (((lane & 15) ^ swz(r)) << 4);
+        dma16(k_row0, off, lds_addr(kt) + 4 * i * ROW_B);
+        dma16(v_row0, off, lds_addr(vt) + 4 * i * ROW_B);
+    }
+}
+__device__ __forceinline__ void own_frags(const char* kt, const char* vt, bf16x8 (&ka)[8], bf16x8 (&va)[2][4], int lane) {
+    const int lg = lane >> 5, lc = lane & 31;
+#pragma unroll
+    for (int t8 = 0; t8 < 8; ++t8) ka[t8] = lds_frag_n(kt, lc, 16 * t8 + 8 * lg);
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int db = 0; db < 4; ++db) va[ks][db] = lds_frag_t(vt, 16 * ks, 32 * db, lane);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+}
+__device__ __forceinline__ void own_load_q(const bf16_t* __restrict__ q, int b, int Hq, int hk, int G, int lc, int lg,
+                                           bf16x8 (&qf)[8]) {
+    const bf16_t* qp = q + (static_cast<size_t>(b) * Hq + hk * G + min(lc, G - 1)) * HD + 8 * lg;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) qf[t] = *reinterpret_cast<const bf16x8*>(qp + 16 * t);
+}
+
+// Own-KV role.  The own caches of all requests are one packed tensor [T][Hkv][128], so the work
+// is cut evenly along T whatever the requests' lengths: wavefront (range r, KV head hk) streams
+// token rows [r*share, (r+1)*share) of head hk, 32 rows per step, without a pause where one
+// request ends and the next begins -- the next step's rows are requested before the current step
+// is computed, and the next request's query rows are fetched while the current request runs.
+// A step never spans two requests (its tail is masked), and every (request, range) pair leaves
+// one partial: request b's slot j is range cu[b]/share + j.  Equal bytes per wavefront, all
+// wavefronts resident from the start: nothing depends on the order or the pace at which the
+// hardware hands out workgroups.  (One workgroup per four (request, head, chunk) items, left
+// to the dispatcher, measured 20 us slower on the serving shape: by the middle of the kernel 50
+// to 90 CUs sat empty with hundreds of workgroups still to start.)
+__device__ __forceinline__ void decode_own_stream(char* sm, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+                                                  const bf16_t* __restrict__ v, const int32_t* __restrict__ cu,
+                                                  float* __restrict__ part_o, float* __restrict__ part_l, int B, int Hq,
+                                                  int Hkv, float c, int slot0, int n_oc, int share, int wid) {
+    const int G = Hq / Hkv;
+    const int lane = threadIdx.x & 63, lg = lane >> 5, lc = lane & 31;
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int r = wid / Hkv, hk = wid - r * Hkv;
+    const int T = cu[B];
+    const long t_lo_l = static_cast<long>(r) * share;
+    if (t_lo_l >= T) return;
+    const int t_lo = static_cast<int>(t_lo_l);
+    const int t_hi = min(t_lo + share, T);
+    // the request the range starts in: cu[b] <= t_lo < cu[b+1]
+    int cnt = 0;
+    for (int i = lane + 1; i <= B; i += 64) cnt += cu[i] <= t_lo ? 1 : 0;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o, CART_WAVE);
+    int b = __builtin_amdgcn_readfirstlane(cnt);
+    if (b >= B) return;                       // (cu not increasing: nothing sensible to do)
+    int req_lo = cu[b], req_hi = cu[b + 1];
+    int run_end = min(req_hi, t_hi);          // rows [t, run_end) belong to request b
+    int next_hi = b + 2 <= B ? cu[b + 2] : T; // end of request b+1
+    const uint32_t pitch = static_cast<uint32_t>(Hkv) * ROW_B;
+    const char* k_h = reinterpret_cast<const char*>(k) + static_cast<size_t>(hk) * ROW_B;
+    const char* v_h = reinterpret_cast<const char*>(v) + static_cast<size_t>(hk) * ROW_B;
+    char* kt = sm + (2 * wv) * DEC_SUB_B;
+    char* vt = kt + DEC_SUB_B;
+    bf16x8 qf[8], qn[8];
+    own_load_q(q, b, Hq, hk, G, lc, lg, qf);
+    own_load_q(q, min(b + 1, B - 1), Hq, hk, G, lc, lg, qn);
+    OwnState st;
+    own_reset(st);
+    int t = t_lo;
+    own_issue(k_h + static_cast<size_t>(t) * pitch, v_h + static_cast<size_t>(t) * pitch, pitch, run_end - 1 - t, kt, vt,
+              lane);
+    for (;;) {
+        const int nkeys = min(DEC_SUB, run_end - t);
+        const bool run_last = t + DEC_SUB >= run_end;
+        const int t_next = run_last ? run_end : t + DEC_SUB;
+        const bool more = t_next < t_hi;
+        const int next_end = run_last ? min(next_hi, t_hi) : run_end;
+        bf16x8 ka[8], va[2][4];
+        dma_wait();                      // this step's rows have landed
+        own_frags(kt, vt, ka, va, lane); // into registers; the slot then takes the next step's rows
+        if (more)
+            own_issue(k_h + static_cast<size_t>(t_next) * pitch, v_h + static_cast<size_t>(t_next) * pitch, pitch,
+                      next_end - 1 - t_next, kt, vt, lane);
+        own_step(st, ka, va, qf, nkeys, c, lg);
+        if (run_last) {
+            const int j = r - req_lo / share;
+            if (j < n_oc)      // (always, unless a request is longer than the max_own_len the caller stated)
+                own_store(st, part_o, part_l, (static_cast<size_t>(slot0 + j) * B + b) * Hq + hk * G, G, lc, lg);
+            if (!more) break;
+            ++b;
+            req_lo = req_hi;
+            req_hi = next_hi;
+            run_end = next_end;
+            next_hi = b + 2 <= B ? cu[b + 2] : T;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) qf[i] = qn[i];
+            own_load_q(q, min(b + 1, B - 1), Hq, hk, G, lc, lg, qn);
+            own_reset(st);
+        }
+        t = t_next;
+    }
+}
+
+// One chunk of a request's private cartridge pool[cart_id[b]] ([Hkv,pool_p,128]; none when
+// cart_id is null or negative), streamed like own rows: item = (request b, chunk cc, KV head hk).
+__device__ __forceinline__ void decode_pool_item(char* sm, const bf16_t* __restrict__ q,
+                                                 const bf16_t* __restrict__ pool_k, const bf16_t* __restrict__ pool_v,
+                                                 const int32_t* __restrict__ cart_id, int pool_p,
+                                                 float* __restrict__ part_o, float* __restrict__ part_l, int B, int Hq,
+                                                 int Hkv, float c, int chunk, int n_cc, int n_ps, long item) {
+    const int G = Hq / Hkv;
+    const int lane = threadIdx.x & 63, lg = lane >> 5, lc = lane & 31;
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int hk = item % Hkv; item /= Hkv;
+    const int cc = item % n_cc;
+    const int b = static_cast<int>(item / n_cc);
+    const int cid = cart_id ? cart_id[b] : -1;
+    if (cid < 0) return;
+    const int k0 = cc * chunk;
+    if (k0 >= pool_p) return;
+    const int nk = min(chunk, pool_p - k0);
+    const size_t row0 = (static_cast<size_t>(cid) * Hkv + hk) * pool_p + k0;
+    const char* k_b = reinterpret_cast<const char*>(pool_k) + row0 * ROW_B;
+    const char* v_b = reinterpret_cast<const char*>(pool_v) + row0 * ROW_B;
+    char* kt = sm + (2 * wv) * DEC_SUB_B;
+    char* vt = kt + DEC_SUB_B;
+    bf16x8 qf[8];
+    own_load_q(q, b, Hq, hk, G, lc, lg, qf);
+    OwnState st;
+    own_reset(st);
+    own_issue(k_b, v_b, ROW_B, nk - 1, kt, vt, lane);
+    for (int j0 = 0; j0 < nk; j0 += DEC_SUB) {
+        bf16x8 ka[8], va[2][4];
+        dma_wait();
+        own_frags(kt, vt, ka, va, lane);
+        if (j0 + DEC_SUB < nk)
+            own_issue(k_b + static_cast<size_t>(j0 + DEC_SUB) * ROW_B, v_b + static_cast<size_t>(j0 + DEC_SUB) * ROW_B, ROW_B,
+                      nk - 1 - j0 - DEC_SUB, kt, vt, lane);
+        own_step(st, ka, va, qf, min(DEC_SUB, nk - j0), c, lg);
+    }
+    own_store(st, part_o, part_l, (static_cast<size_t>(n_ps + cc) * B + b) * Hq + hk * G, G, lc, lg);
 }
 
 // Both roles in one launch, two workgroups per CU: prefix workgroups (matrix-core and LDS work
 // on data that sits in L2) and own-KV workgroups (HBM streaming) alternate in the grid while
-// both kinds remain, so that the two run side by side instead of one after the other.
+// both kinds remain, so that the two run side by side instead of one after the other.  The
+// launch holds no more workgroups than the chip keeps resident.
 __global__ __launch_bounds__(256, 2) void decode_fused_kernel(
     const bf16_t* __restrict__ q, const PrefixTable tab, const bf16_t* __restrict__ k,
     const bf16_t* __restrict__ v, const int32_t* __restrict__ cu, const bf16_t* __restrict__ pool_k,
     const bf16_t* __restrict__ pool_v, const int32_t* __restrict__ cart_id, int pool_p,
     float* __restrict__ part_o, float* __restrict__ part_l, int B, int Hq, int Hkv, float c, int n_rb, int chunk,
-    int n_cc, int n_oc, int n_ps, int n_pre_wg, int n_own_wg) {
-    static_assert(2 * DEC_NBUF * DEC_TILE_B == 4 * 2 * DEC_SUB_B, "the two roles share one LDS block");
-    __shared__ __attribute__((aligned(16))) char sm[4 * 2 * DEC_SUB_B];
+    int n_cc, int n_oc, int share, int n_ps, int n_pre_wg, int n_own_wg) {
+    constexpr int pre_b = 2 * DEC_NBUF * DEC_TILE_B, own_b = 4 * 2 * DEC_SUB_B;   // the two roles share one LDS block
+    __shared__ __attribute__((aligned(16))) char sm[pre_b > own_b ? pre_b : own_b];
     const int i = blockIdx.x;
     const int both = min(n_pre_wg, n_own_wg);
     bool pre;
@@ -393,14 +572,24 @@ __global__ __launch_bounds__(256, 2) void decode_fused_kernel(
     else               { const int r = i - 2 * both8, left = both - both8;
                          if (r < 2 * left) { pre = !(r & 1); idx = both8 + (r >> 1); }
                          else              { pre = n_pre_wg > n_own_wg; idx = i - both; } }
-    if (pre) decode_prefix_role(sm, q, tab, part_o, part_l, B, Hq, Hkv, c, n_rb, idx);
-    else     decode_own_role(sm, q, k, v, cu, pool_k, pool_v, cart_id, pool_p, part_o, part_l, B, Hq, Hkv, c, chunk,
-                             n_cc, n_oc, n_ps, idx);
+    if (pre) {
+        decode_prefix_role(sm, q, tab, part_o, part_l, B, Hq, Hkv, c, n_rb, idx);
+        return;
+    }
+    // every wavefront on its own from here on: no barrier in this role
+    const int wid = __builtin_amdgcn_readfirstlane(idx * 4 + static_cast<int>(threadIdx.x >> 6));
+    decode_own_stream(sm, q, k, v, cu, part_o, part_l, B, Hq, Hkv, c, n_ps + n_cc, n_oc, share, wid);
+    if (n_cc > 0) {
+        const long n_items = static_cast<long>(B) * n_cc * Hkv;
+        for (long item = wid; item < n_items; item += 4L * n_own_wg)
+            decode_pool_item(sm, q, pool_k, pool_v, cart_id, pool_p, part_o, part_l, B, Hq, Hkv, c, chunk, n_cc, n_ps,
+                             item);
+    }
 }
 
 // o[b,h,:] = sum_i w_i part_o[i] / sum_i w_i, w_i = exp(lse_i - max lse), over the partial slots
 // that exist for the request: the n_ps prefix parts, the chunks of its private cartridge (when it
-// has one), the chunks of its own rows (own_chunk_keys(len) keys each).  One wavefront per
+// has one), one per range of `share` token rows its own rows reach into.  One wavefront per
 // (b, h), the slots in groups of 64: lane i holds the lse and the weight of the group's slot i,
 // then every lane accumulates its two head elements over the group's slots with the loads of
 // eight slots in flight.
@@ -410,15 +599,13 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(const float* __restri
                                                            const int32_t* __restrict__ cart_id, int pool_p,
                                                            bf16_t* __restrict__ o,
                                                            float* __restrict__ lse, int B, int Hq,
-                                                           int n_ps, int n_cc, int n_oc, int chunk) {
+                                                           int n_ps, int n_cc, int n_oc, int chunk, int share) {
     const int lane = threadIdx.x & 63;
     const long row = static_cast<long>(blockIdx.x) * 4 + (threadIdx.x >> 6);
     if (row >= static_cast<long>(B) * Hq) return;
     const int b = row / Hq;
-    const int len = cu[b + 1] - cu[b];
     const int priv = (n_cc > 0 && cart_id && cart_id[b] >= 0) ? (pool_p + chunk - 1) / chunk : 0;
-    const int ck = own_chunk_keys(len, n_oc);
-    const int own = (len + ck - 1) / ck;
+    const int own = min(n_oc, (cu[b + 1] - 1) / share - cu[b] / share + 1);
     const int n = n_ps + n_cc + n_oc;
     auto valid = [&](int i) { return i < n_ps || (i < n_ps + n_cc ? i - n_ps < priv : i - n_ps - n_cc < own); };
     const size_t stride = static_cast<size_t>(B) * Hq;
@@ -470,7 +657,7 @@ bool decode_mfma_supported(const cart_decode_desc& d) {
 }
 
 size_t decode_mfma_workspace(const cart_decode_desc& d) {
-    const DecodePlan p = make_plan(d.B, d.Hq, d.Hkv, d.max_own_len, &d.P, d.P > 0 ? 1 : 0, 0);
+    const DecodePlan p = make_plan(d.B, d.Hq, d.Hkv, d.max_own_len, d.total_own_tokens, &d.P, d.P > 0 ? 1 : 0, 0);
     return p.part_o_bytes + p.part_l_bytes;
 }
 
@@ -481,7 +668,8 @@ bool decode_composed_supported(const cart_decode_composed_desc& d) {
 static DecodePlan composed_plan(const cart_decode_composed_desc& d, const cart_segment* shared) {
     int seg_p[DEC_MAX_SEG];
     for (int s = 0; s < d.n_shared; ++s) seg_p[s] = shared[s].p;
-    return make_plan(d.B, d.Hq, d.Hkv, d.max_own_len, seg_p, d.n_shared, d.n_pool > 0 ? d.pool_p : 0);
+    return make_plan(d.B, d.Hq, d.Hkv, d.max_own_len, d.total_own_tokens, seg_p, d.n_shared,
+                     d.n_pool > 0 ? d.pool_p : 0);
 }
 
 size_t decode_composed_workspace(const cart_decode_composed_desc& d, const cart_segment* shared) {
@@ -489,27 +677,25 @@ size_t decode_composed_workspace(const cart_decode_composed_desc& d, const cart_
     return p.part_o_bytes + p.part_l_bytes;
 }
 
-// prefix parts, then private-cartridge and own chunks, then the merge
+// prefix parts + private-cartridge chunks + own ranges (one launch), then the merge
 static int run_decode(const DecodePlan& p, int B, int Hq, int Hkv, float scale, const void* q, const void* pool_k,
                       const void* pool_v, const int32_t* cart_id, int pool_p, const void* k, const void* v,
                       const int32_t* cu, void* o, float* lse, void* ws, hipStream_t st) {
     float* part_o = static_cast<float*>(ws);
     float* part_l = reinterpret_cast<float*>(static_cast<char*>(ws) + p.part_o_bytes);
     const float c = scale * CART_LOG2E;
-    const long items = static_cast<long>(B) * Hkv * (p.n_cc + p.n_oc);
-    const int n_own_wg = static_cast<int>((items + 3) / 4);
     const bf16_t *Q = static_cast<const bf16_t*>(q), *K = static_cast<const bf16_t*>(k), *V = static_cast<const bf16_t*>(v),
                  *PK = static_cast<const bf16_t*>(pool_k), *PV = static_cast<const bf16_t*>(pool_v);
     trace_begin(st);   // kernel order: prefix + own (one launch), merge
     const int n_pre_wg = p.n_ps > 0 ? p.tab.blk0[p.tab.n_seg] : 0;
-    hipLaunchKernelGGL(decode_fused_kernel, dim3(static_cast<unsigned>(n_pre_wg + n_own_wg)), dim3(256), 0, st, Q, p.tab,
-                       K, V, cu, PK, PV, cart_id, pool_p, part_o, part_l, B, Hq, Hkv, c, p.n_rb, p.chunk, p.n_cc,
-                       p.n_oc, p.n_ps, n_pre_wg, n_own_wg);
+    hipLaunchKernelGGL(decode_fused_kernel, dim3(static_cast<unsigned>(n_pre_wg + p.n_own_wg)), dim3(256), 0, st, Q,
+                       p.tab, K, V, cu, PK, PV, cart_id, pool_p, part_o, part_l, B, Hq, Hkv, c, p.n_rb, p.chunk, p.n_cc,
+                       p.n_oc, p.share, p.n_ps, n_pre_wg, p.n_own_wg);
     trace_mark(st);
     const long rows = static_cast<long>(B) * Hq;
     hipLaunchKernelGGL(decode_merge_kernel, dim3(static_cast<unsigned>((rows + 3) / 4)), dim3(256), 0, st, part_o,
                        part_l, cu, cart_id, pool_p, static_cast<bf16_t*>(o), lse, B, Hq, p.n_ps, p.n_cc, p.n_oc,
-                       p.chunk);
+                       p.chunk, p.share);
     trace_mark(st);
     return static_cast<int>(hipGetLastError());
 }
@@ -517,7 +703,7 @@ static int run_decode(const DecodePlan& p, int B, int Hq, int Hkv, float scale, 
 int launch_decode_mfma(const cart_decode_desc& d, float scale, const void* q, const void* zk,
                        const void* zv, const void* k, const void* v, const int32_t* cu, void* o,
                        float* lse, void* ws, hipStream_t st) {
-    DecodePlan p = make_plan(d.B, d.Hq, d.Hkv, d.max_own_len, &d.P, d.P > 0 ? 1 : 0, 0);
+    DecodePlan p = make_plan(d.B, d.Hq, d.Hkv, d.max_own_len, d.total_own_tokens, &d.P, d.P > 0 ? 1 : 0, 0);
     if (p.tab.n_seg > 0) {
         p.tab.zk[0] = static_cast<const bf16_t*>(zk);
         p.tab.zv[0] = static_cast<const bf16_t*>(zv);
