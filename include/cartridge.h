@@ -217,7 +217,7 @@ cart_status cart_decode(const cart_decode_desc *desc, const void *q, const void 
  *   - bf16 with D = 128 only (the matrix-core decode kernels): CART_ERR_UNSUPPORTED otherwise.
  *   - A problem whose cart_decode_workspace() exceeds cart_decode_static_capacity() is refused
  *     with CART_ERR_WORKSPACE before anything is launched (the 128-request, 8192-slot serving
- *     shape needs 16.9 MB).
+ *     shape needs 21.1 MB).
  *   - Every call on a GPU uses that GPU's one array: calls that overlap in time on the same GPU
  *     (two streams, two threads) race; calls on one stream do not.  Nothing in it has to be
  *     cleared between calls: every partial result is written before it is read.

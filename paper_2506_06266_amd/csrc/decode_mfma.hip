@@ -26,10 +26,12 @@ constexpr int DEC_BN = 32;             // prefix keys per LDS tile
 #ifndef DEC_NBUF
 #define DEC_NBUF 4                     // prefix tiles in LDS: one read, one ready, the rest in flight
 #endif
-// Prefix workgroups aimed at: half the CUs.  Measured on the serving shape (128 requests, 8192
-// shared slots, own caches U[1,1024]): 64 -> 131 us, 128 -> 84 us, 192 -> 90 us, 256 -> 94 us,
-// 512 -> 118 us for the whole call.
-constexpr int DEC_PREFIX_WGS = 128;
+// Prefix workgroups aimed at.  Measured on the serving shape (128 requests, 8192 shared slots,
+// own caches U[1,1024]), fused kernel + merge: 96 -> 66.8 + 7.6 us, 128 -> 57.7 + 8.0, 160 ->
+// 59.3 + 8.8, 192 -> 53.0 + 9.0, 256 -> 60.8 + 10.0.  The prefix workgroups and the own-KV
+// workgroups that share their CUs are the last to finish; more, shorter prefix workgroups end
+// closer to the rest, until their extra partials cost more in the merge.
+constexpr int DEC_PREFIX_WGS = 192;
 constexpr int DEC_TILE_B = DEC_BN * ROW_B;
 constexpr int DEC_SUB = 32;            // own keys per wavefront step
 constexpr int DEC_SUB_B = DEC_SUB * ROW_B;
