@@ -332,6 +332,6 @@ const char* cart_status_str(cart_status s) {
     return "unknown status";
 }
 
-int cart_version(void) { return 140; }   // 1.4: + composed decode, teacher top-k, loss modes, packed batches
+int cart_version(void) { return 150; }   // 1.5: + cart_decode_static, calibration hooks; backward in two kernels
 
 }  // extern "C"
