@@ -96,6 +96,21 @@ __device__ __forceinline__ f32x16 mma(bf16x8 a, bf16x8 b, f32x16 c) {
 // the builtin is an accumulation register whenever a kernel uses those at all) and the B operand
 // read from an accumulation register.  The compiler does not know these are matrix-core
 // instructions: a consumer on the vector ALU must be at least 20 wait states away.
+// Where that distance comes from, kernel by kernel (a product occupies the matrix cores for 32
+// cycles, so one product issued in between already covers it; every place states its own margin):
+//   forward        S(u+1) written in groups 0-15 of an iteration, first read by the vector ALU
+//                  in group 0 of the next one: the 16 O products of groups 16-31 lie between.
+//   dQ             block 1's S / dP written up to groups 44 / 45, first read in group 0 of the
+//                  next iteration: 3 products between (groups 46, 47, 0); block 0's written up to
+//                  groups 46 / 47, first read in group 16: 17 products between.  The masked path
+//                  reads them at the top of the iteration and waits 24 states first.
+//   dK + dV, A     S(u+1) written in groups 0-15, first read in group 0 of the next iteration:
+//                  the 16 dV products between.
+//   dK + dV, B     dP(u) written in groups 0-15, first read in group 4 of the next iteration: the
+//                  16 dK products and 4 more between.
+//   prologues      every first score product is followed by s_nop 15; s_nop 7 (24 states).
+// The GPU tests hold the tripwires: the forward and the backward run twice bit-equal, and the
+// matrix-core kernels against the vector kernels and the oracle over a sweep of random shapes.
 __device__ __forceinline__ void mma_vd_zero(f32x16& d, bf16x8 a, const u32x4& b) {
     asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b));
 }
