@@ -39,6 +39,7 @@ constexpr int DEC_SUB_B = DEC_SUB * ROW_B;
 #ifndef DEC_POOL_CHUNK
 #define DEC_POOL_CHUNK 256             // most keys per chunk of a private cartridge
 #endif
+constexpr int DEC_MIN_SHARE = 256;      // fewest token rows per own-KV range (a multiple of DEC_SUB)
 constexpr int DEC_MAX_SEG = CART_MAX_SEGMENTS;
 
 // The shared prefix as a list of segments (one for a single cartridge), by value in the kernel
@@ -110,8 +111,9 @@ static DecodePlan make_plan(int B, int Hq, int Hkv, int max_own_len, int T, cons
     if (wgs < 64) wgs = 64;
     long ranges = 4 * wgs / Hkv;
     if (ranges < 1) { ranges = 1; wgs = (Hkv + 3) / 4; }
+    // (not below DEC_MIN_SHARE rows: shorter ranges only multiply the partials a request leaves)
     long share = ((static_cast<long>(T) + ranges - 1) / ranges + DEC_SUB - 1) / DEC_SUB * DEC_SUB;
-    if (share < DEC_SUB) share = DEC_SUB;
+    if (share < DEC_MIN_SHARE) share = DEC_MIN_SHARE;
     const long used = (static_cast<long>(T) + share - 1) / share;            // ranges that hold rows
     if (p.n_cc == 0 && (used * Hkv + 3) / 4 < wgs) wgs = (used * Hkv + 3) / 4;
     p.share = static_cast<int>(share);

@@ -7,6 +7,8 @@
   stopping at the first mismatch: the tripwire for their hand-scheduled instruction groups
   (results of matrix-core instructions issued from inline assembly are invisible to the
   compiler's hazard tracking, so a broken spacing would show up as wrong numbers here);
+* the same kind of sweep through the decode entry points, with the length mixes that stress the
+  even split of the packed own caches;
 * the forward pass run twice gives the same bits, and the matrix-core kernels agree with the
   fp32 vector kernels on a problem with a real softmax.
 """
@@ -206,6 +208,65 @@ def test_random_shape_sweep_of_the_matrix_core_attention_kernels():
         worst = max(errs.values())
         print("sweep %2d  B%d S%d Hq%d Hkv%d P%d sharp=%d  worst %.2e" % (case, B, S, Hkv * G, Hkv, P, sharp, worst), flush=True)
         assert worst <= 2e-2, (case, (B, S, Hkv * G, Hkv, P), errs)
+
+
+def test_random_shape_sweep_of_the_decode_kernels():
+    """Forty seeded random decode problems against the oracle, every element: request counts from 1
+    to 300, every head grouping, prefixes from none to ragged, and the length mixes that stress the
+    split of the packed own caches -- all requests one token long, one request as long as all
+    others together, lengths around the 32-row step and around a range boundary; the composed
+    entry point on every third case (two shared segments, a private cartridge for some requests)
+    and the static-scratch entry point on every case (bit-equal with the workspace one)."""
+    rng = np.random.default_rng(20250607)
+    g = torch.Generator().manual_seed(77)
+    rn = lambda *sz, std=1.0: (std * torch.randn(*sz, generator=g)).to(torch.bfloat16)
+    for case in range(40):
+        Hkv = int(rng.choice([1, 2, 3, 8]))
+        G = int(rng.choice([1, 2, 4, 7]))
+        B = int(rng.choice([1, 2, rng.integers(3, 40), rng.integers(40, 301)]))
+        P = int(rng.choice([0, rng.integers(1, 40), rng.integers(33, 200), 257]))
+        mix = int(rng.integers(0, 5))
+        if mix == 0:   lens = np.ones(B, dtype=np.int64)
+        elif mix == 1: lens = rng.integers(1, 70, B)
+        elif mix == 2: lens = np.where(rng.random(B) < 0.15, rng.integers(200, 900, B), rng.integers(1, 5, B))
+        elif mix == 3: lens = rng.choice([31, 32, 33, 63, 64, 65, 1], B)
+        else:
+            lens = rng.integers(1, 20, B)
+            lens[int(rng.integers(0, B))] = int(lens.sum()) + 300        # one request as long as all the others
+        if int(lens.sum()) * Hkv > 60000:                               # keep the oracle's share to seconds
+            lens = np.minimum(lens, 64)
+        max_len = int(lens.max())
+        cu_np = np.zeros(B + 1, dtype=np.int64)
+        cu_np[1:] = np.cumsum(lens)
+        T = int(cu_np[-1])
+        q, k, v = rn(B, Hkv * G, 128, std=0.6), rn(T, Hkv, 128, std=0.6), rn(T, Hkv, 128)
+        zk, zv = (rn(Hkv, P, 128, std=0.6), rn(Hkv, P, 128)) if P else (None, None)
+        cu = torch.from_numpy(cu_np).to(torch.int32).to(DEV)
+        dz = (zk.to(DEV), zv.to(DEV)) if P else (None, None)
+        print("decode sweep %2d  B%d Hq%d Hkv%d P%d T%d max_len%d mix%d" % (case, B, Hkv * G, Hkv, P, T, max_len, mix), flush=True)
+        o, lse = cb.cart_decode(q.to(DEV), *dz, k.to(DEV), v.to(DEV), cu, max_len)
+        o2, lse2 = cb.cart_decode_static(q.to(DEV), *dz, k.to(DEV), v.to(DEV), cu, max_len)
+        torch.cuda.synchronize()
+        zk_n = to_np(zk) if P else np.zeros((Hkv, 0, 128))
+        zv_n = to_np(zv) if P else np.zeros((Hkv, 0, 128))
+        o_ref, lse_ref = orc.decode(to_np(q), zk_n, zv_n, to_np(k), to_np(v), cu_np)
+        errs = {"o": rel_err(to_np(o), o_ref), "lse": rel_err(to_np(lse), lse_ref)}
+        assert max(errs.values()) <= 2e-2, (case, errs)
+        assert torch.equal(o, o2) and torch.equal(lse, lse2), case
+        if case % 3 == 0 and P >= 2:
+            cut = max(1, P // 3)
+            shared = [(zk[:, :cut].contiguous().to(DEV), zv[:, :cut].contiguous().to(DEV)),
+                      (zk[:, cut:].contiguous().to(DEV), zv[:, cut:].contiguous().to(DEV))]
+            pool_p = int(rng.choice([1, 40, 300]))
+            pool_k, pool_v = rn(2, Hkv, pool_p, 128, std=0.6), rn(2, Hkv, pool_p, 128)
+            cart_id = (torch.arange(B) % 3 - 1).to(torch.int32)
+            o3, lse3 = cb.cart_decode_composed(q.to(DEV), shared, pool_k.to(DEV), pool_v.to(DEV), cart_id.to(DEV),
+                                               k.to(DEV), v.to(DEV), cu, max_len)
+            torch.cuda.synchronize()
+            o3_ref, lse3_ref = orc.decode_composed(to_np(q), [(to_np(a), to_np(b)) for a, b in shared], to_np(pool_k),
+                                                   to_np(pool_v), cart_id.numpy(), to_np(k), to_np(v), cu_np)
+            errs = {"o": rel_err(to_np(o3), o3_ref), "lse": rel_err(to_np(lse3), lse3_ref)}
+            assert max(errs.values()) <= 2e-2, (case, "composed", errs)
 
 
 def test_forward_twice_same_bits_and_matrix_core_vs_vector_kernels():
