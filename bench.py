@@ -214,6 +214,13 @@ def main() -> int:
     graph_ms = timed(dec_graph.replay) / 10
     del dec_graph
 
+    # the same call through the entry point that keeps its partial results in the library's own
+    # device array (one launch less to set up for the caller, the same kernels), and alone in a
+    # loop (in the timed step the call follows 8 GB of loss traffic)
+    static_ms = timed(lambda: cb.cart_decode_static(dc["q"], dc["z_k"], dc["z_v"], dc["k_own"], dc["v_own"],
+                                                    dc["cu_lens"], dcfg.max_len, o=dec_o, lse=dec_lse), n=20)
+    alone_ms = timed(dec_step, n=20)
+
     # the serving comparison run: no cartridge, 8 requests that each carry a 131072-token KV cache
     lcfg = synth.DECODE_CONFIGS["cfg5_long"]
     lg = synth.decode_inputs(lcfg, dev)
@@ -252,6 +259,16 @@ def main() -> int:
                                                d_z_v=g2[4], workspace=ws2), n=10)
     c2_pairs = attn_pairs(c2) * c2.B * c2.Hq
     del a2, o2, lse2, g2, ws2
+
+    # the cfg3 step's attention kernels on all-zero inputs: the same instruction streams with no
+    # switching activity in the data paths -- what the schedules would run at if the chip were not
+    # power-limited under them (a statement about the machine, not a throughput claim)
+    zq, zk_, zv_, zdo = (torch.zeros_like(a[n]) for n in ("q", "k_own", "v_own", "d_o"))
+    zzk, zzv = torch.zeros_like(a["z_k"]), torch.zeros_like(a["z_v"])
+    zero_fwd_ms = timed(lambda: cb.cart_attn_fwd(zq, zk_, zv_, zzk, zzv, o=o, lse=lse, workspace=ws_attn))
+    zero_bwd_ms = timed(lambda: cb.cart_attn_bwd(zq, zk_, zv_, zzk, zzv, o, lse, zdo, d_q=dq, d_k_own=dk, d_v_own=dv,
+                                                 d_z_k=dzk, d_z_v=dzv, workspace=ws_attn))
+    del zq, zk_, zv_, zdo, zzk, zzv
 
     # what this machine gives a kernel with nothing else to do, measured in this run: a matrix-core-only
     # loop of the attention kernels' instruction, a 4 GiB device copy and a 4 GiB device read
@@ -350,9 +367,13 @@ def main() -> int:
                            "attn_fwd_bwd_tflops": round(c2_pairs * 14 * c2.D / (c2_fwd_ms + c2_bwd_ms) / 1e9, 1),
                            "attn_mfma_frac": round(c2_pairs * 14 * c2.D / (c2_fwd_ms + c2_bwd_ms) / 1e9
                                                    / PEAK_BF16_TFLOPS, 4)}},
-        "measured_peaks": {"mfma_bf16_tflops": round(peak_mfma_tflops, 1), "copy_4GiB_gbs": round(peak_copy_gbs, 1),
+        "measured_peaks": {"attn_fwd_ms_on_zero_inputs": round(zero_fwd_ms, 4),
+                           "attn_bwd_ms_on_zero_inputs": round(zero_bwd_ms, 4),
+                           "mfma_bf16_tflops": round(peak_mfma_tflops, 1), "copy_4GiB_gbs": round(peak_copy_gbs, 1),
                            "read_4GiB_gbs": round(peak_read_gbs, 1),
-                           "note": "plain kernels of this library timed in this run (matrix-core-only loop; "
+                           "note": "timed in this run: the cfg3 attention calls on all-zero inputs (same instruction streams, no "
+                                   "switching activity: the chip is power-limited under these kernels); plain kernels of "
+                                   "this library (matrix-core-only loop; "
                                    "16-byte-per-lane copy and read of 4 GiB)"},
         "roofline": roofline,
         "next_rows": {"kl_rest_bucket_ms": round(rest_ms, 4),
@@ -365,6 +386,8 @@ def main() -> int:
                       "decode_cartridge_per_request_ms": round(pool_ms, 4),
                       "decode_cartridge_per_request_gbs": round(pool_bytes / pool_ms / 1e6, 1),
                       "decode_graph_replay_ms": round(graph_ms, 4),
+                      "decode_alone_in_a_loop_ms": round(alone_ms, 4),
+                      "decode_static_scratch_ms": round(static_ms, 4),
                       "decode_no_cartridge_8x131072_ms": round(long_ms, 4),
                       "decode_no_cartridge_8x131072_gbs": round(long_bytes / long_ms / 1e6, 1),
                       "attn_packed_64_conversations_fwd_bwd_ms": round(packed_ms, 4),
