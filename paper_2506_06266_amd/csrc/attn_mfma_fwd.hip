@@ -374,8 +374,18 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_mfma_kernel(
         const int j0 = tile_j0(t);
         dma_wait_but<8>();      // tile t+1 has landed (t+2 may still be in flight)
         __syncthreads();
-        stage(std::integral_constant<int, 0>{}, masked_tag, pre, j0, sa, sb, ts);
-        stage(std::integral_constant<int, 1>{}, masked_tag, pre, j0, sb, sa, ts);
+        if (decltype(masked_tag)::value && !pre && j0 > wrow0 + 63) {
+            // A diagonal tile that lies entirely behind this wavefront's 64 queries (so do all
+            // that follow): nothing to compute -- its share of the loads still goes out, and the
+            // state of the pipeline (P and the V fragments of the last visible sub-tile) waits
+            // for the drain.  The products skipped are a few per cent of the kernel's, and under
+            // these kernels the chip's clock follows the energy spent.
+#pragma unroll
+            for (int n = 0; n < 8; ++n) dma_piece(ts, n);
+        } else {
+            stage(std::integral_constant<int, 0>{}, masked_tag, pre, j0, sa, sb, ts);
+            stage(std::integral_constant<int, 1>{}, masked_tag, pre, j0, sb, sa, ts);
+        }
         // fragment addresses follow the buffers: K to tile t+2's, V to tile t+1's
         const uint32_t dk = nnbuf == 0 ? static_cast<uint32_t>(-(FWD_NBUF - 1) * FWD_TILE_B) : static_cast<uint32_t>(FWD_TILE_B);
         const uint32_t dv = nbuf == 0 ? static_cast<uint32_t>(-(FWD_NBUF - 1) * FWD_TILE_B) : static_cast<uint32_t>(FWD_TILE_B);
