@@ -78,7 +78,8 @@ typedef struct {
 typedef struct {
     int32_t B;                  /* requests, >= 1 */
     int32_t Hq, Hkv, D, P;      /* as in cart_attn_desc */
-    int32_t total_own_tokens;   /* T = cu_lens[B] */
+    int32_t total_own_tokens;   /* T = cu_lens[B]; sizes the even split of the packed own rows (rows
+                                   past a smaller value would go unattended) */
     int32_t max_own_len;        /* upper bound on any request's own length (sizes the split) */
     cart_dtype dtype;
     float softmax_scale;        /* 0 selects 1/sqrt(D) */
@@ -109,7 +110,8 @@ typedef struct {
     int32_t n_shared;           /* 0..CART_MAX_SEGMENTS segments every request attends over */
     int32_t n_pool;             /* cartridges in the per-request pool, 0 = no pool */
     int32_t pool_p;             /* slots of each pooled cartridge (all the same size), >= 1 with a pool */
-    int32_t total_own_tokens;   /* T = cu_lens[B] */
+    int32_t total_own_tokens;   /* T = cu_lens[B]; sizes the even split of the packed own rows (rows
+                                   past a smaller value would go unattended) */
     int32_t max_own_len;        /* upper bound on any request's own length */
     cart_dtype dtype;           /* CART_BF16 with D = 128 and Hq/Hkv <= 32 (else CART_ERR_UNSUPPORTED) */
     float softmax_scale;        /* 0 selects 1/sqrt(D) */
@@ -130,7 +132,10 @@ typedef struct {
     int32_t dz_accumulate;  /* as in cart_attn_desc */
 } cart_attn_varlen_desc;
 
-/* Bytes of workspace each entry point needs for the given descriptor (0 on an invalid one). */
+/* Bytes of workspace each entry point needs for the given descriptor (0 on an invalid one).  The
+ * decode figures depend on the number of CUs of the current device as well (the own-KV part is cut
+ * into as many ranges as the chip keeps wavefronts resident): ask with the device current that the
+ * call will run on. */
 size_t cart_attn_fwd_workspace(const cart_attn_desc *desc);
 size_t cart_attn_bwd_workspace(const cart_attn_desc *desc);
 size_t cart_attn_varlen_fwd_workspace(const cart_attn_varlen_desc *desc);
