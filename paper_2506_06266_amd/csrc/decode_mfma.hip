@@ -37,7 +37,7 @@ constexpr int DEC_SUB = 32;            // own keys per wavefront step
 constexpr int DEC_SUB_B = DEC_SUB * ROW_B;
 
 #ifndef DEC_POOL_CHUNK
-#define DEC_POOL_CHUNK 256             // most keys per chunk of a private cartridge
+#define DEC_POOL_CHUNK 256             // fewest keys per chunk of a private cartridge
 #endif
 constexpr int DEC_MIN_SHARE = 256;      // fewest token rows per own-KV range (a multiple of DEC_SUB)
 constexpr int DEC_MAX_SEG = CART_MAX_SEGMENTS;
@@ -101,8 +101,6 @@ static DecodePlan make_plan(int B, int Hq, int Hkv, int max_own_len, int T, cons
         p.tab.blk0[k + 1] = p.tab.blk0[k] + Hkv * p.n_rb * p.tab.n_ps[k];
         p.tab.zk[k] = p.tab.zv[k] = nullptr;                        // filled by the launcher
     }
-    p.chunk = pool_p > 4096 ? 1024 : DEC_POOL_CHUNK;
-    p.n_cc = (pool_p + p.chunk - 1) / p.chunk;
     // Own KV: the workgroups that stay resident beside the prefix workgroups, four wavefronts
     // each, one wavefront per (range of token rows, KV head); the ranges cut T evenly, in whole
     // steps of 32 rows.
@@ -115,7 +113,20 @@ static DecodePlan make_plan(int B, int Hq, int Hkv, int max_own_len, int T, cons
     long share = ((static_cast<long>(T) + ranges - 1) / ranges + DEC_SUB - 1) / DEC_SUB * DEC_SUB;
     if (share < DEC_MIN_SHARE) share = DEC_MIN_SHARE;
     const long used = (static_cast<long>(T) + share - 1) / share;            // ranges that hold rows
-    if (p.n_cc == 0 && (used * Hkv + 3) / 4 < wgs) wgs = (used * Hkv + 3) / 4;
+    if (pool_p == 0 && (used * Hkv + 3) / 4 < wgs) wgs = (used * Hkv + 3) / 4;
+    // Private cartridges: chunks sized so that there is about one per wavefront (measured on 128
+    // requests x 2048 slots: chunks of 256 / 512 / 1024 / 2048 slots -> 0.268 / 0.259 / 0.254 /
+    // 0.248 ms: every chunk starts with a round trip nothing overlaps), not below DEC_POOL_CHUNK
+    p.chunk = DEC_POOL_CHUNK;
+    if (pool_p > 0) {
+        const long rows = static_cast<long>(B) * Hkv * pool_p;
+        long ck = ((rows + 4 * wgs - 1) / (4 * wgs) + DEC_SUB - 1) / DEC_SUB * DEC_SUB;
+        const long whole = (static_cast<long>(pool_p) + DEC_SUB - 1) / DEC_SUB * DEC_SUB;
+        if (ck < DEC_POOL_CHUNK) ck = DEC_POOL_CHUNK;
+        if (ck > whole) ck = whole;
+        p.chunk = static_cast<int>(ck);
+    }
+    p.n_cc = (pool_p + p.chunk - 1) / p.chunk;
     p.share = static_cast<int>(share);
     p.n_own_wg = static_cast<int>(wgs);
     p.n_oc = static_cast<int>((max_own_len + share - 1) / share) + 1;
