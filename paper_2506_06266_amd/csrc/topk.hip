@@ -260,25 +260,38 @@ __global__ __launch_bounds__(256) void topk_row_one_pass(const bf16_t* logits, i
 
     // per thread: a running maximum (raw, as in the resident kernel), the sum of
     // 2^(x log2e - reference) against a reference that moves only in whole steps, and the two
-    // best (order word: value, then lower index) among its logits above -inf
+    // best among its logits above -inf.  The two best are kept as 32-bit words, order key of the
+    // value in the upper half and 0xffff - (position among the thread's own elements) in the
+    // lower, so that "larger value first, then lower index" is an unsigned comparison and the
+    // update is three min / max instructions per element with no branch: a vector whose maximum
+    // exceeds the thread's second best is rare for a thread but not for a wavefront (some lane
+    // of 64 sees one in most iterations), so the update runs almost every time and has to be cheap.
+    constexpr uint32_t NONE = 0x007f0000u;           // the word of -inf at the last position: below every listed logit
     float tmax = __uint_as_float(0xff7f0000u), ref = -3.0e38f, sum = 0.f;
-    uint64_t t1w = 0, t2w = 0;                       // 0 = none yet
+    uint32_t t1 = NONE, t2 = NONE;
     float t2v = __uint_as_float(0xff800000u);        // value of the second best (-inf: none)
-    auto take = [&](int v, const u32x4 q) __attribute__((always_inline)) {
+    const float ninf = __uint_as_float(0xff800000u);
+    auto take = [&](int lbase /* 0xffff - first position of the vector */, const u32x4 q) __attribute__((always_inline)) {
         const uint32_t w[4] = {q.x, q.y, q.z, q.w};
         float vv = __uint_as_float(0xff800000u);     // maximum of this vector
 #pragma unroll
         for (int e = 0; e < 4; ++e) vv = max3_raw(vv, w[e] & 0xffff0000u, w[e] << 16);
-        if (vv > t2v) {                              // (rare after the first few vectors)
+        if (vv > t2v) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const uint32_t bits = (e & 1) ? (w[e >> 1] & 0xffff0000u) : (w[e >> 1] << 16);
-                if (__uint_as_float(bits) > t2v) {   // equal values: the earlier index stays
-                    const uint64_t ow = order_word(bf16_key(bits >> 16), 8u * v + e);
-                    if (ow > t1w) { t2w = t1w; t1w = ow; } else { t2w = ow; }
-                    t2v = t2w ? bf16_key_value(static_cast<uint32_t>(t2w >> 32)) : __uint_as_float(0xff800000u);
-                }
+                float x;     // -0 -> +0 (one value: ties go by index), NaN -> -inf (never listed)
+                asm("v_add_f32 %0, 0, %1\n\tv_max_f32 %0, %0, %2" : "=&v"(x) : "v"(bits), "v"(ninf));
+                const uint32_t u = __float_as_uint(x);
+                const uint32_t key = u ^ (static_cast<uint32_t>(static_cast<int32_t>(u) >> 31) | 0x80000000u);
+                const uint32_t wd = (key & 0xffff0000u) | static_cast<uint32_t>(lbase - e);
+                const uint32_t lo = t1 < wd ? t1 : wd;
+                t1 = t1 > wd ? t1 : wd;
+                t2 = t2 > lo ? t2 : lo;
             }
+            const uint32_t k = t2 & 0xffff0000u;
+            const uint32_t m = ~static_cast<uint32_t>(static_cast<int32_t>(k) >> 31) | 0x80000000u;
+            t2v = __uint_as_float((k ^ m) & 0xffff0000u);
         }
         const float vm = max3_raw(tmax, __float_as_uint(vv), __float_as_uint(vv));
         tmax = vm;
@@ -298,15 +311,21 @@ __global__ __launch_bounds__(256) void topk_row_one_pass(const bf16_t* logits, i
     // Four vectors per thread in flight instead of one: 3 % (1.15 -> 1.11 ms for 16384 rows of
     // 128256 logits).  At 3.8 TB/s of logits the kernel is bound by its arithmetic, one exponential
     // per logit, not by the loads.
-    int v = tid;
-    for (; v + 3 * THREADS < nvec; v += 4 * THREADS) {
+    int v = tid, lb = 0xffff;
+    for (; v + 3 * THREADS < nvec; v += 4 * THREADS, lb -= 32) {
         const u32x4 q0 = src[v], q1 = src[v + THREADS], q2 = src[v + 2 * THREADS], q3 = src[v + 3 * THREADS];
-        take(v, q0);
-        take(v + THREADS, q1);
-        take(v + 2 * THREADS, q2);
-        take(v + 3 * THREADS, q3);
+        take(lb, q0);
+        take(lb - 8, q1);
+        take(lb - 16, q2);
+        take(lb - 24, q3);
     }
-    for (; v < nvec; v += THREADS) take(v, src[v]);
+    for (; v < nvec; v += THREADS, lb -= 8) take(lb, src[v]);
+    // the thread's best two as (order key, token index): position p of its own elements is
+    // element p % 8 of its vector p / 8, i.e. token 8 (tid + THREADS (p / 8)) + p % 8
+    const uint32_t k1 = t1 >> 16, k2 = t2 >> 16;
+    const bool has1 = k1 > (NONE >> 16), has2 = k2 > (NONE >> 16);
+    const uint32_t p1 = 0xffffu - (t1 & 0xffffu);
+    const uint32_t idx1 = 8u * (static_cast<uint32_t>(tid) + THREADS * (p1 >> 3)) + (p1 & 7u);
     const uint32_t kmax = bf16_key(__float_as_uint(tmax) >> 16);
     all_kmax[tid] = static_cast<uint16_t>(kmax);
     const float wref = wave_max(ref);
@@ -341,8 +360,7 @@ __global__ __launch_bounds__(256) void topk_row_one_pass(const bf16_t* logits, i
     // logits leave the -inf ones out, so such a row takes the selection rounds below)
     const bool listed = tau > bf16_key(0xff80u);
     if (listed) {
-        const uint32_t k1 = static_cast<uint32_t>(t1w >> 32), k2 = static_cast<uint32_t>(t2w >> 32);
-        if (t2w != 0 && k2 >= tau) {
+        if (has2 && k2 >= tau) {
             // both of the thread's best reach tau: there may be more, read its vectors again
             const float tau_f = bf16_key_value(tau);
             for (int v = tid; v < nvec; v += THREADS) {
@@ -362,9 +380,9 @@ __global__ __launch_bounds__(256) void topk_row_one_pass(const bf16_t* logits, i
                     }
                 }
             }
-        } else if (t1w != 0 && k1 >= tau) {
+        } else if (has1 && k1 >= tau) {
             const int pos = atomicAdd(&list_n, 1);
-            if (pos < CAP) { list_key[pos] = k1; list_idx[pos] = 0xffffffffu - static_cast<uint32_t>(t1w); }
+            if (pos < CAP) { list_key[pos] = k1; list_idx[pos] = idx1; }
         }
     }
     __syncthreads();
