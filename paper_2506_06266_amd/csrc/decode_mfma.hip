@@ -4,13 +4,15 @@
 //
 // The cartridge is shared by every request, so its part is a real GEMM: the B*G query rows
 // that read one KV head (G = Hq/Hkv) are stacked and run against the prefix, split along the
-// prefix into about half as many workgroups as there are CUs (prefix role).  The ragged own-KV
-// part is bandwidth-bound: one wavefront per (request, KV head, chunk of keys) streams its chunk
-// through a private LDS slot with the G query rows padded into one 32-column MFMA block (own
-// role).  Both roles are workgroups of one launch (decode_fused_kernel), sized so that two share
-// a CU: the matrix-core work on the L2-resident cartridge overlaps the HBM streaming of the own
-// caches instead of preceding it.  Every split writes a normalised partial (O, lse);
-// decode_merge_kernel combines them by their log-sum-exps.
+// prefix into workgroups of 128 rows (prefix role).  The ragged own-KV part is bandwidth-bound:
+// the packed own caches are cut evenly along their token axis, whatever the requests' lengths,
+// and every resident wavefront streams one range of one KV head through a private LDS slot, with
+// the G query rows of the request it is passing padded into one 32-column MFMA block (own role).
+// Both roles are workgroups of one launch (decode_fused_kernel), sized so that two share a CU --
+// the matrix-core work on the L2-resident cartridge overlaps the HBM streaming of the own caches
+// instead of preceding it -- and the launch holds no more workgroups than the chip keeps
+// resident.  Every split writes a normalised partial (O, lse); decode_merge_kernel combines them
+// by their log-sum-exps.
 //
 // Composition (Sec. 5.4: cartridges trained apart are concatenated without retraining) and the
 // per-request cartridges of App. A.3's serving protocol use the same two kernels: the shared
